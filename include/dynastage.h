@@ -1,0 +1,297 @@
+/*
+ * dynastage — one pipeline stage's forward and backward pass over dynamically planned
+ * micro-batches, for AMD MI355X (gfx950).
+ *
+ * C ABI.  Plain pointers and sizes only.  Every pointer is tagged HOST or DEVICE below.
+ * Every call returns a ds_status and never throws or aborts across the boundary.
+ *
+ * Citations name passages of "DynaPipe: Optimizing Multi-task Training through Dynamic
+ * Pipelines" (EuroSys '24): section, equation, algorithm.
+ */
+#ifndef DYNASTAGE_H
+#define DYNASTAGE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DS_OK = 0,
+    DS_EINVAL = -1,       /* null pointer, non-positive length / size, unknown enum value, misaligned shape */
+    DS_EINFEASIBLE = -2,  /* no partition satisfies the memory cap (some sequence alone exceeds it) */
+    DS_ENOMEM = -3,       /* host or device allocation failed */
+    DS_EOVERFLOW = -4,    /* a cost or an objective does not fit in int64 */
+    DS_EHIP = -5,         /* a HIP runtime call failed (no device, launch error) */
+    DS_ELAYOUT = -6       /* layout does not fit the stage's workspace or does not match its model kind */
+} ds_status;
+
+/* ------------------------------------------------------------------------------------------
+ * Cost model t(b, L): predicted forward+backward time of a micro-batch of b sequences padded
+ * to length L (section "Overview", paragraph "Cost models").  Exact 64-bit integers.
+ *   DS_COST_POLY_GPT : fixed + b*L*(lin + L)
+ *   DS_COST_POLY_T5  : fixed + b*Lin*(lin + Lin) + b*Ltgt*(lin + Ltgt + Lin)
+ *   DS_COST_TABLE    : table[(b-1)*tl + (L-1)]  (HOST, row-major [tb][tl]; decoder-only;
+ *                      a slice with b > tb or L > tl makes dp_plan return DS_EINVAL)
+ * With fixed = 0, lin = 2048 the polynomial is t = b*L*(1 + L/2048) in units of 1/2048 token.
+ */
+enum { DS_COST_POLY_GPT = 0, DS_COST_POLY_T5 = 1, DS_COST_TABLE = 2 };
+
+typedef struct {
+    int32_t kind;
+    int64_t fixed;
+    int64_t lin;
+    const int64_t* table;   /* HOST; only for DS_COST_TABLE; borrowed for the duration of the call */
+    int32_t tb, tl;
+} ds_cost_model;
+
+/* ------------------------------------------------------------------------------------------
+ * Layout: the micro-batch partition of one global batch and the placement of every sequence
+ * in the padded token streams the stage works on.
+ *
+ * Stream layout (DEVICE tensors handed to stage_fwd_bwd): micro-batches one after another;
+ * micro-batch m is a row-major [mb_count[m], mb_lpad[m], d_model] block starting at row
+ * mb_row[m]; sequence at sorted position s occupies rows seq_row[s] .. seq_row[s]+seq_len[s]-1;
+ * all other rows are padding.  Encoder-decoder layouts have a second ("tgt") stream for the
+ * decoder, padded per micro-batch to mb_ltgt[m].
+ *
+ * All arrays in the view are HOST memory owned by the layout (valid until ds_layout_free).
+ */
+typedef struct ds_layout ds_layout;
+
+typedef struct {
+    int32_t n_seq, n_mb;
+    int32_t total_rows, total_rows_tgt;       /* padded rows of each stream (tgt: 0 if none) */
+    int64_t total_tokens, total_tokens_tgt;   /* non-pad tokens */
+    int64_t objective;                        /* (c-1)*max t + sum t of this partition (Eq1); 0 if no cost model was given */
+    int64_t t_max;                            /* max_m t(M_m) */
+    const int32_t* perm;                      /* [n_seq] sorted position -> original sample index */
+    const int32_t* mb_start;                  /* [n_mb] first sorted position of micro-batch m */
+    const int32_t* mb_count;                  /* [n_mb] sequences in micro-batch m */
+    const int32_t* mb_lpad;                   /* [n_mb] padded length (packed layouts: the row length) */
+    const int32_t* mb_ltgt;                   /* [n_mb] padded target length, or NULL */
+    const int32_t* mb_row;                    /* [n_mb] first stream row */
+    const int32_t* mb_nrows;                  /* [n_mb] stream rows the micro-batch occupies */
+    const int32_t* mb_row_tgt;                /* [n_mb] or NULL */
+    const int32_t* mb_nrows_tgt;              /* [n_mb] or NULL */
+    const int32_t* seq_row;                   /* [n_seq] */
+    const int32_t* seq_len;                   /* [n_seq] */
+    const int32_t* seq_row_tgt;               /* [n_seq] or NULL */
+    const int32_t* seq_len_tgt;               /* [n_seq] or NULL */
+} ds_layout_view;
+
+/*
+ * dp_plan — the paper's micro-batch construction (section "Micro-batch Construction").
+ *   1. order samples ascending by length (encoder-decoder: by input length, then target
+ *      length); equal keys keep their original order;
+ *   2. cut the ordered list into consecutive micro-batches minimising
+ *         (num_stages-1) * max_m t(M_m) + sum_m t(M_m)                     (Eq1)
+ *      with the recurrence over t_max of Eq2, every distinct single-micro-batch cost being a
+ *      candidate t_max (no sampling of t_max);
+ *   3. only micro-batches with  count * padded_length <= mem_cap_tokens  are admissible
+ *      (paragraph "Limit memory consumption"; encoder-decoder: input stream only).
+ * Ties: the smallest optimal t_max; among partitions of equal sum the one whose last
+ * micro-batch is longest, then whose second-last is longest, and so on.
+ *
+ * len, len_tgt: HOST int32[n]; len_tgt NULL for decoder-only (required for DS_COST_POLY_T5).
+ * *out: new layout owned by the caller (ds_layout_free).  Pure host code, re-entrant,
+ * thread-safe.  Errors: DS_EINVAL (null, n <= 0, a length <= 0, num_stages < 1, cap <= 0, bad
+ * cost model), DS_EINFEASIBLE, DS_EOVERFLOW, DS_ENOMEM.
+ */
+ds_status dp_plan(const int32_t* len, const int32_t* len_tgt, int32_t n,
+                  const ds_cost_model* cm, int64_t mem_cap_tokens, int32_t num_stages,
+                  ds_layout** out);
+
+/*
+ * ds_layout_from_cuts — layout for a given order and given cut points (the baselines the paper
+ * compares against, section "Background", naive padding; and single-sequence micro-batches).
+ * perm: HOST int32[n] permutation (NULL = identity); cuts: HOST int32[n_mb+1], cuts[0]=0,
+ * cuts[n_mb]=n, strictly increasing.  pad_to / pad_to_tgt: 0 = pad each micro-batch to its own
+ * longest sequence; otherwise every micro-batch is padded to that length (>= longest).
+ * cm may be NULL (objective, t_max reported as 0).
+ */
+ds_status ds_layout_from_cuts(const int32_t* len, const int32_t* len_tgt, int32_t n,
+                              const int32_t* perm, const int32_t* cuts, int32_t n_mb,
+                              int32_t pad_to, int32_t pad_to_tgt,
+                              const ds_cost_model* cm, int32_t num_stages, ds_layout** out);
+
+/*
+ * ds_layout_packed — the packing baseline (section "Background", "The current packing
+ * solution"): sequences, in their original order, are placed first-fit into rows of row_len
+ * tokens; rows_per_mb rows form one micro-batch; attention never crosses a sequence boundary.
+ * Decoder-only.  Errors: DS_EINVAL (a length > row_len, ...).
+ */
+ds_status ds_layout_packed(const int32_t* len, int32_t n, int32_t row_len, int32_t rows_per_mb,
+                           ds_layout** out);
+
+ds_status ds_layout_get(const ds_layout* layout, ds_layout_view* view);
+void ds_layout_free(ds_layout* layout);
+
+/* ------------------------------------------------------------------------------------------
+ * Stage: the transformer layers of one pipeline stage (what the ForwardPass / BackwardPass
+ * pipeline instructions execute, section "Overview", paragraph "Execution plans").
+ */
+enum { DS_MODEL_GPT = 0, DS_MODEL_T5 = 1 };
+enum { DS_DTYPE_F32 = 0, DS_DTYPE_BF16 = 1 };
+
+typedef struct {
+    int32_t model;          /* DS_MODEL_* */
+    int32_t dtype;          /* storage type of weights and activations; accumulation is always fp32 */
+    int32_t n_layers;       /* GPT: decoder layers.  T5: encoder layers */
+    int32_t n_dec_layers;   /* T5: decoder layers (0 for GPT) */
+    int32_t d_model, n_heads, d_ff;
+    int32_t max_rows;       /* workspace capacity: padded rows of the main stream */
+    int32_t max_rows_tgt;   /* ... of the target stream (0 for GPT) */
+    int32_t max_seqs;
+} ds_stage_config;
+
+/* Per-layer tensors, DEVICE pointers.  The same structs carry weights (element type = the
+ * stage dtype) and weight gradients (always float32).  Matrices are row-major
+ * [in_features, out_features]: y = x W (+ b).
+ *   GPT block (pre-LayerNorm, eps 1e-5):  x1 = x + Attn_causal(LN1(x)) Wo + bo;
+ *                                         x2 = x1 + GELU_tanh(LN2(x1) W1 + b1) W2 + b2.
+ *   T5 blocks (pre-RMSNorm, eps 1e-6, no biases, gated GELU):
+ *     encoder: x += Attn_bidir(RMS1(x)) Wo;  x += (GELU(u Wg) * (u Wu)) W2, u = RMS2(x).
+ *     decoder: causal self-attention, cross-attention (queries RMSc(x) Wcq, keys/values
+ *              enc_out Wckv), MLP.
+ *   Attention scale 1/sqrt(head_dim); heads are consecutive column groups of width head_dim. */
+typedef struct {
+    void *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o, *ln2_g, *ln2_b, *w_1, *b_1, *w_2, *b_2;
+} ds_gpt_layer;
+
+typedef struct {
+    void *ln1_g, *w_qkv, *w_o, *ln2_g, *w_g, *w_u, *w_2;
+} ds_t5_enc_layer;
+
+typedef struct {
+    void *ln1_g, *w_qkv, *w_o, *lnc_g, *w_cq, *w_ckv, *w_co, *ln2_g, *w_g, *w_u, *w_2;
+} ds_t5_dec_layer;
+
+/* Activations and gradients of one call, DEVICE pointers, element type = stage dtype, in
+ * stream layout ([total_rows, d_model] row-major).  Values at padding rows of the inputs are
+ * ignored (they may be NaN); padding rows of the outputs are written as zeros. */
+typedef struct {
+    const void* act_in;       /* GPT: stage input.  T5: encoder-side input                   */
+    const void* act_in_tgt;   /* T5: decoder-side input [total_rows_tgt, d]; NULL for GPT     */
+    const void* grad_out;     /* gradient w.r.t. act_out (same shape as act_out)              */
+    void* act_out;            /* GPT: [total_rows, d].  T5: decoder output [total_rows_tgt, d] */
+    void* grad_in;            /* gradient w.r.t. act_in                                       */
+    void* grad_in_tgt;        /* T5: gradient w.r.t. act_in_tgt; NULL for GPT                 */
+} ds_stage_io;
+
+typedef struct ds_stage ds_stage;
+
+/* Allocates the stage's device workspace once (saved activations of every layer for max_rows
+ * rows, backward temporaries, layout tables).  Uses the current HIP device.
+ * Errors: DS_EINVAL (d_model % n_heads, head_dim not in {64,128} for bf16 fast paths is NOT an
+ * error: generic kernels take over), DS_ENOMEM, DS_EHIP. */
+ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out);
+void ds_stage_destroy(ds_stage* stage);
+/* Bytes of device workspace the stage holds. */
+int64_t ds_stage_workspace_bytes(const ds_stage* stage);
+
+/*
+ * stage_fwd_bwd — run forward then backward of every layer of the stage over every
+ * micro-batch of the layout (ForwardPass and BackwardPass of all micro-batches; weight
+ * gradients summed over micro-batches, section "Background", pipeline-parallel paragraph).
+ *
+ * weights: HOST array of n_layers ds_gpt_layer (GPT), or n_layers ds_t5_enc_layer followed in
+ *          a second array (weights_dec) by n_dec_layers ds_t5_dec_layer (T5); the structs hold
+ *          DEVICE pointers.  grads / grads_dec: same shape, DEVICE float32 buffers.
+ * accumulate: 0 = overwrite the weight-gradient buffers, 1 = add to them.
+ * hip_stream: a hipStream_t (NULL = default stream).  The call enqueues work on that stream and
+ * returns; it allocates nothing.  The first call with a new layout uploads the layout's tables
+ * (a few KB) and may wait for the stream to drain; later calls with the same layout do not.
+ * Calls on the same stage must not overlap in time (they share the workspace).
+ * Errors: DS_EINVAL, DS_ELAYOUT (layout rows / sequences exceed the workspace, or stream kinds
+ * do not match the model), DS_EHIP.
+ */
+ds_status stage_fwd_bwd(ds_stage* stage, const ds_layout* layout,
+                        const void* weights, const void* weights_dec,
+                        const ds_stage_io* io,
+                        void* grads, void* grads_dec, int32_t accumulate,
+                        void* hip_stream);
+
+/* Rough count of the kernels one stage_fwd_bwd call launches (diagnostics). */
+int32_t ds_stage_last_launch_count(const ds_stage* stage);
+
+/*
+ * ds_pack / ds_unpack — move rows between the canonical form (sequences back to back in
+ * ORIGINAL sample order, [total_tokens, d] row-major, DEVICE) and a stream of the layout
+ * ("padded to the longest in the micro-batch", section "Background").  ds_pack zero-fills
+ * padding rows.  which: 0 = main stream, 1 = target stream.  dtype: DS_DTYPE_*.
+ */
+ds_status ds_pack(const ds_layout* layout, int32_t which, int32_t dtype, int32_t d,
+                  const void* canonical, void* stream_rows, void* hip_stream);
+ds_status ds_unpack(const ds_layout* layout, int32_t which, int32_t dtype, int32_t d,
+                    const void* stream_rows, void* canonical, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Building blocks, exported so that each kernel can be checked and profiled alone.  All
+ * pointers DEVICE unless said otherwise; dtype = element type of the non-float32 tensors.
+ */
+
+/* C[M,N] = op(A) op(B) (+ epilogue).  trans_a = 0: A is [M,K] row-major; 1: A is [K,M].
+ * trans_b = 0: B is [K,N]; 1: B is [N,K].  Accumulation in float32.
+ * epilogue (DS_EPI_*):
+ *   NONE     C = acc (+ bias[n])
+ *   GELU     C = acc + bias (pre-activation, stored), C2 = GELU_tanh(C)
+ *   RESID    C = acc + bias + R[m,n]; rows with row_valid[m] < 0 are written as 0
+ *   DGELU    C = acc * GELU_tanh'(R[m,n])
+ *   ACC32    C is float32 [M,N]; C = acc + (accumulate ? C : 0)
+ *   GATE     C = acc (stored), C2 = GELU_tanh(R[m,n]) * C            (gated MLP forward)
+ *   DGATE    C = acc * R2[m,n] * GELU_tanh'(R[m,n]), C2 = acc * GELU_tanh(R[m,n])   (its backward)
+ * N must be a multiple of 8.  force_generic != 0 selects the plain FMA kernel.
+ * bias may be NULL.  row_valid may be NULL (all rows valid). */
+enum { DS_EPI_NONE = 0, DS_EPI_GELU = 1, DS_EPI_RESID = 2, DS_EPI_DGELU = 3, DS_EPI_ACC32 = 4,
+       DS_EPI_GATE = 5, DS_EPI_DGATE = 6 };
+ds_status ds_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
+                  const void* A, const void* B, void* C, int32_t epilogue, const void* bias,
+                  const void* R, const void* R2, void* C2, const int32_t* row_valid, int32_t accumulate,
+                  int32_t force_generic, void* hip_stream);
+
+/* Variable-length attention over a packed QKV-style tensor.
+ * q, k, v: row-major with row strides ldq, ldk, ldv (elements); head h uses columns
+ * h*head_dim .. of each.  Query sequence s occupies rows q_row[s] .. +q_len[s]-1 of q/o, its
+ * keys rows k_row[s] .. +k_len[s]-1 of k/v.  mask: 0 = none (bidirectional / cross), 1 = causal.
+ * o: [rows, n_heads*head_dim] with row stride ldo; lse: float32 [n_heads, lse_stride].
+ * Rows not covered by any sequence are not touched.  q_row etc. are DEVICE int32 arrays. */
+ds_status ds_attention_fwd(int32_t dtype, int32_t n_seq, int32_t n_heads, int32_t head_dim, int32_t mask,
+                           const int32_t* q_row, const int32_t* q_len, const int32_t* k_row, const int32_t* k_len,
+                           int32_t max_q_len, int32_t max_k_len,
+                           const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v, int32_t ldv,
+                           void* o, int32_t ldo, float* lse, int32_t lse_stride,
+                           int32_t force_generic, void* hip_stream);
+/* Backward: given dO, O, LSE produce dQ, dK, dV (same strides as q, k, v).  delta: float32
+ * scratch [n_heads, lse_stride]. */
+ds_status ds_attention_bwd(int32_t dtype, int32_t n_seq, int32_t n_heads, int32_t head_dim, int32_t mask,
+                           const int32_t* q_row, const int32_t* q_len, const int32_t* k_row, const int32_t* k_len,
+                           int32_t max_q_len, int32_t max_k_len,
+                           const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v, int32_t ldv,
+                           const void* o, const void* d_o, int32_t ldo, const float* lse, float* delta, int32_t lse_stride,
+                           void* dq, void* dk, void* dv,
+                           int32_t force_generic, void* hip_stream);
+
+/* Row normalisation.  rms = 0: LayerNorm (gain g, bias b, eps 1e-5, stats = mean and rstd);
+ * rms = 1: RMSNorm (gain only, eps 1e-6, stats = rstd).  stats: float32 [2, rows]. */
+ds_status ds_norm_fwd(int32_t dtype, int32_t rms, int32_t rows, int32_t d, const void* x,
+                      const void* g, const void* b, void* y, float* stats, void* hip_stream);
+/* dx = (resid ? resid : 0) + norm_backward(dy); dg, db: float32 [d], overwritten or added to
+ * (accumulate).  partial: float32 scratch of at least ds_norm_bwd_scratch_floats(rows, d). */
+ds_status ds_norm_bwd(int32_t dtype, int32_t rms, int32_t rows, int32_t d, const void* dy, const void* x,
+                      const void* g, const float* stats, const void* resid, void* dx,
+                      float* dg, float* db, float* partial, int32_t accumulate, void* hip_stream);
+int64_t ds_norm_bwd_scratch_floats(int32_t rows, int32_t d);
+
+/* out[n] (float32) = sum_m x[m,n] (+ out[n] if accumulate).  partial as above (same size rule). */
+ds_status ds_colsum(int32_t dtype, int32_t rows, int32_t n, const void* x, float* out, float* partial,
+                    int32_t accumulate, void* hip_stream);
+
+/* Library identification: returns a static HOST string "dynastage <version> gfx950". */
+const char* ds_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNASTAGE_H */

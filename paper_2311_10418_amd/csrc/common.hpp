@@ -1,0 +1,93 @@
+// Shared device/host helpers for the HIP translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include "../../include/dynastage.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+#define DS_HIP_CHECK(expr)                         \
+    do {                                           \
+        hipError_t e__ = (expr);                   \
+        if (e__ != hipSuccess) return DS_EHIP;     \
+    } while (0)
+
+#define DS_LAUNCH_CHECK()                          \
+    do {                                           \
+        if (hipGetLastError() != hipSuccess) return DS_EHIP; \
+    } while (0)
+
+constexpr float kLnEps = 1e-5f;
+constexpr float kRmsEps = 1e-6f;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+template <class T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
+
+// 8 consecutive elements <-> 8 floats
+template <class T> struct Vec8;
+template <> struct Vec8<float> {
+    static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
+        const float4 a = *reinterpret_cast<const float4*>(p);
+        const float4 b = *reinterpret_cast<const float4*>(p + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+    static __device__ __forceinline__ void store(float* p, const float (&v)[8]) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+};
+template <> struct Vec8<bf16_t> {
+    static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
+        const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(p);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (float)a[i];
+    }
+    static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
+        bf16x8_t a;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] = (bf16_t)v[i];
+        *reinterpret_cast<bf16x8_t*>(p) = a;
+    }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+
+// tanh-form GELU and its derivative (fp32)
+__device__ __forceinline__ float gelu_f(float z) {
+    const float c = 0.7978845608028654f, a = 0.044715f;
+    const float u = c * (z + a * z * z * z);
+    return 0.5f * z * (1.0f + tanhf(u));
+}
+__device__ __forceinline__ float gelu_grad_f(float z) {
+    const float c = 0.7978845608028654f, a = 0.044715f;
+    const float u = c * (z + a * z * z * z);
+    const float t = tanhf(u);
+    const float du = c * (1.0f + 3.0f * a * z * z);
+    return 0.5f * (1.0f + t) + 0.5f * z * (1.0f - t * t) * du;
+}
+
+static inline size_t dtype_size(int32_t dtype) { return dtype == DS_DTYPE_BF16 ? 2 : 4; }
+
+// ---- launchers shared between translation units (all enqueue on `st`, return ds_status)
+ds_status launch_mask_rows(int32_t dtype, int32_t rows, int32_t d, const void* in, void* out,
+                           const int32_t* row_valid, hipStream_t st);
+ds_status launch_gather_rows(int32_t dtype, int32_t out_rows, int32_t d, const void* in, void* out,
+                             const int32_t* src_row, hipStream_t st);
+ds_status launch_scatter_rows(int32_t dtype, int32_t in_rows, int32_t d, const void* in, void* out,
+                              const int32_t* dst_row, hipStream_t st);

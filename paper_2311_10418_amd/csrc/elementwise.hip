@@ -1,0 +1,393 @@
+// HBM-bound kernels of the stage: row masking / gathering, LayerNorm and RMSNorm forward and
+// backward, column sums (bias gradients).  One 64-lane wavefront owns one row; row reductions
+// use wavefront shuffles; every global access is a 16-byte (bf16) or 32-byte (fp32) vector
+// per lane, consecutive lanes touching consecutive addresses.
+#include "common.hpp"
+
+namespace {
+
+constexpr int kPartialRows = 2048;   // upper bound on partial-sum rows written by column reductions
+
+// ------------------------------------------------------------------ row copy kernels
+template <class T>
+__global__ __launch_bounds__(256) void mask_rows_kernel(int rows, int d8, const T* __restrict__ in, T* __restrict__ out,
+                                                        const int32_t* __restrict__ row_valid) {
+    const long long total = (long long)rows * d8;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const int r = (int)(i / d8);
+        float v[8];
+        if (row_valid == nullptr || row_valid[r] >= 0) {
+            Vec8<T>::load(in + i * 8, v);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = 0.f;
+        }
+        Vec8<T>::store(out + i * 8, v);
+    }
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void gather_rows_kernel(int out_rows, int d8, const T* __restrict__ in, T* __restrict__ out,
+                                                          const int32_t* __restrict__ src_row) {
+    const long long total = (long long)out_rows * d8;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const int r = (int)(i / d8);
+        const int c = (int)(i - (long long)r * d8);
+        const int s = src_row[r];
+        float v[8];
+        if (s >= 0) {
+            Vec8<T>::load(in + ((long long)s * d8 + c) * 8, v);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = 0.f;
+        }
+        Vec8<T>::store(out + i * 8, v);
+    }
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void scatter_rows_kernel(int in_rows, int d8, const T* __restrict__ in, T* __restrict__ out,
+                                                           const int32_t* __restrict__ dst_row) {
+    const long long total = (long long)in_rows * d8;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const int r = (int)(i / d8);
+        const int c = (int)(i - (long long)r * d8);
+        const int t = dst_row[r];
+        if (t < 0) continue;
+        float v[8];
+        Vec8<T>::load(in + i * 8, v);
+        Vec8<T>::store(out + ((long long)t * d8 + c) * 8, v);
+    }
+}
+
+inline int grid_for(long long work_items, int block) {
+    long long g = (work_items + block - 1) / block;
+    if (g > 65536) g = 65536;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+// ------------------------------------------------------------------ norm forward
+// stats[0..rows) = mean (LayerNorm) or unused (RMS); stats[rows..2rows) = rstd.
+template <class T, bool RMS, int NI>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(int rows, int d, const T* __restrict__ x, const T* __restrict__ g,
+                                                       const T* __restrict__ b, T* __restrict__ y, float* __restrict__ stats) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= rows) return;
+    const T* xr = x + (size_t)row * d;
+    float v[NI][8];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int col = (lane + 64 * i) * 8;
+        if (col < d) {
+            Vec8<T>::load(xr + col, v[i]);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += v[i][j];
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[i][j] = 0.f;
+        }
+    }
+    const float inv_d = 1.0f / (float)d;
+    const float mean = RMS ? 0.f : wave_sum(s) * inv_d;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int col = (lane + 64 * i) * 8;
+        if (col < d) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float t = v[i][j] - mean;
+                q += t * t;
+            }
+        }
+    }
+    q = wave_sum(q) * inv_d;
+    const float rstd = 1.0f / sqrtf(q + (RMS ? kRmsEps : kLnEps));
+    T* yr = y + (size_t)row * d;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int col = (lane + 64 * i) * 8;
+        if (col < d) {
+            float gg[8], bb[8], o[8];
+            Vec8<T>::load(g + col, gg);
+            if (!RMS) Vec8<T>::load(b + col, bb);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float xh = (v[i][j] - mean) * rstd;
+                o[j] = RMS ? xh * gg[j] : xh * gg[j] + bb[j];
+            }
+            Vec8<T>::store(yr + col, o);
+        }
+    }
+    if (lane == 0) {
+        stats[row] = mean;
+        stats[rows + row] = rstd;
+    }
+}
+
+// ------------------------------------------------------------------ norm backward
+// dx = resid + rstd * (dy*g - mean(dy*g) - xhat * mean(dy*g*xhat))    (RMS: no mean(dy*g) term)
+// partial[w][0][:] = sum over the rows wave w handled of dy*xhat, partial[w][1][:] = sum of dy.
+template <class T, bool RMS, int NI>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(int rows, int d, const T* __restrict__ dy, const T* __restrict__ x,
+                                                       const T* __restrict__ g, const float* __restrict__ stats,
+                                                       const T* __restrict__ resid, T* __restrict__ dx,
+                                                       float* __restrict__ partial) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int gw = blockIdx.x * 4 + wave;
+    const int nw = gridDim.x * 4;
+    float gg[NI][8], dg[NI][8], db[NI][8];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int col = (lane + 64 * i) * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { dg[i][j] = 0.f; db[i][j] = 0.f; gg[i][j] = 0.f; }
+        if (col < d) Vec8<T>::load(g + col, gg[i]);
+    }
+    const float inv_d = 1.0f / (float)d;
+    for (int row = gw; row < rows; row += nw) {
+        const float mean = RMS ? 0.f : stats[row];
+        const float rstd = stats[rows + row];
+        const T* dyr = dy + (size_t)row * d;
+        const T* xr = x + (size_t)row * d;
+        float a[NI][8], xh[NI][8];
+        float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int col = (lane + 64 * i) * 8;
+            if (col < d) {
+                Vec8<T>::load(dyr + col, a[i]);
+                Vec8<T>::load(xr + col, xh[i]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    xh[i][j] = (xh[i][j] - mean) * rstd;
+                    dg[i][j] += a[i][j] * xh[i][j];
+                    db[i][j] += a[i][j];
+                    a[i][j] *= gg[i][j];
+                    c1 += a[i][j];
+                    c2 += a[i][j] * xh[i][j];
+                }
+            }
+        }
+        c1 = RMS ? 0.f : wave_sum(c1) * inv_d;
+        c2 = wave_sum(c2) * inv_d;
+        T* dxr = dx + (size_t)row * d;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int col = (lane + 64 * i) * 8;
+            if (col < d) {
+                float o[8];
+                if (resid) {
+                    Vec8<T>::load(resid + (size_t)row * d + col, o);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) o[j] = 0.f;
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) o[j] += rstd * (a[i][j] - c1 - xh[i][j] * c2);
+                Vec8<T>::store(dxr + col, o);
+            }
+        }
+    }
+    float* p0 = partial + (size_t)gw * 2 * d;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int col = (lane + 64 * i) * 8;
+        if (col < d) {
+            Vec8<float>::store(p0 + col, dg[i]);
+            if (!RMS) Vec8<float>::store(p0 + d + col, db[i]);
+        }
+    }
+}
+
+// out[c] = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c];  block = 32 columns x 8 row lanes
+__global__ __launch_bounds__(256) void reduce_partials_kernel(int n_partial, int n, size_t stride,
+                                                              const float* __restrict__ partial,
+                                                              float* __restrict__ out, int accumulate) {
+    __shared__ float red[8][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int col = blockIdx.x * 32 + tx;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (col < n) {
+        int p = ty;
+        for (; p + 24 < n_partial; p += 32) {
+            s0 += partial[(size_t)p * stride + col];
+            s1 += partial[(size_t)(p + 8) * stride + col];
+            s2 += partial[(size_t)(p + 16) * stride + col];
+            s3 += partial[(size_t)(p + 24) * stride + col];
+        }
+        for (; p < n_partial; p += 8) s0 += partial[(size_t)p * stride + col];
+    }
+    red[ty][tx] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (ty == 0 && col < n) {
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s += red[k][tx];
+        out[col] = accumulate ? out[col] + s : s;
+    }
+}
+
+// ------------------------------------------------------------------ column sums
+// block (64, 4): thread (tx, ty) owns 8 columns, rows blockIdx.y*4+ty, stepping gridDim.y*4.
+template <class T>
+__global__ __launch_bounds__(256) void colsum_kernel(int rows, int n, const T* __restrict__ x, float* __restrict__ partial) {
+    __shared__ float red[4][64][9];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int col = (blockIdx.x * 64 + tx) * 8;
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    if (col < n) {
+        for (int r = blockIdx.y * 4 + ty; r < rows; r += gridDim.y * 4) {
+            float v[8];
+            Vec8<T>::load(x + (size_t)r * n + col, v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += v[j];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[ty][tx][j] = acc[j];
+    __syncthreads();
+    if (ty == 0 && col < n) {
+        float o[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = red[0][tx][j] + red[1][tx][j] + red[2][tx][j] + red[3][tx][j];
+        Vec8<float>::store(partial + (size_t)blockIdx.y * n + col, o);
+    }
+}
+
+template <class T, bool RMS>
+ds_status norm_fwd_dispatch(int rows, int d, const T* x, const T* g, const T* b, T* y, float* stats, hipStream_t st) {
+    const int ni = (d + 511) / 512;
+    dim3 grid((rows + 3) / 4), block(256);
+    if (ni <= 1) hipLaunchKernelGGL((norm_fwd_kernel<T, RMS, 1>), grid, block, 0, st, rows, d, x, g, b, y, stats);
+    else if (ni <= 2) hipLaunchKernelGGL((norm_fwd_kernel<T, RMS, 2>), grid, block, 0, st, rows, d, x, g, b, y, stats);
+    else if (ni <= 4) hipLaunchKernelGGL((norm_fwd_kernel<T, RMS, 4>), grid, block, 0, st, rows, d, x, g, b, y, stats);
+    else hipLaunchKernelGGL((norm_fwd_kernel<T, RMS, 8>), grid, block, 0, st, rows, d, x, g, b, y, stats);
+    DS_LAUNCH_CHECK();
+    return DS_OK;
+}
+
+template <class T, bool RMS>
+ds_status norm_bwd_dispatch(int rows, int d, const T* dy, const T* x, const T* g, const float* stats, const T* resid,
+                            T* dx, float* dg, float* db, float* partial, int accumulate, hipStream_t st) {
+    const int ni = (d + 511) / 512;
+    int nblk = (rows + 3) / 4;
+    if (nblk > kPartialRows / 4) nblk = kPartialRows / 4;
+    dim3 grid(nblk), block(256);
+    if (ni <= 1) hipLaunchKernelGGL((norm_bwd_kernel<T, RMS, 1>), grid, block, 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
+    else if (ni <= 2) hipLaunchKernelGGL((norm_bwd_kernel<T, RMS, 2>), grid, block, 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
+    else if (ni <= 4) hipLaunchKernelGGL((norm_bwd_kernel<T, RMS, 4>), grid, block, 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
+    else hipLaunchKernelGGL((norm_bwd_kernel<T, RMS, 8>), grid, block, 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
+    DS_LAUNCH_CHECK();
+    const int np = nblk * 4;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32), dim3(256), 0, st, np, d, (size_t)2 * d, partial, dg, accumulate);
+    if (!RMS)
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32), dim3(256), 0, st, np, d, (size_t)2 * d, partial + d, db, accumulate);
+    DS_LAUNCH_CHECK();
+    return DS_OK;
+}
+
+}  // namespace
+
+ds_status launch_mask_rows(int32_t dtype, int32_t rows, int32_t d, const void* in, void* out,
+                           const int32_t* row_valid, hipStream_t st) {
+    if (rows <= 0) return DS_OK;
+    if (d % 8) return DS_EINVAL;
+    const long long items = (long long)rows * (d / 8);
+    if (dtype == DS_DTYPE_BF16)
+        hipLaunchKernelGGL(mask_rows_kernel<bf16_t>, dim3(grid_for(items, 256)), dim3(256), 0, st, rows, d / 8,
+                           (const bf16_t*)in, (bf16_t*)out, row_valid);
+    else
+        hipLaunchKernelGGL(mask_rows_kernel<float>, dim3(grid_for(items, 256)), dim3(256), 0, st, rows, d / 8,
+                           (const float*)in, (float*)out, row_valid);
+    DS_LAUNCH_CHECK();
+    return DS_OK;
+}
+
+ds_status launch_gather_rows(int32_t dtype, int32_t out_rows, int32_t d, const void* in, void* out,
+                             const int32_t* src_row, hipStream_t st) {
+    if (out_rows <= 0) return DS_OK;
+    if (d % 8) return DS_EINVAL;
+    const long long items = (long long)out_rows * (d / 8);
+    if (dtype == DS_DTYPE_BF16)
+        hipLaunchKernelGGL(gather_rows_kernel<bf16_t>, dim3(grid_for(items, 256)), dim3(256), 0, st, out_rows, d / 8,
+                           (const bf16_t*)in, (bf16_t*)out, src_row);
+    else
+        hipLaunchKernelGGL(gather_rows_kernel<float>, dim3(grid_for(items, 256)), dim3(256), 0, st, out_rows, d / 8,
+                           (const float*)in, (float*)out, src_row);
+    DS_LAUNCH_CHECK();
+    return DS_OK;
+}
+
+ds_status launch_scatter_rows(int32_t dtype, int32_t in_rows, int32_t d, const void* in, void* out,
+                              const int32_t* dst_row, hipStream_t st) {
+    if (in_rows <= 0) return DS_OK;
+    if (d % 8) return DS_EINVAL;
+    const long long items = (long long)in_rows * (d / 8);
+    if (dtype == DS_DTYPE_BF16)
+        hipLaunchKernelGGL(scatter_rows_kernel<bf16_t>, dim3(grid_for(items, 256)), dim3(256), 0, st, in_rows, d / 8,
+                           (const bf16_t*)in, (bf16_t*)out, dst_row);
+    else
+        hipLaunchKernelGGL(scatter_rows_kernel<float>, dim3(grid_for(items, 256)), dim3(256), 0, st, in_rows, d / 8,
+                           (const float*)in, (float*)out, dst_row);
+    DS_LAUNCH_CHECK();
+    return DS_OK;
+}
+
+extern "C" int64_t ds_norm_bwd_scratch_floats(int32_t rows, int32_t d) {
+    (void)rows;
+    return (int64_t)kPartialRows * 2 * (d > 0 ? d : 0);
+}
+
+extern "C" ds_status ds_norm_fwd(int32_t dtype, int32_t rms, int32_t rows, int32_t d, const void* x, const void* g,
+                                 const void* b, void* y, float* stats, void* hip_stream) {
+    if (rows < 0 || d <= 0 || d % 8 || d > 4096 || !x || !g || !y || !stats || (!rms && !b)) return DS_EINVAL;
+    if (dtype != DS_DTYPE_F32 && dtype != DS_DTYPE_BF16) return DS_EINVAL;
+    if (rows == 0) return DS_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (dtype == DS_DTYPE_BF16) {
+        if (rms) return norm_fwd_dispatch<bf16_t, true>(rows, d, (const bf16_t*)x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)y, stats, st);
+        return norm_fwd_dispatch<bf16_t, false>(rows, d, (const bf16_t*)x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)y, stats, st);
+    }
+    if (rms) return norm_fwd_dispatch<float, true>(rows, d, (const float*)x, (const float*)g, (const float*)b, (float*)y, stats, st);
+    return norm_fwd_dispatch<float, false>(rows, d, (const float*)x, (const float*)g, (const float*)b, (float*)y, stats, st);
+}
+
+extern "C" ds_status ds_norm_bwd(int32_t dtype, int32_t rms, int32_t rows, int32_t d, const void* dy, const void* x,
+                                 const void* g, const float* stats, const void* resid, void* dx, float* dg, float* db,
+                                 float* partial, int32_t accumulate, void* hip_stream) {
+    if (rows <= 0 || d <= 0 || d % 8 || d > 4096 || !dy || !x || !g || !stats || !dx || !dg || !partial || (!rms && !db))
+        return DS_EINVAL;
+    if (dtype != DS_DTYPE_F32 && dtype != DS_DTYPE_BF16) return DS_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (dtype == DS_DTYPE_BF16) {
+        if (rms) return norm_bwd_dispatch<bf16_t, true>(rows, d, (const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)g, stats, (const bf16_t*)resid, (bf16_t*)dx, dg, db, partial, accumulate, st);
+        return norm_bwd_dispatch<bf16_t, false>(rows, d, (const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)g, stats, (const bf16_t*)resid, (bf16_t*)dx, dg, db, partial, accumulate, st);
+    }
+    if (rms) return norm_bwd_dispatch<float, true>(rows, d, (const float*)dy, (const float*)x, (const float*)g, stats, (const float*)resid, (float*)dx, dg, db, partial, accumulate, st);
+    return norm_bwd_dispatch<float, false>(rows, d, (const float*)dy, (const float*)x, (const float*)g, stats, (const float*)resid, (float*)dx, dg, db, partial, accumulate, st);
+}
+
+extern "C" ds_status ds_colsum(int32_t dtype, int32_t rows, int32_t n, const void* x, float* out, float* partial,
+                               int32_t accumulate, void* hip_stream) {
+    if (rows <= 0 || n <= 0 || n % 8 || !x || !out || !partial) return DS_EINVAL;
+    if (dtype != DS_DTYPE_F32 && dtype != DS_DTYPE_BF16) return DS_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int gx = (n / 8 + 63) / 64;
+    int gy = (rows + 3) / 4;
+    const int cap = kPartialRows / gx > 0 ? kPartialRows / gx : 1;
+    if (gy > cap) gy = cap;
+    if (dtype == DS_DTYPE_BF16)
+        hipLaunchKernelGGL(colsum_kernel<bf16_t>, dim3(gx, gy), dim3(256), 0, st, rows, n, (const bf16_t*)x, partial);
+    else
+        hipLaunchKernelGGL(colsum_kernel<float>, dim3(gx, gy), dim3(256), 0, st, rows, n, (const float*)x, partial);
+    DS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((n + 31) / 32), dim3(256), 0, st, gy, n, (size_t)n, partial, out, accumulate);
+    DS_LAUNCH_CHECK();
+    return DS_OK;
+}

@@ -1,0 +1,477 @@
+// GEMMs of the stage: projections forward (NN), input gradients (NT) and weight gradients (TN,
+// the contraction running over every token of every micro-batch, which is the gradient
+// accumulation across micro-batches).
+//
+// Two kernels:
+//   * gemm_bf16_mfma_kernel — bf16 in, fp32 accumulate on the CDNA4 matrix cores
+//     (v_mfma_f32_32x32x16_bf16).  256x256x64 macro tile, 4 wavefronts of 64 lanes in a 2x2
+//     arrangement, each owning a 128x128 accumulator block (16 MFMA tiles, 256 accumulator
+//     registers per lane).  Operands are staged global -> registers -> LDS (double buffered,
+//     128 KB of the 160 KB LDS) in a [row][k] layout with a 16-byte XOR swizzle so that both
+//     the 16-byte LDS writes and the MFMA fragment reads are bank-conflict free.  Operands
+//     whose contraction index is not contiguous in memory are transposed in registers (8x8
+//     bf16 blocks, v_perm_b32) on their way to LDS, so one kernel body serves NN, NT and TN.
+//     The epilogue goes back through LDS so that global stores (and the residual / activation
+//     reads) are 16-byte per lane and row-contiguous.  Work-group ids are remapped so that each
+//     XCD (own L2) gets a contiguous run of tiles, ordered in groups of 8 tile-rows.
+//   * gemm_generic_kernel — any dtype / shape / stride, plain FMA; the fp32 path and the
+//     fallback for shapes the MFMA kernel does not take.
+#include "gemm.hpp"
+
+
+namespace {
+
+// ---------------------------------------------------------------------------- epilogues
+// Applied to 8 consecutive columns n..n+7 of row m; acc holds the fp32 accumulators.
+template <class T, int EPI>
+__device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], T* __restrict__ C, const GemmEpi& p) {
+    const size_t off = (size_t)m * N + n;
+    if (EPI == DS_EPI_ACC32) {
+        float* c = reinterpret_cast<float*>(C) + off;
+        if (p.accumulate) {
+            float old[8];
+            Vec8<float>::load(c, old);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += old[j];
+        }
+        Vec8<float>::store(c, acc);
+        return;
+    }
+    if (p.bias) {
+        float b[8];
+        Vec8<T>::load(reinterpret_cast<const T*>(p.bias) + n, b);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += b[j];
+    }
+    if (EPI == DS_EPI_NONE) {
+        Vec8<T>::store(C + off, acc);
+    } else if (EPI == DS_EPI_GELU) {
+        // round the pre-activation to storage precision first, so that forward and backward see the same z
+        float z[8], a[8];
+        Vec8<T>::store(C + off, acc);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { z[j] = to_f32(from_f32<T>(acc[j])); a[j] = gelu_f(z[j]); }
+        Vec8<T>::store(reinterpret_cast<T*>(p.C2) + off, a);
+    } else if (EPI == DS_EPI_RESID) {
+        if (p.row_valid && p.row_valid[m] < 0) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+        } else {
+            float r[8];
+            Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, r);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += r[j];
+        }
+        Vec8<T>::store(C + off, acc);
+    } else if (EPI == DS_EPI_DGELU) {
+        float z[8];
+        Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, z);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] *= gelu_grad_f(z[j]);
+        Vec8<T>::store(C + off, acc);
+    } else if (EPI == DS_EPI_GATE) {
+        // acc = u Wu (stored); C2 = GELU(R) * acc with R = u Wg
+        float zg[8], a[8];
+        Vec8<T>::store(C + off, acc);
+        Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, zg);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a[j] = gelu_f(zg[j]) * to_f32(from_f32<T>(acc[j]));
+        Vec8<T>::store(reinterpret_cast<T*>(p.C2) + off, a);
+    } else if (EPI == DS_EPI_DGATE) {
+        // acc = da; R = zg, R2 = zu; C = dzg = da * zu * GELU'(zg); C2 = dzu = da * GELU(zg)
+        float zg[8], zu[8], o1[8], o2[8];
+        Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, zg);
+        Vec8<T>::load(reinterpret_cast<const T*>(p.R2) + off, zu);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            o1[j] = acc[j] * zu[j] * gelu_grad_f(zg[j]);
+            o2[j] = acc[j] * gelu_f(zg[j]);
+        }
+        Vec8<T>::store(C + off, o1);
+        Vec8<T>::store(reinterpret_cast<T*>(p.C2) + off, o2);
+    }
+}
+
+// ---------------------------------------------------------------------------- generic kernel
+// 64x64 tile, 256 threads, 4x4 outputs per thread, K step 16.  A(m,k) = A[m*sam + k*sak].
+// Requires N % 8 == 0 (8-wide epilogue); M, K arbitrary.
+template <class T, int EPI>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(int M, int N, int K, const T* __restrict__ A, long long sam,
+                                                           long long sak, const T* __restrict__ B, long long sbk,
+                                                           long long sbn, T* __restrict__ C, GemmEpi p) {
+    __shared__ float As[16][68];
+    __shared__ float Bs[16][68];
+    const int t = threadIdx.x;
+    const int tx = t & 7, ty = t >> 3;            // tx: 8 column groups of 8, ty: 32 row pairs
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    float acc[2][8];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+    for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = t + 256 * i;
+            {
+                const int mm = sak == 1 ? idx >> 4 : idx & 63;
+                const int kk = sak == 1 ? idx & 15 : idx >> 6;
+                const int m = m0 + mm, k = k0 + kk;
+                As[kk][mm] = (m < M && k < K) ? to_f32(A[m * sam + k * sak]) : 0.f;
+            }
+            {
+                const int nn = sbk == 1 ? idx >> 4 : idx & 63;
+                const int kk = sbk == 1 ? idx & 15 : idx >> 6;
+                const int n = n0 + nn, k = k0 + kk;
+                Bs[kk][nn] = (n < N && k < K) ? to_f32(B[k * sbk + n * sbn]) : 0.f;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const float a0 = As[kk][ty * 2], a1 = As[kk][ty * 2 + 1];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float b = Bs[kk][tx * 8 + j];
+                acc[0][j] += a0 * b;
+                acc[1][j] += a1 * b;
+            }
+        }
+        __syncthreads();
+    }
+    const int n = n0 + tx * 8;
+    if (n < N) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int m = m0 + ty * 2 + i;
+            if (m < M) epilogue8<T, EPI>(m, n, N, acc[i], C, p);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------- MFMA kernel
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kTileBytes = BM * BK * 2;          // 32 KB per operand per buffer
+constexpr int kStageLd = 132;                    // fp32 row stride of the epilogue staging area
+
+// byte offset of the 16-byte chunk `chunk` (8 bf16 along k) of tile row `row`
+__device__ __forceinline__ int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+
+// Load one 256x64 operand tile into registers.
+//  TR = 0: memory is [row][k] (k contiguous, leading dimension ld): chunk c = t + 256*i -> row c/8, k-chunk c%8.
+//  TR = 1: memory is [k][row] (row contiguous): thread owns k-chunk t%8 and rows (t/8)*8..+7; register i holds
+//          8 consecutive rows at k = kc*8 + i.
+template <int TR>
+__device__ __forceinline__ void load_tile(uint4 (&r)[8], const bf16_t* __restrict__ base, long long ld, int row0,
+                                          int n_rows, int k0, int n_k, int t) {
+    if (TR == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = t + 256 * i;
+            int row = row0 + (c >> 3);
+            row = row < n_rows ? row : n_rows - 1;           // clamp: rows beyond the edge are never stored
+            const int k = k0 + ((c & 7) << 3);
+            r[i] = *reinterpret_cast<const uint4*>(base + (long long)row * ld + k);
+        }
+    } else {
+        const int kc = t & 7, rg = t >> 3;
+        const int row = row0 + rg * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int k = k0 + kc * 8 + i;
+            if (k < n_k)
+                r[i] = *reinterpret_cast<const uint4*>(base + (long long)k * ld + row);
+            else
+                r[i] = make_uint4(0u, 0u, 0u, 0u);            // contraction tail contributes zero
+        }
+    }
+}
+
+__device__ __forceinline__ uint32_t pick(const uint4& v, int w) {
+    return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w));
+}
+
+template <int TR>
+__device__ __forceinline__ void store_tile(const uint4 (&r)[8], char* __restrict__ lds, int t) {
+    if (TR == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = t + 256 * i;
+            *reinterpret_cast<uint4*>(lds + lds_off(c >> 3, c & 7)) = r[i];
+        }
+    } else {
+        const int kc = t & 7, rg = t >> 3;
+        // 8x8 transpose of 16-bit elements: out row i, k pair (2j, 2j+1) <- element i of r[2j], r[2j+1]
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint4 o;
+            const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+            o.x = __builtin_amdgcn_perm(pick(r[1], i >> 1), pick(r[0], i >> 1), sel);
+            o.y = __builtin_amdgcn_perm(pick(r[3], i >> 1), pick(r[2], i >> 1), sel);
+            o.z = __builtin_amdgcn_perm(pick(r[5], i >> 1), pick(r[4], i >> 1), sel);
+            o.w = __builtin_amdgcn_perm(pick(r[7], i >> 1), pick(r[6], i >> 1), sel);
+            *reinterpret_cast<uint4*>(lds + lds_off(rg * 8 + i, kc)) = o;
+        }
+    }
+}
+
+// A: TA = 0 -> [M][K] (lda = K stride); TA = 1 -> [K][M].  B: TB = 1 -> [N][K]; TB = 0 -> [K][N].
+// Requirements checked by the launcher: N % 256 == 0; (TA == 0: K % 64 == 0) ; (TA == 1: M % 256 == 0);
+// TB == 0 needs N % 8 == 0 (implied).  k range of this work-group: [k_begin, k_end) in units of BK tiles.
+template <int TA, int TB, int EPI>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_mfma_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
+                                                                const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
+                                                                long long lda, long long ldb, int tiles_m, int tiles_n,
+                                                                int splits, float* __restrict__ split_ws, GemmEpi p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // ---- work-group id -> (tile_m, tile_n, split): contiguous runs per XCD, groups of 8 tile rows
+    const int total = tiles_m * tiles_n * splits;
+    int logical;
+    {
+        const int pid = blockIdx.x;
+        const int xcd = pid & 7, local = pid >> 3;
+        const int per = total >> 3, rem = total & 7;
+        const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+        logical = start + local;
+    }
+    const int split = logical / (tiles_m * tiles_n);
+    logical -= split * (tiles_m * tiles_n);
+    int tile_m, tile_n;
+    {
+        const int group_sz = 8 * tiles_n;
+        const int group = logical / group_sz;
+        const int first_m = group * 8;
+        const int gs = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
+        const int in_group = logical - group * group_sz;
+        tile_m = first_m + in_group % gs;
+        tile_n = in_group / gs;
+    }
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int nk_total = (K + BK - 1) / BK;
+    const int per_split = (nk_total + splits - 1) / splits;
+    const int kt_begin = split * per_split;
+    const int kt_end = (kt_begin + per_split) < nk_total ? (kt_begin + per_split) : nk_total;
+
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // LDS map: buffer b holds A at b*2*kTileBytes and B right after it
+
+    if (kt_begin < kt_end) {
+        uint4 ra[8], rb[8];
+        load_tile<TA>(ra, A, lda, m0, M, kt_begin * BK, K, t);
+        load_tile<(TB == 0)>(rb, B, ldb, n0, N, kt_begin * BK, K, t);
+        store_tile<TA>(ra, smem, t);
+        store_tile<(TB == 0)>(rb, smem + kTileBytes, t);
+        __syncthreads();
+
+        const int frag_row = lane & 31, frag_half = lane >> 5;
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            const int buf = (kt - kt_begin) & 1;
+            const bool more = kt + 1 < kt_end;
+            if (more) {
+                load_tile<TA>(ra, A, lda, m0, M, (kt + 1) * BK, K, t);
+                load_tile<(TB == 0)>(rb, B, ldb, n0, N, (kt + 1) * BK, K, t);
+            }
+            const char* a_base = smem + buf * (2 * kTileBytes);
+            const char* b_base = a_base + kTileBytes;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                bf16x8_t af[4], bfr[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int ar = wm * 128 + i * 32 + frag_row;
+                    af[i] = *reinterpret_cast<const bf16x8_t*>(a_base + lds_off(ar, ks * 2 + frag_half));
+                    const int br = wn * 128 + i * 32 + frag_row;
+                    bfr[i] = *reinterpret_cast<const bf16x8_t*>(b_base + lds_off(br, ks * 2 + frag_half));
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            }
+            if (more) {
+                char* nxt = smem + (buf ^ 1) * (2 * kTileBytes);
+                store_tile<TA>(ra, nxt, t);
+                store_tile<(TB == 0)>(rb, nxt + kTileBytes, t);
+            }
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue through LDS: per wave a [32][kStageLd] fp32 staging block
+    float* stage = reinterpret_cast<float*>(smem) + wave * (32 * kStageLd);
+    const int col_l = lane & 31, half = lane >> 5;
+    const int rd_row = lane >> 4, rd_col = (lane & 15) * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = 8 * (e >> 2) + 4 * half + (e & 3);
+                stage[row * kStageLd + j * 32 + col_l] = acc[i][j][e];
+            }
+        __syncthreads();
+#pragma unroll
+        for (int pss = 0; pss < 8; ++pss) {
+            const int row = pss * 4 + rd_row;
+            const int m = m0 + wm * 128 + i * 32 + row;
+            const int n = n0 + wn * 128 + rd_col;
+            if (m < M) {
+                float v[8];
+                const float4 x0 = *reinterpret_cast<const float4*>(stage + row * kStageLd + rd_col);
+                const float4 x1 = *reinterpret_cast<const float4*>(stage + row * kStageLd + rd_col + 4);
+                v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+                if (splits > 1) {
+                    Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
+                } else {
+                    epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
+                }
+            }
+        }
+    }
+}
+
+// sum the split-K partials and apply the epilogue; one thread per 8 columns
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(int M, int N, int splits, const float* __restrict__ ws,
+                                                            bf16_t* __restrict__ C, GemmEpi p) {
+    const long long total = (long long)M * (N / 8);
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const int m = (int)(i / (N / 8));
+        const int n = (int)(i - (long long)m * (N / 8)) * 8;
+        float v[8];
+        Vec8<float>::load(ws + (size_t)m * N + n, v);
+        for (int s = 1; s < splits; ++s) {
+            float w[8];
+            Vec8<float>::load(ws + ((size_t)s * M + m) * N + n, w);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] += w[j];
+        }
+        epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
+    }
+}
+
+template <class T, int EPI>
+ds_status launch_generic(int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C, const GemmEpi& p,
+                         hipStream_t st) {
+    const long long sam = ta ? 1 : K, sak = ta ? M : 1;
+    const long long sbk = tb ? 1 : N, sbn = tb ? K : 1;
+    dim3 grid((N + 63) / 64, (M + 63) / 64);
+    hipLaunchKernelGGL((gemm_generic_kernel<T, EPI>), grid, dim3(256), 0, st, M, N, K, (const T*)A, sam, sak, (const T*)B,
+                       sbk, sbn, (T*)C, p);
+    DS_LAUNCH_CHECK();
+    return DS_OK;
+}
+
+template <int TA, int TB, int EPI>
+ds_status launch_mfma(int M, int N, int K, const void* A, const void* B, void* C, const GemmEpi& p, float* split_ws,
+                      size_t split_ws_floats, hipStream_t st) {
+    static bool attr_set = false;
+    auto kern = gemm_bf16_mfma_kernel<TA, TB, EPI>;
+    const int smem = 4 * kTileBytes;
+    if (!attr_set) {
+        DS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        attr_set = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    const int nk = (K + BK - 1) / BK;
+    int splits = 1;
+    if (EPI == DS_EPI_ACC32 && split_ws) {
+        const int tiles = tiles_m * tiles_n;
+        if (tiles < 384) {
+            splits = (512 + tiles - 1) / tiles;
+            if (splits > 16) splits = 16;
+            if (splits > nk / 8) splits = nk / 8 > 0 ? nk / 8 : 1;
+            while (splits > 1 && (size_t)splits * M * N > split_ws_floats) --splits;
+            // every split must own at least one K tile
+            const int per = (nk + splits - 1) / splits;
+            splits = (nk + per - 1) / per;
+        }
+    }
+    const long long lda = TA ? M : K;
+    const long long ldb = TB ? K : N;
+    const int total = tiles_m * tiles_n * splits;
+    hipLaunchKernelGGL(kern, dim3(total), dim3(256), smem, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C, lda,
+                       ldb, tiles_m, tiles_n, splits, split_ws, p);
+    DS_LAUNCH_CHECK();
+    if (splits > 1) {
+        long long items = (long long)M * (N / 8);
+        long long g = (items + 255) / 256;
+        if (g > 8192) g = 8192;
+        hipLaunchKernelGGL(splitk_finish_kernel<EPI>, dim3((int)g), dim3(256), 0, st, M, N, splits, split_ws, (bf16_t*)C, p);
+        DS_LAUNCH_CHECK();
+    }
+    return DS_OK;
+}
+
+template <int EPI>
+ds_status dispatch_epi(int dtype, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C,
+                       const GemmEpi& p, bool force_generic, float* split_ws, size_t split_ws_floats, hipStream_t st) {
+    if (dtype == DS_DTYPE_BF16 && !force_generic) {
+        const bool ok_n = N % BN == 0;
+        const bool ok_a = ta ? (M % BM == 0) : (K % BK == 0);
+        const bool ok_b = tb ? (K % BK == 0) : true;
+        const bool aligned = ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && ((uintptr_t)C % 16 == 0);
+        if (ok_n && ok_a && ok_b && aligned && M >= 1 && K >= 1) {
+            if (!ta && !tb) return launch_mfma<0, 0, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
+            if (!ta && tb) return launch_mfma<0, 1, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
+            if (ta && !tb) return launch_mfma<1, 0, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
+        }
+    }
+    if (dtype == DS_DTYPE_BF16) return launch_generic<bf16_t, EPI>(ta, tb, M, N, K, A, B, C, p, st);
+    return launch_generic<float, EPI>(ta, tb, M, N, K, A, B, C, p, st);
+}
+
+}  // namespace
+
+// Shared with the stage driver.
+ds_status launch_gemm(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int32_t N, int32_t K, const void* A, const void* B,
+                      void* C, int32_t epilogue, const GemmEpi& p, bool force_generic, float* split_ws,
+                      size_t split_ws_floats, hipStream_t st) {
+    if (M <= 0 || N <= 0 || K <= 0 || !A || !B || !C) return DS_EINVAL;
+    if (N % 8) return DS_EINVAL;
+    if (dtype != DS_DTYPE_F32 && dtype != DS_DTYPE_BF16) return DS_EINVAL;
+    switch (epilogue) {
+    case DS_EPI_NONE: return dispatch_epi<DS_EPI_NONE>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
+    case DS_EPI_GELU:
+        if (!p.C2) return DS_EINVAL;
+        return dispatch_epi<DS_EPI_GELU>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
+    case DS_EPI_RESID:
+        if (!p.R) return DS_EINVAL;
+        return dispatch_epi<DS_EPI_RESID>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
+    case DS_EPI_DGELU:
+        if (!p.R) return DS_EINVAL;
+        return dispatch_epi<DS_EPI_DGELU>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
+    case DS_EPI_ACC32: return dispatch_epi<DS_EPI_ACC32>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
+    case DS_EPI_GATE:
+        if (!p.R || !p.C2) return DS_EINVAL;
+        return dispatch_epi<DS_EPI_GATE>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
+    case DS_EPI_DGATE:
+        if (!p.R || !p.R2 || !p.C2) return DS_EINVAL;
+        return dispatch_epi<DS_EPI_DGATE>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
+    }
+    return DS_EINVAL;
+}
+
+extern "C" ds_status ds_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
+                             const void* A, const void* B, void* C, int32_t epilogue, const void* bias, const void* R,
+                             const void* R2, void* C2, const int32_t* row_valid, int32_t accumulate,
+                             int32_t force_generic, void* hip_stream) {
+    GemmEpi p{bias, R, R2, C2, row_valid, accumulate};
+    return launch_gemm(dtype, trans_a, trans_b, M, N, K, A, B, C, epilogue, p, force_generic != 0, nullptr, 0,
+                       (hipStream_t)hip_stream);
+}

@@ -1,0 +1,40 @@
+"""The C-ABI library loads without a GPU and exports every function include/dynastage.h declares."""
+import ctypes
+import os
+import re
+
+from paper_2311_10418_amd import binding as ds
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "dynastage.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:ds_status|void|int32_t|int64_t|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = ctypes.CDLL(ds.LIB_PATH)
+    declared = _declared_functions()
+    assert "dp_plan" in declared and "stage_fwd_bwd" in declared and len(declared) >= 18
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(ds.EXPORTS) == declared
+
+
+def test_version_string():
+    assert ds.ds_version().startswith("dynastage") and "gfx950" in ds.ds_version()
+
+
+def test_argument_checks_without_a_gpu():
+    lib = ds.lib()
+    assert lib.ds_stage_create(None, None) == ds.DS_EINVAL
+    assert lib.ds_layout_get(None, None) == ds.DS_EINVAL
+    assert lib.stage_fwd_bwd(None, None, None, None, None, None, None, 0, None) == ds.DS_EINVAL
+    assert lib.ds_gemm(1, 0, 0, 0, 8, 8, None, None, None, 0, None, None, None, None, None, 0, 0, None) == ds.DS_EINVAL
+    assert lib.ds_norm_fwd(1, 0, 4, 7, None, None, None, None, None, None) == ds.DS_EINVAL
+    cfg = ds.ds_stage_config(ds.DS_MODEL_GPT, ds.DS_DTYPE_BF16, 1, 0, 100, 3, 64, 16, 0, 4)   # 100 % 3 != 0
+    h = ctypes.c_void_p()
+    assert lib.ds_stage_create(ctypes.byref(cfg), ctypes.byref(h)) == ds.DS_EINVAL
