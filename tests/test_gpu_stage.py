@@ -1,0 +1,108 @@
+"""GPU parity of stage_fwd_bwd against the per-sequence float64 oracle, through the C ABI.
+
+Bar: normwise relative error per tensor (each output, each input gradient, each weight gradient)
+<= 1e-4 for fp32 and <= 2e-2 for bf16 storage; padding rows of the outputs exactly zero; results
+independent of the micro-batch layout (DP plan, padded DP plan, fixed padding, packing,
+single-sequence micro-batches), with NaN planted in every padding row of the inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stage as ost
+from paper_2311_10418_amd import binding as ds
+from paper_2311_10418_amd import workload as wl
+from helpers import cat, rel_err, run_gpt_stage
+
+pytestmark = pytest.mark.gpu
+
+TOL = {ds.DS_DTYPE_F32: 1e-4, ds.DS_DTYPE_BF16: 2e-2}
+
+
+def _small_case(bf16, n_seq=None, seed=0):
+    cfg = dict(wl.CONFIGS["gpt_small_fp32"])
+    lens, _ = wl.draw_lengths(cfg["lengths"], seed=seed)
+    if n_seq:
+        lens = lens[:n_seq]
+    params = wl.draw_params(wl.GPT_KEYS, cfg["n_layers"], cfg["d_model"], cfg["d_ff"], seed=seed, bf16=bf16)
+    xs = wl.draw_embedded_tokens(lens, cfg["d_model"], seed=seed, bf16=bf16)
+    dys = wl.draw_rows(lens, cfg["d_model"], seed=seed, tag=5, bf16=bf16)
+    return cfg, lens, params, xs, dys
+
+
+_ORACLE_CACHE = {}
+
+
+def _oracle(key, xs, dys, params, h):
+    if key not in _ORACLE_CACHE:
+        _ORACLE_CACHE[key] = ost.gpt_stage_fwd_bwd(xs, dys, params, h)
+    return _ORACLE_CACHE[key]
+
+
+def _compare(tag, got, ref, tol):
+    outs, dxs, grads, pad_o, pad_dx = got
+    r_outs, r_dxs, r_grads = ref
+    errs = {"act_out": rel_err(cat(outs), cat(r_outs)), "grad_in": rel_err(cat(dxs), cat(r_dxs))}
+    for li, layer in enumerate(r_grads):
+        for k, v in layer.items():
+            errs["L%d.%s" % (li, k)] = rel_err(grads[li][k], v)
+    worst = max(errs, key=errs.get)
+    print(tag, "worst", worst, "%.3e" % errs[worst])
+    for k, e in errs.items():
+        assert e <= tol, (tag, k, e)
+    assert pad_o.size == 0 or np.all(pad_o == 0), tag
+    assert pad_dx.size == 0 or np.all(pad_dx == 0), tag
+    return errs
+
+
+def _layouts(lens, cap, c):
+    n = len(lens)
+    yield "dp", ds.dp_plan(lens, ds.make_cost_model(), cap, c)
+    yield "dp_overhead", ds.dp_plan(lens, ds.make_cost_model(fixed=2_000_000), cap, c)
+    yield "fixed_pad", ds.ds_layout_from_cuts(lens, list(range(0, n, 8)) + [n], pad_to=int(max(lens)))
+    yield "packed", ds.ds_layout_packed(lens, int(max(lens)), 4)
+    yield "singletons", ds.ds_layout_from_cuts(lens, list(range(n + 1)))
+
+
+@pytest.mark.parametrize("dtype_code", [ds.DS_DTYPE_F32, ds.DS_DTYPE_BF16])
+def test_small_gpt_stage_matches_oracle_on_every_layout(dtype_code):
+    bf16 = dtype_code == ds.DS_DTYPE_BF16
+    cfg, lens, params, xs, dys = _small_case(bf16)
+    ref = _oracle(("small", bf16), xs, dys, params, cfg["n_heads"])
+    for name, lo in _layouts(lens, cfg["cap"], cfg["num_stages"]):
+        got = run_gpt_stage(lo, cfg, params, xs, dys, dtype_code)
+        _compare("%s/%s rows=%d tokens=%d" % ("bf16" if bf16 else "f32", name, lo.total_rows, lo.total_tokens),
+                 got, ref, TOL[dtype_code])
+
+
+def test_weight_gradients_accumulate_across_calls():
+    cfg, lens, params, xs, dys = _small_case(True, n_seq=12)
+    ref = _oracle(("small12", True), xs, dys, params, cfg["n_heads"])
+    lo = ds.dp_plan(lens, ds.make_cost_model(fixed=2_000_000), cfg["cap"], cfg["num_stages"])
+    stage = ds.Stage(ds.DS_MODEL_GPT, ds.DS_DTYPE_BF16, cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["d_ff"],
+                     max_rows=lo.total_rows + 100, max_seqs=64)
+    from helpers import params_to_dev, zero_grads_like
+    grads = zero_grads_like(params_to_dev(params, torch.bfloat16))
+    for g in grads:
+        for v in g.values():
+            v.fill_(123.0)                       # overwritten by the first (non-accumulating) call
+    run_gpt_stage(lo, cfg, params, xs, dys, ds.DS_DTYPE_BF16, stage=stage, grads=grads, accumulate=False)
+    got = run_gpt_stage(lo, cfg, params, xs, dys, ds.DS_DTYPE_BF16, stage=stage, grads=grads, accumulate=True)
+    for li, layer in enumerate(ref[2]):
+        for k, v in layer.items():
+            assert rel_err(got[2][li][k], 2 * v) <= 2e-2, (li, k)
+    # same stage object, another layout right after: tables are re-bound
+    lo2 = ds.ds_layout_from_cuts(lens, list(range(len(lens) + 1)))
+    got2 = run_gpt_stage(lo2, cfg, params, xs, dys, ds.DS_DTYPE_BF16, stage=stage)
+    _compare("rebind", got2, ref, 2e-2)
+    stage.close()
+
+
+def test_layout_too_large_for_workspace_is_rejected():
+    cfg, lens, params, xs, dys = _small_case(True, n_seq=6)
+    lo = ds.ds_layout_from_cuts(lens, list(range(len(lens) + 1)))
+    stage = ds.Stage(ds.DS_MODEL_GPT, ds.DS_DTYPE_BF16, 1, cfg["d_model"], cfg["n_heads"], cfg["d_ff"],
+                     max_rows=lo.total_rows - 1, max_seqs=64)
+    with pytest.raises(ds.DsError) as e:
+        run_gpt_stage(lo, dict(cfg, n_layers=1), params[:1], xs, dys, ds.DS_DTYPE_BF16, stage=stage)
+    assert e.value.code == ds.DS_ELAYOUT
+    stage.close()
