@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark: non-pad tokens/s of one stage's forward+backward over a DP-planned global batch.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME] [--layout dp|fixed|packed]
+
+One step = one stage_fwd_bwd call over the whole seeded synthetic global batch (every micro-batch
+of the layout, forward and backward of every layer, weight gradients overwritten), inputs and
+weights already resident in HBM.  Prints ONE JSON line on stdout; everything else goes to stderr.
+The roofline figure is for the dominant kernel family (the bf16 MFMA GEMM), timed with HIP events
+the library records on the launch stream inside the timed region.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_flops(cfg, lens):
+    """Forward+backward flops the method must execute on non-pad tokens (causal half only)."""
+    d, F, L = cfg["d_model"], cfg["d_ff"], cfg["n_layers"]
+    tokens = int(lens.sum())
+    linear = 3 * 2 * (4 * d * d + 2 * d * F) * tokens * L
+    attn = 3 * sum(2 * d * int(l) * (int(l) + 1) for l in lens) * L
+    return linear, attn
+
+
+def build_layout(ds, kind, lens, cfg):
+    if kind == "dp":
+        return ds.dp_plan(lens, ds.make_cost_model(), cfg["cap"], cfg["num_stages"]), \
+            "dp_plan c=%d cap=%d t=b*L*(1+L/2048)" % (cfg["num_stages"], cfg["cap"])
+    hi = cfg["lengths"]["hi"]
+    n = len(lens)
+    if kind == "fixed":
+        return ds.ds_layout_from_cuts(lens, list(range(0, n, 8)) + [n], pad_to=hi), "fixed padding to %d, 8 per micro-batch" % hi
+    if kind == "packed":
+        return ds.ds_layout_packed(lens, hi, 8), "first-fit packing into %d-token rows, 8 rows per micro-batch" % hi
+    raise SystemExit("unknown layout " + kind)
+
+
+def cpu_baseline(cfg, lens, seed, budget_s=15.0):
+    """The oracle, as it stands, on a bounded seeded sample of the same workload."""
+    from oracle import stage as ost
+    from paper_2311_10418_amd import workload as wl
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    d, F, L = cfg["d_model"], cfg["d_ff"], cfg["n_layers"]
+    n = 1024
+    a = np.random.default_rng(0).standard_normal((n, n))
+    t0 = time.perf_counter()
+    a @ a
+    rate = 2 * n ** 3 / (time.perf_counter() - t0)                      # fp64 flop/s of the host BLAS
+    per_token = 3 * 2 * (4 * d * d + 2 * d * F) * L
+    budget_tokens = int(min(max(budget_s * rate / per_token, 64), 8192))
+    order = np.random.default_rng([seed, 9]).permutation(len(lens))
+    pick, tok = [], 0
+    for i in order:
+        if tok + int(lens[i]) > budget_tokens and pick:
+            continue
+        pick.append(int(i))
+        tok += int(lens[i])
+        if tok >= budget_tokens:
+            break
+    params = wl.draw_params(wl.GPT_KEYS, L, d, F, seed=seed, bf16=True)
+    params = [{k: v.astype(np.float64) for k, v in layer.items()} for layer in params]
+    sub = lens[pick]
+    xs = wl.draw_rows(sub, d, seed=seed, tag=3, bf16=True)
+    dys = wl.draw_rows(sub, d, seed=seed, tag=5, bf16=True)
+    t0 = time.perf_counter()
+    ost.gpt_stage_fwd_bwd(xs, dys, params, cfg["n_heads"])
+    dt = time.perf_counter() - t0
+    return {"value": tok / dt, "unit": "non-pad tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d seeded sequences of the batch, %d tokens, float64 numpy, %.1f s" % (len(pick), tok, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="gpt_2048_bf16")
+    ap.add_argument("--layout", default="dp", choices=["dp", "fixed", "packed"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus)
+        sys.exit(2)
+
+    import torch
+    from paper_2311_10418_amd import binding as ds
+    from paper_2311_10418_amd import workload as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    cfg = wl.CONFIGS[args.config]
+    if cfg["kind"] != "gpt":
+        raise SystemExit("bench.py times the decoder-only stage")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    lens, _ = wl.draw_lengths(cfg["lengths"], seed=args.seed)
+    t0 = time.perf_counter()
+    layout, layout_desc = build_layout(ds, args.layout, lens, cfg)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    d, F, L, H = cfg["d_model"], cfg["d_ff"], cfg["n_layers"], cfg["n_heads"]
+    bf16 = cfg["dtype"] == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    code = ds.DS_DTYPE_BF16 if bf16 else ds.DS_DTYPE_F32
+    R = layout.total_rows
+    log("workload %s: %d sequences, %d non-pad tokens, %d rows in %d micro-batches (%s), plan %.2f ms"
+        % (args.config, len(lens), layout.total_tokens, R, layout.n_mb, layout_desc, plan_ms))
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    shapes = {"ln1_g": (d,), "ln1_b": (d,), "w_qkv": (d, 3 * d), "b_qkv": (3 * d,), "w_o": (d, d), "b_o": (d,),
+              "ln2_g": (d,), "ln2_b": (d,), "w_1": (d, F), "b_1": (F,), "w_2": (F, d), "b_2": (d,)}
+    weights, grads = [], []
+    for _ in range(L):
+        w, g = {}, {}
+        for k in ds.GPT_KEYS:
+            v = torch.randn(shapes[k], generator=gen, device=dev, dtype=torch.float32) * 0.02
+            if k.endswith("_g"):
+                v = v + 1.0
+            w[k] = v.to(tdt).contiguous()
+            g[k] = torch.zeros(shapes[k], device=dev, dtype=torch.float32)
+        weights.append(w)
+        grads.append(g)
+    x = torch.randn((R, d), generator=gen, device=dev, dtype=torch.float32).to(tdt)
+    dy = torch.randn((R, d), generator=gen, device=dev, dtype=torch.float32).to(tdt)
+    out = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    stage = ds.Stage(ds.DS_MODEL_GPT, code, L, d, H, F, max_rows=R, max_seqs=len(lens))
+    log("workspace %.2f GB" % (stage.workspace_bytes() / 2 ** 30))
+
+    def step():
+        ds.stage_fwd_bwd(stage, layout, weights, x, dy, out, dx, grads, accumulate=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    stage.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = stage.profile_read()
+    stage.profile_enable(False)
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens = int(layout.total_tokens)
+    value = tokens / (elapsed / args.steps)
+
+    lin_flops, attn_flops = algorithmic_flops(cfg, lens)
+    gemm_ms = sum(prof[k][0] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) / args.steps
+    gemm_launches = sum(prof[k][1] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) // args.steps
+    achieved = lin_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    breakdown = {k: round(v[0] / args.steps, 4) for k, v in prof.items()}
+    log("per-step ms by kernel group:", json.dumps(breakdown))
+    log("launches per step: %d" % stage.last_launch_count())
+    useful_util = (lin_flops + attn_flops) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+    executed_lin = lin_flops * R / max(tokens, 1)
+    log("useful MFMA utilisation (all algorithmic flops / step time / %.0f TFLOP/s): %.4f" % (PEAK_BF16_TFLOPS, useful_util))
+    log("padding efficiency %.4f, executed GEMM flops / algorithmic %.3f" % (tokens / R, executed_lin / lin_flops))
+
+    result = {
+        "metric": "non-pad tokens/s, stage fwd+bwd bf16 on 1 MI355X",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": args.config, "model": "%d layers d_model %d heads %d d_ff %d causal" % (L, d, H, F),
+                   "layout": layout_desc, "n_seq": int(len(lens)), "non_pad_tokens": tokens, "rows": int(R),
+                   "n_micro_batches": int(layout.n_mb), "padding_efficiency": tokens / R,
+                   "dp_plan_ms": plan_ms, "useful_mfma_utilisation": useful_util,
+                   "ms_per_step_by_group": breakdown},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_mfma_kernel (all projections: forward, dgrad, wgrad)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches_per_step": int(gemm_launches), "ms_per_step": gemm_ms,
+                     "algorithmic_flops_per_step": lin_flops},
+    }
+    stage.close()
+    del x, dy, out, dx, weights, grads
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, lens, args.seed)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

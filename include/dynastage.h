@@ -213,6 +213,17 @@ ds_status stage_fwd_bwd(ds_stage* stage, const ds_layout* layout,
                         void* grads, void* grads_dec, int32_t accumulate,
                         void* hip_stream);
 
+/* Per-kernel-group timing of stage_fwd_bwd.  When enabled, every kernel group the call enqueues
+ * is bracketed by a pair of HIP events on the caller's stream (events are created here, once,
+ * never inside stage_fwd_bwd; at most 2048 groups are recorded between two reads).
+ * ds_stage_profile_read waits for the recorded events, returns per group kind the summed
+ * milliseconds and the number of groups since the last read (HOST arrays of DS_PROF_COUNT
+ * entries) and clears the record. */
+enum { DS_PROF_GEMM_FWD = 0, DS_PROF_GEMM_DGRAD = 1, DS_PROF_GEMM_WGRAD = 2, DS_PROF_ATTN_FWD = 3,
+       DS_PROF_ATTN_BWD = 4, DS_PROF_NORM = 5, DS_PROF_COLSUM = 6, DS_PROF_OTHER = 7, DS_PROF_COUNT = 8 };
+ds_status ds_stage_profile_enable(ds_stage* stage, int32_t enable);
+ds_status ds_stage_profile_read(ds_stage* stage, float* ms, int32_t* count);
+
 /* Rough count of the kernels one stage_fwd_bwd call launches (diagnostics). */
 int32_t ds_stage_last_launch_count(const ds_stage* stage);
 

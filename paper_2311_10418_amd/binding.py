@@ -19,12 +19,14 @@ DS_MODEL_GPT, DS_MODEL_T5 = 0, 1
 DS_DTYPE_F32, DS_DTYPE_BF16 = 0, 1
 DS_EPI_NONE, DS_EPI_GELU, DS_EPI_RESID, DS_EPI_DGELU, DS_EPI_ACC32, DS_EPI_GATE, DS_EPI_DGATE = range(7)
 
+PROF_KINDS = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "norm", "colsum", "other")
+
 _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOMEM", -4: "DS_EOVERFLOW",
                  -5: "DS_EHIP", -6: "DS_ELAYOUT"}
 
 EXPORTS = ["dp_plan", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "stage_fwd_bwd",
-           "ds_stage_last_launch_count", "ds_pack", "ds_unpack", "ds_gemm", "ds_attention_fwd",
+           "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_attention_fwd",
            "ds_attention_bwd", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
            "ds_version"]
 
@@ -233,6 +235,16 @@ class Stage:
 
     def last_launch_count(self):
         return lib().ds_stage_last_launch_count(self.handle)
+
+    def profile_enable(self, on=True):
+        _check(lib().ds_stage_profile_enable(self.handle, C.c_int32(int(on))), "ds_stage_profile_enable")
+
+    def profile_read(self):
+        """-> dict kind -> (milliseconds, groups) summed since the last read."""
+        ms = (C.c_float * 8)()
+        cnt = (C.c_int32 * 8)()
+        _check(lib().ds_stage_profile_read(self.handle, ms, cnt), "ds_stage_profile_read")
+        return {k: (ms[i], cnt[i]) for i, k in enumerate(PROF_KINDS)}
 
     def close(self):
         if getattr(self, "handle", None) and _lib is not None:

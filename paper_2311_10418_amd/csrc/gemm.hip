@@ -157,60 +157,103 @@ constexpr int kStageLd = 132;                    // fp32 row stride of the epilo
 // byte offset of the 16-byte chunk `chunk` (8 bf16 along k) of tile row `row`
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
-// Load one 256x64 operand tile into registers.
-//  TR = 0: memory is [row][k] (k contiguous, leading dimension ld): chunk c = t + 256*i -> row c/8, k-chunk c%8.
-//  TR = 1: memory is [k][row] (row contiguous): thread owns k-chunk t%8 and rows (t/8)*8..+7; register i holds
-//          8 consecutive rows at k = kc*8 + i.
+// Register staging for one 256x64 operand tile: 8 chunks of 16 bytes per thread, kept in ONE
+// 32-dword vector value (chunk i = dwords 4i..4i+3) so that it stays in VGPRs across the K loop.
+typedef uint32_t u32x32_t __attribute__((ext_vector_type(32)));
+
+__device__ __forceinline__ void put4(u32x32_t& r, int i, const uint4& v) {
+    r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+}
+__device__ __forceinline__ uint4 get4(const u32x32_t& r, int i) {
+    return make_uint4(r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]);
+}
+
+typedef int i32x8_t __attribute__((ext_vector_type(8)));
+
+// Operand tile loader (256 rows x 64 k per step).  Addresses are a work-group-uniform 64-bit
+// panel base plus a per-thread 32-bit byte offset computed once, outside the K loop.
+//  TR = 0: memory is [row][k] (k contiguous): chunk c = t + 256*i -> row c/8, k-chunk c%8; the
+//          K step advances the uniform base by 64 elements.  Rows past the edge are clamped
+//          (they are never stored).
+//  TR = 1: memory is [k][row] (row contiguous): the thread owns k-chunk t%8 and rows
+//          (t/8)*8..+7; chunk i holds 8 consecutive rows at k = kc*8 + i; the K step advances
+//          the base by 64*ld elements.  k indices past the contraction length are clamped for the
+//          load and zeroed when the tile is written to LDS.
 template <int TR>
-__device__ __forceinline__ void load_tile(uint4 (&r)[8], const bf16_t* __restrict__ base, long long ld, int row0,
-                                          int n_rows, int k0, int n_k, int t) {
+__device__ __forceinline__ i32x8_t tile_offsets(long long ld, int row0, int n_rows, int t) {
+    i32x8_t off;
     if (TR == 0) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int c = t + 256 * i;
             int row = row0 + (c >> 3);
-            row = row < n_rows ? row : n_rows - 1;           // clamp: rows beyond the edge are never stored
-            const int k = k0 + ((c & 7) << 3);
-            r[i] = *reinterpret_cast<const uint4*>(base + (long long)row * ld + k);
+            row = row < n_rows ? row : n_rows - 1;
+            off[i] = (int)(((long long)(row - row0) * ld + ((c & 7) << 3)) * 2);
         }
     } else {
-        const int kc = t & 7, rg = t >> 3;
-        const int row = row0 + rg * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) off[i] = (t >> 3) * 16;         // row-group offset; the k part is added per step
+    }
+    return off;
+}
+
+template <int TR>
+__device__ __forceinline__ void load_tile(u32x32_t& r, const char* __restrict__ panel, const i32x8_t& off, int ld_bytes,
+                                          int k_left, int t) {
+    if (TR == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) put4(r, i, *reinterpret_cast<const uint4*>(panel + off[i]));
+    } else {
+        const int kc = t & 7;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int k = k0 + kc * 8 + i;
-            if (k < n_k)
-                r[i] = *reinterpret_cast<const uint4*>(base + (long long)k * ld + row);
-            else
-                r[i] = make_uint4(0u, 0u, 0u, 0u);            // contraction tail contributes zero
+            int k = kc * 8 + i;
+            k = k < k_left ? k : k_left - 1;
+            put4(r, i, *reinterpret_cast<const uint4*>(panel + (off[i] + k * ld_bytes)));
         }
     }
 }
 
-__device__ __forceinline__ uint32_t pick(const uint4& v, int w) {
-    return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w));
-}
-
 template <int TR>
-__device__ __forceinline__ void store_tile(const uint4 (&r)[8], char* __restrict__ lds, int t) {
+__device__ __forceinline__ void store_tile(const u32x32_t& r, char* __restrict__ lds, int k_left, int t) {
     if (TR == 0) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int c = t + 256 * i;
-            *reinterpret_cast<uint4*>(lds + lds_off(c >> 3, c & 7)) = r[i];
+            *reinterpret_cast<uint4*>(lds + lds_off(c >> 3, c & 7)) = get4(r, i);
         }
     } else {
         const int kc = t & 7, rg = t >> 3;
-        // 8x8 transpose of 16-bit elements: out row i, k pair (2j, 2j+1) <- element i of r[2j], r[2j+1]
+        // transpose 8x8 16-bit elements: out row i, k pair (2j, 2j+1) <- element i of chunks 2j, 2j+1.
+        // In the (work-group-uniform) tail tile, chunks whose k index lies past the contraction
+        // length are zeroed first.
+        if (k_left >= BK) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            uint4 o;
-            const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-            o.x = __builtin_amdgcn_perm(pick(r[1], i >> 1), pick(r[0], i >> 1), sel);
-            o.y = __builtin_amdgcn_perm(pick(r[3], i >> 1), pick(r[2], i >> 1), sel);
-            o.z = __builtin_amdgcn_perm(pick(r[5], i >> 1), pick(r[4], i >> 1), sel);
-            o.w = __builtin_amdgcn_perm(pick(r[7], i >> 1), pick(r[6], i >> 1), sel);
-            *reinterpret_cast<uint4*>(lds + lds_off(rg * 8 + i, kc)) = o;
+            for (int i = 0; i < 8; ++i) {
+                uint4 o;
+                const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+                const int w = i >> 1;
+                o.x = __builtin_amdgcn_perm(r[4 * 1 + w], r[4 * 0 + w], sel);
+                o.y = __builtin_amdgcn_perm(r[4 * 3 + w], r[4 * 2 + w], sel);
+                o.z = __builtin_amdgcn_perm(r[4 * 5 + w], r[4 * 4 + w], sel);
+                o.w = __builtin_amdgcn_perm(r[4 * 7 + w], r[4 * 6 + w], sel);
+                *reinterpret_cast<uint4*>(lds + lds_off(rg * 8 + i, kc)) = o;
+            }
+        } else {
+            uint32_t keep[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) keep[j] = (kc * 8 + j) < k_left ? 0xffffffffu : 0u;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                uint4 o;
+                const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+                const int w = i >> 1;
+                o.x = __builtin_amdgcn_perm(r[4 * 1 + w] & keep[1], r[4 * 0 + w] & keep[0], sel);
+                o.y = __builtin_amdgcn_perm(r[4 * 3 + w] & keep[3], r[4 * 2 + w] & keep[2], sel);
+                o.z = __builtin_amdgcn_perm(r[4 * 5 + w] & keep[5], r[4 * 4 + w] & keep[4], sel);
+                o.w = __builtin_amdgcn_perm(r[4 * 7 + w] & keep[7], r[4 * 6 + w] & keep[6], sel);
+                *reinterpret_cast<uint4*>(lds + lds_off(rg * 8 + i, kc)) = o;
+            }
         }
     }
 }
@@ -268,23 +311,36 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_mfma_kernel(int M, int N, in
     // LDS map: buffer b holds A at b*2*kTileBytes and B right after it
 
     if (kt_begin < kt_end) {
-        uint4 ra[8], rb[8];
-        load_tile<TA>(ra, A, lda, m0, M, kt_begin * BK, K, t);
-        load_tile<(TB == 0)>(rb, B, ldb, n0, N, kt_begin * BK, K, t);
-        store_tile<TA>(ra, smem, t);
-        store_tile<(TB == 0)>(rb, smem + kTileBytes, t);
-        __syncthreads();
-
+        // Software pipeline: the tile for step kt+1 is fetched into registers right before the MFMA
+        // block of step kt and written to the idle LDS buffer at the top of step kt+1, so the global
+        // latency hides behind a whole MFMA block and one barrier per step suffices.  The prefetch is
+        // unconditional (the last step re-reads its own tile): a conditional one makes the compiler
+        // keep the staging registers in scratch and serialise the loads.
+        u32x32_t ra, rb;
+        const i32x8_t offA = tile_offsets<TA>(lda, m0, M, t);
+        const i32x8_t offB = tile_offsets<(TB == 0)>(ldb, n0, N, t);
+        const int lda_b = (int)(lda * 2), ldb_b = (int)(ldb * 2);
+        // uniform panel bases; one K step advances them by stepA / stepB bytes
+        const char* pa = reinterpret_cast<const char*>(A) + (TA ? (long long)m0 * 2 : (long long)m0 * lda * 2);
+        const char* pb = reinterpret_cast<const char*>(B) + (TB ? (long long)n0 * ldb * 2 : (long long)n0 * 2);
+        const long long stepA = TA ? (long long)BK * lda * 2 : (long long)BK * 2;
+        const long long stepB = TB ? (long long)BK * 2 : (long long)BK * ldb * 2;
+        load_tile<TA>(ra, pa + kt_begin * stepA, offA, lda_b, K - kt_begin * BK, t);
+        load_tile<(TB == 0)>(rb, pb + kt_begin * stepB, offB, ldb_b, K - kt_begin * BK, t);
         const int frag_row = lane & 31, frag_half = lane >> 5;
+        int k_left_cur = K - kt_begin * BK;                    // contraction elements left at the tile in registers
         for (int kt = kt_begin; kt < kt_end; ++kt) {
             const int buf = (kt - kt_begin) & 1;
-            const bool more = kt + 1 < kt_end;
-            if (more) {
-                load_tile<TA>(ra, A, lda, m0, M, (kt + 1) * BK, K, t);
-                load_tile<(TB == 0)>(rb, B, ldb, n0, N, (kt + 1) * BK, K, t);
-            }
-            const char* a_base = smem + buf * (2 * kTileBytes);
-            const char* b_base = a_base + kTileBytes;
+            char* a_base = smem + buf * (2 * kTileBytes);
+            char* b_base = a_base + kTileBytes;
+            store_tile<TA>(ra, a_base, k_left_cur, t);
+            store_tile<(TB == 0)>(rb, b_base, k_left_cur, t);
+            __syncthreads();
+            const int kn = kt + 1 < kt_end ? kt + 1 : kt;
+            k_left_cur = K - kn * BK;
+            load_tile<TA>(ra, pa + kn * stepA, offA, lda_b, k_left_cur, t);
+            load_tile<(TB == 0)>(rb, pb + kn * stepB, offB, ldb_b, k_left_cur, t);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 bf16x8_t af[4], bfr[4];
@@ -301,12 +357,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_mfma_kernel(int M, int N, in
                     for (int j = 0; j < 4; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
             }
-            if (more) {
-                char* nxt = smem + (buf ^ 1) * (2 * kTileBytes);
-                store_tile<TA>(ra, nxt, t);
-                store_tile<(TB == 0)>(rb, nxt + kTileBytes, t);
-            }
-            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 

@@ -78,6 +78,11 @@ struct ds_stage {
     float *delta = nullptr, *partial = nullptr, *split_ws = nullptr;
     size_t split_ws_floats = 0;
     int32_t launches = 0;
+    // optional per-kernel-group timing
+    bool prof_on = false;
+    std::vector<hipEvent_t> ev_pool;
+    std::vector<int> ev_cat;
+    int ev_used = 0;
 };
 
 namespace {
@@ -159,33 +164,54 @@ AttnArgs self_attn_args(ds_stage* s, const void* qkv, int mask) {
     return a;
 }
 
+// Runs fn, bracketed by a pair of HIP events on the stream when profiling is on.
+template <class F>
+ds_status timed(ds_stage* s, int cat, hipStream_t st, F&& fn) {
+    if (!s->prof_on || s->ev_used + 2 > (int)s->ev_pool.size()) return fn();
+    hipEvent_t e0 = s->ev_pool[s->ev_used], e1 = s->ev_pool[s->ev_used + 1];
+    DS_HIP_CHECK(hipEventRecord(e0, st));
+    const ds_status r = fn();
+    DS_HIP_CHECK(hipEventRecord(e1, st));
+    s->ev_cat[s->ev_used / 2] = cat;
+    s->ev_used += 2;
+    return r;
+}
+
 ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io, const ds_gpt_layer* g, int accumulate,
                       hipStream_t st) {
     const int R = s->bound_rows, d = s->cfg.d_model, F = s->cfg.d_ff, L = s->cfg.n_layers;
     const int dt = s->cfg.dtype;
     const bool pad = s->bound_has_pad;
+    auto G = [&](int cat, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C, int epi,
+                 const void* bias, const void* Rr, void* C2, bool mask, int acc) {
+        return timed(s, cat, st, [&] { return gemm(s, ta, tb, M, N, K, A, B, C, epi, bias, Rr, nullptr, C2, mask, acc, st); });
+    };
+    auto colsum = [&](int n, const void* x, void* out) {
+        s->launches += 2;
+        return timed(s, DS_PROF_COLSUM, st, [&] { return ds_colsum(dt, R, n, x, (float*)out, s->partial, accumulate, st); });
+    };
 
     // ---------------- forward (ForwardPass of every micro-batch)
     const void* x_in = io->act_in;
     if (pad) {
-        DS_TRY(launch_mask_rows(dt, R, d, io->act_in, s->x0, s->tab.row_valid, st));
+        DS_TRY(timed(s, DS_PROF_OTHER, st, [&] { return launch_mask_rows(dt, R, d, io->act_in, s->x0, s->tab.row_valid, st); }));
         s->launches++;
         x_in = s->x0;
     }
     for (int l = 0; l < L; ++l) {
         LayerBufs& b = s->layers[l];
         void* x_out = (l == L - 1) ? io->act_out : b.xout;
-        DS_TRY(ds_norm_fwd(dt, 0, R, d, x_in, w[l].ln1_g, w[l].ln1_b, b.u1, b.stats1, st));
-        DS_TRY(gemm(s, 0, 0, R, 3 * d, d, b.u1, w[l].w_qkv, b.qkv, DS_EPI_NONE, w[l].b_qkv, nullptr, nullptr, nullptr, false, 0, st));
+        DS_TRY(timed(s, DS_PROF_NORM, st, [&] { return ds_norm_fwd(dt, 0, R, d, x_in, w[l].ln1_g, w[l].ln1_b, b.u1, b.stats1, st); }));
+        DS_TRY(G(DS_PROF_GEMM_FWD, 0, 0, R, 3 * d, d, b.u1, w[l].w_qkv, b.qkv, DS_EPI_NONE, w[l].b_qkv, nullptr, nullptr, false, 0));
         AttnArgs a = self_attn_args(s, b.qkv, 1);
         a.o = b.o;
         a.lse = b.lse;
-        DS_TRY(launch_attention_fwd(a, false, st));
-        DS_TRY(zero_pad_rows(s, b.o, d, st));
-        DS_TRY(gemm(s, 0, 0, R, d, d, b.o, w[l].w_o, b.x1, DS_EPI_RESID, w[l].b_o, x_in, nullptr, nullptr, true, 0, st));
-        DS_TRY(ds_norm_fwd(dt, 0, R, d, b.x1, w[l].ln2_g, w[l].ln2_b, b.u2, b.stats2, st));
-        DS_TRY(gemm(s, 0, 0, R, F, d, b.u2, w[l].w_1, b.z, DS_EPI_GELU, w[l].b_1, nullptr, nullptr, b.a, false, 0, st));
-        DS_TRY(gemm(s, 0, 0, R, d, F, b.a, w[l].w_2, x_out, DS_EPI_RESID, w[l].b_2, b.x1, nullptr, nullptr, true, 0, st));
+        DS_TRY(timed(s, DS_PROF_ATTN_FWD, st, [&] { return launch_attention_fwd(a, false, st); }));
+        DS_TRY(timed(s, DS_PROF_OTHER, st, [&] { return zero_pad_rows(s, b.o, d, st); }));
+        DS_TRY(G(DS_PROF_GEMM_FWD, 0, 0, R, d, d, b.o, w[l].w_o, b.x1, DS_EPI_RESID, w[l].b_o, x_in, nullptr, true, 0));
+        DS_TRY(timed(s, DS_PROF_NORM, st, [&] { return ds_norm_fwd(dt, 0, R, d, b.x1, w[l].ln2_g, w[l].ln2_b, b.u2, b.stats2, st); }));
+        DS_TRY(G(DS_PROF_GEMM_FWD, 0, 0, R, F, d, b.u2, w[l].w_1, b.z, DS_EPI_GELU, w[l].b_1, nullptr, b.a, false, 0));
+        DS_TRY(G(DS_PROF_GEMM_FWD, 0, 0, R, d, F, b.a, w[l].w_2, x_out, DS_EPI_RESID, w[l].b_2, b.x1, nullptr, true, 0));
         s->launches += 3;
         x_in = x_out;
     }
@@ -193,7 +219,7 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
     // ---------------- backward (BackwardPass of every micro-batch; weight gradients summed over all of them)
     const void* dy = io->grad_out;
     if (pad) {
-        DS_TRY(launch_mask_rows(dt, R, d, io->grad_out, s->dyA, s->tab.row_valid, st));
+        DS_TRY(timed(s, DS_PROF_OTHER, st, [&] { return launch_mask_rows(dt, R, d, io->grad_out, s->dyA, s->tab.row_valid, st); }));
         s->launches++;
         dy = s->dyA;
     }
@@ -204,18 +230,20 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         const void* xl_in = (l == 0) ? (pad ? s->x0 : io->act_in) : s->layers[l - 1].xout;
         void* dx_in = (l == 0) ? io->grad_in : pp[flip];
         // MLP
-        DS_TRY(gemm(s, 1, 0, F, d, R, b.a, dy, g[l].w_2, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr, false, accumulate, st));
-        DS_TRY(ds_colsum(dt, R, d, dy, (float*)g[l].b_2, s->partial, accumulate, st));
-        DS_TRY(gemm(s, 0, 1, R, F, d, dy, w[l].w_2, s->dz, DS_EPI_DGELU, nullptr, b.z, nullptr, nullptr, false, 0, st));
-        DS_TRY(gemm(s, 1, 0, d, F, R, b.u2, s->dz, g[l].w_1, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr, false, accumulate, st));
-        DS_TRY(ds_colsum(dt, R, F, s->dz, (float*)g[l].b_1, s->partial, accumulate, st));
-        DS_TRY(gemm(s, 0, 1, R, d, F, s->dz, w[l].w_1, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr, nullptr, false, 0, st));
-        DS_TRY(ds_norm_bwd(dt, 0, R, d, s->du, b.x1, w[l].ln2_g, b.stats2, dy, s->dx1, (float*)g[l].ln2_g,
-                           (float*)g[l].ln2_b, s->partial, accumulate, st));
+        DS_TRY(G(DS_PROF_GEMM_WGRAD, 1, 0, F, d, R, b.a, dy, g[l].w_2, DS_EPI_ACC32, nullptr, nullptr, nullptr, false, accumulate));
+        DS_TRY(colsum(d, dy, g[l].b_2));
+        DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, F, d, dy, w[l].w_2, s->dz, DS_EPI_DGELU, nullptr, b.z, nullptr, false, 0));
+        DS_TRY(G(DS_PROF_GEMM_WGRAD, 1, 0, d, F, R, b.u2, s->dz, g[l].w_1, DS_EPI_ACC32, nullptr, nullptr, nullptr, false, accumulate));
+        DS_TRY(colsum(F, s->dz, g[l].b_1));
+        DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, d, F, s->dz, w[l].w_1, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr, false, 0));
+        DS_TRY(timed(s, DS_PROF_NORM, st, [&] {
+            return ds_norm_bwd(dt, 0, R, d, s->du, b.x1, w[l].ln2_g, b.stats2, dy, s->dx1, (float*)g[l].ln2_g,
+                               (float*)g[l].ln2_b, s->partial, accumulate, st);
+        }));
         // attention
-        DS_TRY(gemm(s, 1, 0, d, d, R, b.o, s->dx1, g[l].w_o, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr, false, accumulate, st));
-        DS_TRY(ds_colsum(dt, R, d, s->dx1, (float*)g[l].b_o, s->partial, accumulate, st));
-        DS_TRY(gemm(s, 0, 1, R, d, d, s->dx1, w[l].w_o, s->d_o, DS_EPI_NONE, nullptr, nullptr, nullptr, nullptr, false, 0, st));
+        DS_TRY(G(DS_PROF_GEMM_WGRAD, 1, 0, d, d, R, b.o, s->dx1, g[l].w_o, DS_EPI_ACC32, nullptr, nullptr, nullptr, false, accumulate));
+        DS_TRY(colsum(d, s->dx1, g[l].b_o));
+        DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, d, d, s->dx1, w[l].w_o, s->d_o, DS_EPI_NONE, nullptr, nullptr, nullptr, false, 0));
         AttnArgs a = self_attn_args(s, b.qkv, 1);
         a.o = b.o;
         a.d_o = s->d_o;
@@ -225,14 +253,16 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         a.dq = dq;
         a.dk = dq + (size_t)d * s->es;
         a.dv = dq + (size_t)2 * d * s->es;
-        DS_TRY(launch_attention_bwd(a, false, st));
-        DS_TRY(zero_pad_rows(s, s->dqkv, 3 * d, st));
-        DS_TRY(gemm(s, 1, 0, d, 3 * d, R, b.u1, s->dqkv, g[l].w_qkv, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr, false, accumulate, st));
-        DS_TRY(ds_colsum(dt, R, 3 * d, s->dqkv, (float*)g[l].b_qkv, s->partial, accumulate, st));
-        DS_TRY(gemm(s, 0, 1, R, d, 3 * d, s->dqkv, w[l].w_qkv, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr, nullptr, false, 0, st));
-        DS_TRY(ds_norm_bwd(dt, 0, R, d, s->du, xl_in, w[l].ln1_g, b.stats1, s->dx1, dx_in, (float*)g[l].ln1_g,
-                           (float*)g[l].ln1_b, s->partial, accumulate, st));
-        s->launches += 4 * 2 + 2 * 3 + 3;
+        DS_TRY(timed(s, DS_PROF_ATTN_BWD, st, [&] { return launch_attention_bwd(a, false, st); }));
+        DS_TRY(timed(s, DS_PROF_OTHER, st, [&] { return zero_pad_rows(s, s->dqkv, 3 * d, st); }));
+        DS_TRY(G(DS_PROF_GEMM_WGRAD, 1, 0, d, 3 * d, R, b.u1, s->dqkv, g[l].w_qkv, DS_EPI_ACC32, nullptr, nullptr, nullptr, false, accumulate));
+        DS_TRY(colsum(3 * d, s->dqkv, g[l].b_qkv));
+        DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, d, 3 * d, s->dqkv, w[l].w_qkv, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr, false, 0));
+        DS_TRY(timed(s, DS_PROF_NORM, st, [&] {
+            return ds_norm_bwd(dt, 0, R, d, s->du, xl_in, w[l].ln1_g, b.stats1, s->dx1, dx_in, (float*)g[l].ln1_g,
+                               (float*)g[l].ln1_b, s->partial, accumulate, st);
+        }));
+        s->launches += 2 * 3 + 3;
         dy = dx_in;
         flip ^= 1;
     }
@@ -329,10 +359,42 @@ extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out)
 
 extern "C" void ds_stage_destroy(ds_stage* s) {
     if (!s) return;
+    for (hipEvent_t e : s->ev_pool) (void)hipEventDestroy(e);
     if (s->upload_done) (void)hipEventDestroy(s->upload_done);
     if (s->h_tables) (void)hipHostFree(s->h_tables);
     if (s->ws) (void)hipFree(s->ws);
     delete s;
+}
+
+extern "C" ds_status ds_stage_profile_enable(ds_stage* s, int32_t enable) {
+    if (!s) return DS_EINVAL;
+    if (enable && s->ev_pool.empty()) {
+        const int pairs = 2048;
+        s->ev_pool.reserve(2 * pairs);
+        for (int i = 0; i < 2 * pairs; ++i) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return DS_EHIP;
+            s->ev_pool.push_back(e);
+        }
+        s->ev_cat.assign(pairs, 0);
+    }
+    s->prof_on = enable != 0;
+    s->ev_used = 0;
+    return DS_OK;
+}
+
+extern "C" ds_status ds_stage_profile_read(ds_stage* s, float* ms, int32_t* count) {
+    if (!s || !ms || !count) return DS_EINVAL;
+    for (int c = 0; c < DS_PROF_COUNT; ++c) { ms[c] = 0.f; count[c] = 0; }
+    for (int i = 0; i + 1 < s->ev_used; i += 2) {
+        DS_HIP_CHECK(hipEventSynchronize(s->ev_pool[i + 1]));
+        float t = 0.f;
+        DS_HIP_CHECK(hipEventElapsedTime(&t, s->ev_pool[i], s->ev_pool[i + 1]));
+        ms[s->ev_cat[i / 2]] += t;
+        count[s->ev_cat[i / 2]]++;
+    }
+    s->ev_used = 0;
+    return DS_OK;
 }
 
 extern "C" int64_t ds_stage_workspace_bytes(const ds_stage* s) { return s ? (int64_t)s->ws_bytes : 0; }
