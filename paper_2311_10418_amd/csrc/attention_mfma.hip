@@ -25,11 +25,14 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+// LDS swizzles.  gfx950 serves a 16-byte LDS read for 16 lanes per cycle (64 banks), so 16
+// consecutive rows read at the same chunk index must fall into 16 different 16-byte units of a
+// 256-byte window: 256-byte rows XOR the chunk with row%16, 128-byte rows with (row/2)%8.
 template <int HD> __device__ __forceinline__ int off_rows(int row, int chunk) {      // [row][HD] tile
-    return row * (HD * 2) + ((chunk ^ (row & 7)) << 4);
+    return HD == 128 ? row * 256 + ((chunk ^ (row & 15)) << 4) : row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 __device__ __forceinline__ int off_tr(int d, int kg) {                                // [d][64 slots] tile
-    return d * 128 + ((kg ^ (d & 7)) << 4);
+    return d * 128 + ((kg ^ ((d >> 1) & 7)) << 4);
 }
 __device__ __forceinline__ int slot_row(int t, int g, int j) { return 16 * t + 8 * (j >> 2) + 4 * g + (j & 3); }
 

@@ -60,6 +60,39 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(int in_rows, int d8, 
     }
 }
 
+// ------------------------------------------------------------------ bf16 transpose
+// out[c][r] = in[r][c] for r < rows, zero for rows <= r < rows_pad (out has leading dimension rows_pad).
+// One wavefront per 64x64 tile as 8x8 blocks of 8x8 elements: each lane loads 8 rows of 16 bytes,
+// transposes them in registers (v_perm_b32) and stores 8 rows of 16 bytes; lanes are arranged 8x8 so
+// that both the loads and the stores form 128-byte contiguous segments.  No LDS.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(int rows, int cols, int rows_pad, const bf16_t* __restrict__ in,
+                                                             bf16_t* __restrict__ out) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int bx = lane & 7, by = lane >> 3;
+    const int c0 = blockIdx.x * 64 + bx * 8;
+    const int r0 = (blockIdx.y * 4 + wave) * 64 + by * 8;
+    if (r0 >= rows_pad || c0 >= cols) return;
+    uint32_t v[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = r0 + i;
+        uint4 x = make_uint4(0u, 0u, 0u, 0u);
+        if (r < rows) x = *reinterpret_cast<const uint4*>(in + (size_t)r * cols + c0);
+        v[i][0] = x.x; v[i][1] = x.y; v[i][2] = x.z; v[i][3] = x.w;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {          // output row c0+i gathers element i of the 8 loaded rows
+        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+        const int w = i >> 1;
+        uint4 o;
+        o.x = __builtin_amdgcn_perm(v[1][w], v[0][w], sel);
+        o.y = __builtin_amdgcn_perm(v[3][w], v[2][w], sel);
+        o.z = __builtin_amdgcn_perm(v[5][w], v[4][w], sel);
+        o.w = __builtin_amdgcn_perm(v[7][w], v[6][w], sel);
+        *reinterpret_cast<uint4*>(out + (size_t)(c0 + i) * rows_pad + r0) = o;
+    }
+}
+
 inline int grid_for(long long work_items, int block) {
     long long g = (work_items + block - 1) / block;
     if (g > 65536) g = 65536;
@@ -335,6 +368,14 @@ ds_status launch_scatter_rows(int32_t dtype, int32_t in_rows, int32_t d, const v
     else
         hipLaunchKernelGGL(scatter_rows_kernel<float>, dim3(grid_for(items, 256)), dim3(256), 0, st, in_rows, d / 8,
                            (const float*)in, (float*)out, dst_row);
+    DS_LAUNCH_CHECK();
+    return DS_OK;
+}
+
+ds_status launch_transpose_bf16(int32_t rows, int32_t cols, int32_t rows_pad, const void* in, void* out, hipStream_t st) {
+    if (rows <= 0 || cols <= 0 || cols % 8 || rows_pad < rows || rows_pad % 8 || !in || !out) return DS_EINVAL;
+    dim3 grid((cols + 63) / 64, (rows_pad + 255) / 256);
+    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, st, rows, cols, rows_pad, (const bf16_t*)in, (bf16_t*)out);
     DS_LAUNCH_CHECK();
     return DS_OK;
 }

@@ -154,8 +154,12 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kTileBytes = BM * BK * 2;          // 32 KB per operand per buffer
 constexpr int kStageLd = 132;                    // fp32 row stride of the epilogue staging area
 
-// byte offset of the 16-byte chunk `chunk` (8 bf16 along k) of tile row `row`
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+// Byte offset of the 16-byte chunk `chunk` (8 bf16 along k) of tile row `row`.  gfx950's LDS serves
+// a 16-byte read for 16 lanes per cycle (64 banks x 4 B), so the 16 consecutive rows that 16
+// consecutive lanes read must land in 16 different 16-byte units of a 256-byte window: rows 2q and
+// 2q+1 already differ by 128 bytes, and the XOR with (row/2)%8 separates the 8 row pairs.
+// (Measured with SQ_LDS_BANK_CONFLICT: a swizzle by row%8 costs one extra cycle pass per read.)
+__device__ __forceinline__ int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
 // Register staging for one 256x64 operand tile: 8 chunks of 16 bytes per thread, kept in ONE
 // 32-dword vector value (chunk i = dwords 4i..4i+3) so that it stays in VGPRs across the K loop.
@@ -168,10 +172,11 @@ __device__ __forceinline__ uint4 get4(const u32x32_t& r, int i) {
     return make_uint4(r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]);
 }
 
-typedef int i32x8_t __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x8_t __attribute__((ext_vector_type(8)));
 
-// Operand tile loader (256 rows x 64 k per step).  Addresses are a work-group-uniform 64-bit
-// panel base plus a per-thread 32-bit byte offset computed once, outside the K loop.
+// Operand tile loader (256 rows x 64 k per step, 8 chunks of 16 bytes per thread).  Addresses are a
+// work-group-uniform 64-bit panel base plus a per-thread unsigned 32-bit byte offset computed once,
+// outside the K loop.
 //  TR = 0: memory is [row][k] (k contiguous): chunk c = t + 256*i -> row c/8, k-chunk c%8; the
 //          K step advances the uniform base by 64 elements.  Rows past the edge are clamped
 //          (they are never stored).
@@ -180,81 +185,77 @@ typedef int i32x8_t __attribute__((ext_vector_type(8)));
 //          the base by 64*ld elements.  k indices past the contraction length are clamped for the
 //          load and zeroed when the tile is written to LDS.
 template <int TR>
-__device__ __forceinline__ i32x8_t tile_offsets(long long ld, int row0, int n_rows, int t) {
-    i32x8_t off;
+__device__ __forceinline__ u32x8_t tile_offsets(long long ld, int row0, int n_rows, int t) {
+    u32x8_t off;
     if (TR == 0) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int c = t + 256 * i;
             int row = row0 + (c >> 3);
             row = row < n_rows ? row : n_rows - 1;
-            off[i] = (int)(((long long)(row - row0) * ld + ((c & 7) << 3)) * 2);
+            off[i] = (uint32_t)(((long long)(row - row0) * ld + ((c & 7) << 3)) * 2);
         }
     } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) off[i] = (t >> 3) * 16;         // row-group offset; the k part is added per step
+        for (int i = 0; i < 8; ++i) off[i] = (uint32_t)((t >> 3) * 16);   // row-group offset; the k part is added per step
     }
     return off;
 }
 
 template <int TR>
-__device__ __forceinline__ void load_tile(u32x32_t& r, const char* __restrict__ panel, const i32x8_t& off, int ld_bytes,
-                                          int k_left, int t) {
+__device__ __forceinline__ void load_chunk(u32x32_t& r, int i, const char* __restrict__ panel, const u32x8_t& off,
+                                           uint32_t ld_bytes, int k_left, int t) {
     if (TR == 0) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) put4(r, i, *reinterpret_cast<const uint4*>(panel + off[i]));
+        put4(r, i, *reinterpret_cast<const uint4*>(panel + off[i]));
     } else {
-        const int kc = t & 7;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int k = kc * 8 + i;
-            k = k < k_left ? k : k_left - 1;
-            put4(r, i, *reinterpret_cast<const uint4*>(panel + (off[i] + k * ld_bytes)));
-        }
+        int k = (t & 7) * 8 + i;
+        k = k < k_left ? k : k_left - 1;
+        put4(r, i, *reinterpret_cast<const uint4*>(panel + (off[i] + (uint32_t)k * ld_bytes)));
     }
 }
 
+// Write part i (of 8) of a staged tile to LDS.  TR = 0: chunk i as loaded.  TR = 1: tile row
+// (t/8)*8 + i, gathered from element i of all 8 loaded chunks (8x8 transpose of 16-bit elements:
+// k pair (2j, 2j+1) <- element i of chunks 2j, 2j+1); in the work-group-uniform tail tile the chunks
+// whose k index lies past the contraction length are zeroed first.
 template <int TR>
-__device__ __forceinline__ void store_tile(const u32x32_t& r, char* __restrict__ lds, int k_left, int t) {
+__device__ __forceinline__ void store_chunk(const u32x32_t& r, int i, char* __restrict__ lds, int k_left, int t) {
     if (TR == 0) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int c = t + 256 * i;
-            *reinterpret_cast<uint4*>(lds + lds_off(c >> 3, c & 7)) = get4(r, i);
-        }
+        const int c = t + 256 * i;
+        *reinterpret_cast<uint4*>(lds + lds_off(c >> 3, c & 7)) = get4(r, i);
     } else {
         const int kc = t & 7, rg = t >> 3;
-        // transpose 8x8 16-bit elements: out row i, k pair (2j, 2j+1) <- element i of chunks 2j, 2j+1.
-        // In the (work-group-uniform) tail tile, chunks whose k index lies past the contraction
-        // length are zeroed first.
+        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+        const int w = i >> 1;
+        uint4 o;
         if (k_left >= BK) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                uint4 o;
-                const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-                const int w = i >> 1;
-                o.x = __builtin_amdgcn_perm(r[4 * 1 + w], r[4 * 0 + w], sel);
-                o.y = __builtin_amdgcn_perm(r[4 * 3 + w], r[4 * 2 + w], sel);
-                o.z = __builtin_amdgcn_perm(r[4 * 5 + w], r[4 * 4 + w], sel);
-                o.w = __builtin_amdgcn_perm(r[4 * 7 + w], r[4 * 6 + w], sel);
-                *reinterpret_cast<uint4*>(lds + lds_off(rg * 8 + i, kc)) = o;
-            }
+            o.x = __builtin_amdgcn_perm(r[4 * 1 + w], r[4 * 0 + w], sel);
+            o.y = __builtin_amdgcn_perm(r[4 * 3 + w], r[4 * 2 + w], sel);
+            o.z = __builtin_amdgcn_perm(r[4 * 5 + w], r[4 * 4 + w], sel);
+            o.w = __builtin_amdgcn_perm(r[4 * 7 + w], r[4 * 6 + w], sel);
         } else {
             uint32_t keep[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) keep[j] = (kc * 8 + j) < k_left ? 0xffffffffu : 0u;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                uint4 o;
-                const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-                const int w = i >> 1;
-                o.x = __builtin_amdgcn_perm(r[4 * 1 + w] & keep[1], r[4 * 0 + w] & keep[0], sel);
-                o.y = __builtin_amdgcn_perm(r[4 * 3 + w] & keep[3], r[4 * 2 + w] & keep[2], sel);
-                o.z = __builtin_amdgcn_perm(r[4 * 5 + w] & keep[5], r[4 * 4 + w] & keep[4], sel);
-                o.w = __builtin_amdgcn_perm(r[4 * 7 + w] & keep[7], r[4 * 6 + w] & keep[6], sel);
-                *reinterpret_cast<uint4*>(lds + lds_off(rg * 8 + i, kc)) = o;
-            }
+            o.x = __builtin_amdgcn_perm(r[4 * 1 + w] & keep[1], r[4 * 0 + w] & keep[0], sel);
+            o.y = __builtin_amdgcn_perm(r[4 * 3 + w] & keep[3], r[4 * 2 + w] & keep[2], sel);
+            o.z = __builtin_amdgcn_perm(r[4 * 5 + w] & keep[5], r[4 * 4 + w] & keep[4], sel);
+            o.w = __builtin_amdgcn_perm(r[4 * 7 + w] & keep[7], r[4 * 6 + w] & keep[6], sel);
         }
+        *reinterpret_cast<uint4*>(lds + lds_off(rg * 8 + i, kc)) = o;
+    }
+}
+
+struct Frags {
+    bf16x8_t a[4], b[4];
+};
+
+__device__ __forceinline__ void load_frags(Frags& f, const char* __restrict__ a_base, const char* __restrict__ b_base, int wm,
+                                           int wn, int ks, int frag_row, int frag_half) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f.a[i] = *reinterpret_cast<const bf16x8_t*>(a_base + lds_off(wm * 128 + i * 32 + frag_row, ks * 2 + frag_half));
+        f.b[i] = *reinterpret_cast<const bf16x8_t*>(b_base + lds_off(wn * 128 + i * 32 + frag_row, ks * 2 + frag_half));
     }
 }
 
@@ -311,53 +312,82 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_mfma_kernel(int M, int N, in
     // LDS map: buffer b holds A at b*2*kTileBytes and B right after it
 
     if (kt_begin < kt_end) {
-        // Software pipeline: the tile for step kt+1 is fetched into registers right before the MFMA
-        // block of step kt and written to the idle LDS buffer at the top of step kt+1, so the global
-        // latency hides behind a whole MFMA block and one barrier per step suffices.  The prefetch is
-        // unconditional (the last step re-reads its own tile): a conditional one makes the compiler
-        // keep the staging registers in scratch and serialise the loads.
-        u32x32_t ra, rb;
-        const i32x8_t offA = tile_offsets<TA>(lda, m0, M, t);
-        const i32x8_t offB = tile_offsets<(TB == 0)>(ldb, n0, N, t);
-        const int lda_b = (int)(lda * 2), ldb_b = (int)(ldb * 2);
-        // uniform panel bases; one K step advances them by stepA / stepB bytes
+        // Software pipeline over K tiles: one register staging set, two LDS buffers.  While the MFMAs
+        // of tile kt run out of LDS buffer kt%2, the first quarter of them is interleaved with the LDS
+        // writes of tile kt+1 (fetched 3/4 of a step earlier) into the other buffer, and the second
+        // quarter with the global loads of tile kt+2 into the registers just freed.  One barrier per
+        // step, and no LDS write sits between the barrier and the first MFMA.  Tile indices past the
+        // end are clamped (redundant, harmless work) so that no load or store is conditional:
+        // conditional staging makes the compiler keep it in scratch.
+        constexpr int TBt = (TB == 0);
+        const u32x8_t offA = tile_offsets<TA>(lda, m0, M, t);
+        const u32x8_t offB = tile_offsets<TBt>(ldb, n0, N, t);
+        const uint32_t lda_b = (uint32_t)(lda * 2), ldb_b = (uint32_t)(ldb * 2);
         const char* pa = reinterpret_cast<const char*>(A) + (TA ? (long long)m0 * 2 : (long long)m0 * lda * 2);
         const char* pb = reinterpret_cast<const char*>(B) + (TB ? (long long)n0 * ldb * 2 : (long long)n0 * 2);
         const long long stepA = TA ? (long long)BK * lda * 2 : (long long)BK * 2;
         const long long stepB = TB ? (long long)BK * 2 : (long long)BK * ldb * 2;
-        load_tile<TA>(ra, pa + kt_begin * stepA, offA, lda_b, K - kt_begin * BK, t);
-        load_tile<(TB == 0)>(rb, pb + kt_begin * stepB, offB, ldb_b, K - kt_begin * BK, t);
         const int frag_row = lane & 31, frag_half = lane >> 5;
-        int k_left_cur = K - kt_begin * BK;                    // contraction elements left at the tile in registers
+        const int kt_last = kt_end - 1;
+
+        u32x32_t sa, sb;
+        {   // prologue: tile kt_begin -> LDS buffer 0; tile kt_begin+1 -> registers
+            const int k0 = kt_begin;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                load_chunk<TA>(sa, i, pa + k0 * stepA, offA, lda_b, K - k0 * BK, t);
+                load_chunk<TBt>(sb, i, pb + k0 * stepB, offB, ldb_b, K - k0 * BK, t);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                store_chunk<TA>(sa, i, smem, K - k0 * BK, t);
+                store_chunk<TBt>(sb, i, smem + kTileBytes, K - k0 * BK, t);
+            }
+            const int k1 = k0 + 1 < kt_last ? k0 + 1 : kt_last;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                load_chunk<TA>(sa, i, pa + k1 * stepA, offA, lda_b, K - k1 * BK, t);
+                load_chunk<TBt>(sb, i, pb + k1 * stepB, offB, ldb_b, K - k1 * BK, t);
+            }
+            __syncthreads();
+        }
+
         for (int kt = kt_begin; kt < kt_end; ++kt) {
             const int buf = (kt - kt_begin) & 1;
-            char* a_base = smem + buf * (2 * kTileBytes);
-            char* b_base = a_base + kTileBytes;
-            store_tile<TA>(ra, a_base, k_left_cur, t);
-            store_tile<(TB == 0)>(rb, b_base, k_left_cur, t);
-            __syncthreads();
-            const int kn = kt + 1 < kt_end ? kt + 1 : kt;
-            k_left_cur = K - kn * BK;
-            load_tile<TA>(ra, pa + kn * stepA, offA, lda_b, k_left_cur, t);
-            load_tile<(TB == 0)>(rb, pb + kn * stepB, offB, ldb_b, k_left_cur, t);
-            __builtin_amdgcn_sched_barrier(0);
+            const char* a_base = smem + buf * (2 * kTileBytes);
+            const char* b_base = a_base + kTileBytes;
+            char* na = smem + (buf ^ 1) * (2 * kTileBytes);
+            char* nb = na + kTileBytes;
+            const int k_store = K - (kt + 1 < kt_last ? kt + 1 : kt_last) * BK;   // tile now in registers
+            const int kn = kt + 2 < kt_last ? kt + 2 : kt_last;                  // tile to fetch
+            const int k_load = K - kn * BK;
+            const char* pan = pa + kn * stepA;
+            const char* pbn = pb + kn * stepB;
+            Frags f[2];
+            load_frags(f[0], a_base, b_base, wm, wn, 0, frag_row, frag_half);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                bf16x8_t af[4], bfr[4];
+                if (ks < 3) load_frags(f[(ks + 1) & 1], a_base, b_base, wm, wn, ks + 1, frag_row, frag_half);
+                const Frags& c = f[ks & 1];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int ar = wm * 128 + i * 32 + frag_row;
-                    af[i] = *reinterpret_cast<const bf16x8_t*>(a_base + lds_off(ar, ks * 2 + frag_half));
-                    const int br = wn * 128 + i * 32 + frag_row;
-                    bfr[i] = *reinterpret_cast<const bf16x8_t*>(b_base + lds_off(br, ks * 2 + frag_half));
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.a[i], c.b[j], acc[i][j], 0, 0, 0);
+                    if (ks == 0) {          // slots 0..3: write staged tile kt+1 (parts 2i, 2i+1 of each operand)
+                        store_chunk<TA>(sa, 2 * i, na, k_store, t);
+                        store_chunk<TA>(sa, 2 * i + 1, na, k_store, t);
+                        store_chunk<TBt>(sb, 2 * i, nb, k_store, t);
+                        store_chunk<TBt>(sb, 2 * i + 1, nb, k_store, t);
+                    } else if (ks == 1) {   // slots 4..7: fetch tile kt+2
+                        load_chunk<TA>(sa, 2 * i, pan, offA, lda_b, k_load, t);
+                        load_chunk<TA>(sa, 2 * i + 1, pan, offA, lda_b, k_load, t);
+                        load_chunk<TBt>(sb, 2 * i, pbn, offB, ldb_b, k_load, t);
+                        load_chunk<TBt>(sb, 2 * i + 1, pbn, offB, ldb_b, k_load, t);
+                    }
+                }
             }
-            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
         }
     }
 
@@ -385,6 +415,168 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_mfma_kernel(int M, int N, in
                 float v[8];
                 const float4 x0 = *reinterpret_cast<const float4*>(stage + row * kStageLd + rd_col);
                 const float4 x1 = *reinterpret_cast<const float4*>(stage + row * kStageLd + rd_col + 4);
+                v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+                if (splits > 1) {
+                    Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
+                } else {
+                    epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------- NT kernel, direct to LDS
+// C[M,N] = A[M,K] * B[N,K]^T, both operands k-contiguous (K % 32 == 0, N % 256 == 0).
+//
+// 256x256 macro tile, 8 wavefronts (2 per SIMD) in a 2x4 arrangement, each owning a 128x64
+// accumulator block (8 MFMA tiles of 32x32, 128 accumulator registers).  Operands go global -> LDS
+// directly (global_load_lds_dwordx4): no staging registers, no LDS write instructions.  A wavefront
+// instruction deposits 64 x 16 bytes at consecutive LDS addresses, i.e. 16 tile rows of 4 chunks;
+// the XOR swizzle that makes the fragment reads conflict-free is obtained by choosing WHICH global
+// chunk each lane fetches.  K advances in 32-element tiles through a ring of 4 LDS stages (32 KB
+// each): three tiles are in flight while one is consumed.  One barrier per tile; the only
+// vector-memory wait is "at most the two newest tiles outstanding".  Tile indices past the end are
+// clamped (a few redundant loads into a free stage) so that this count is the same at every step.
+//
+// Why 8 wavefronts: measured on MI355X, one 4-wavefront work-group cannot pull more than about
+// 40-50 GB/s from L2 however many loads it keeps in flight, which is what a 256x256x(bf16) tile
+// needs at full MFMA rate; the rate scales with the number of wavefronts on the CU.
+constexpr int NT_DK = 32, NT_NS = 4, NT_HALF = 256 * NT_DK * 2, NT_STAGE = 2 * NT_HALF;
+constexpr int kStageLd2 = 68;
+
+template <int EPI>
+__global__ __launch_bounds__(512, 1) void gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
+                                                              const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
+                                                              int tiles_m, int tiles_n, int splits,
+                                                              float* __restrict__ split_ws, GemmEpi p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+
+    // ---- work-group id -> (tile_m, tile_n, split): contiguous runs per XCD, groups of 8 tile rows
+    const int total = tiles_m * tiles_n * splits;
+    int logical;
+    {
+        const int pid = blockIdx.x;
+        const int xcd = pid & 7, local = pid >> 3;
+        const int per = total >> 3, rem = total & 7;
+        const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+        logical = start + local;
+    }
+    const int split = logical / (tiles_m * tiles_n);
+    logical -= split * (tiles_m * tiles_n);
+    int tile_m, tile_n;
+    {
+        const int group_sz = 8 * tiles_n;
+        const int group = logical / group_sz;
+        const int first_m = group * 8;
+        const int gs = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
+        const int in_group = logical - group * group_sz;
+        tile_m = first_m + in_group % gs;
+        tile_n = in_group / gs;
+    }
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int nt_total = K / NT_DK;
+    const int per_split = (nt_total + splits - 1) / splits;
+    const int t_begin = split * per_split;
+    const int t_end = (t_begin + per_split) < nt_total ? (t_begin + per_split) : nt_total;
+
+    f32x16_t acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    if (t_begin < t_end) {
+        uint32_t offA[2], offB[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int u = (wave * 2 + i) * 64 + lane;              // 16-byte unit of the 256x4 tile
+            const int row = u >> 2, slot = u & 3;
+            const int chunk = slot ^ ((row >> 2) & 3);
+            int ra_ = m0 + row;
+            ra_ = ra_ < M ? ra_ : M - 1;                            // rows past the edge: clamped, never stored
+            offA[i] = (uint32_t)(((long long)(ra_ - m0) * K + chunk * 8) * 2);
+            offB[i] = (uint32_t)(((long long)row * K + chunk * 8) * 2);
+        }
+        const char* pa = reinterpret_cast<const char*>(A) + (long long)m0 * K * 2;
+        const char* pb = reinterpret_cast<const char*>(B) + (long long)n0 * K * 2;
+        const int frag_row = lane & 31, frag_half = lane >> 5;
+        const int t_last = t_end - 1;
+        auto issue = [&](int tile, int stage) {
+            tile = tile < t_last ? tile : t_last;
+            const char* ga = pa + (long long)tile * (NT_DK * 2);
+            const char* gb = pb + (long long)tile * (NT_DK * 2);
+            char* la = smem + stage * NT_STAGE + wave * 2048;
+            char* lb = la + NT_HALF;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                __builtin_amdgcn_global_load_lds((gptr_t)(ga + offA[i]), (lptr_t)(la + i * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr_t)(gb + offB[i]), (lptr_t)(lb + i * 1024), 16, 0, 0);
+            }
+        };
+        // 64-byte rows: 16 consecutive rows at one chunk index must hit 16 different 16-byte units
+        auto off32 = [](int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4); };
+        issue(t_begin, 0);
+        issue(t_begin + 1, 1);
+        issue(t_begin + 2, 2);
+        for (int tl = t_begin; tl < t_end; ++tl) {
+            const int st_ = (tl - t_begin) & (NT_NS - 1);
+            __builtin_amdgcn_s_waitcnt(0x0F78);                     // vmcnt(8): this wavefront's part of tile tl has landed
+            __builtin_amdgcn_s_barrier();                           // ... and everyone's; stage (tl-1)%4 is free again
+            issue(tl + 3, (st_ + 3) & (NT_NS - 1));
+            const char* a_base = smem + st_ * NT_STAGE;
+            const char* b_base = a_base + NT_HALF;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                bf16x8_t fa[4], fb[2];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off32(wm * 128 + i * 32 + frag_row, ks * 2 + frag_half));
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off32(wn * 64 + j * 32 + frag_row, ks * 2 + frag_half));
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            }
+        }
+        __syncthreads();          // drains the redundant tail loads before LDS is reused by the epilogue
+    }
+
+    // ---- epilogue through LDS: per wavefront a [32][kStageLd2] fp32 staging block
+    float* stage = reinterpret_cast<float*>(smem) + wave * (32 * kStageLd2);
+    const int col_l = lane & 31, half = lane >> 5;
+    const int rd_row = lane >> 3, rd_col = (lane & 7) * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = 8 * (e >> 2) + 4 * half + (e & 3);
+                stage[row * kStageLd2 + j * 32 + col_l] = acc[i][j][e];
+            }
+        __syncthreads();
+#pragma unroll
+        for (int pss = 0; pss < 4; ++pss) {
+            const int row = pss * 8 + rd_row;
+            const int m = m0 + wm * 128 + i * 32 + row;
+            const int n = n0 + wn * 64 + rd_col;
+            if (m < M) {
+                float v[8];
+                const float4 x0 = *reinterpret_cast<const float4*>(stage + row * kStageLd2 + rd_col);
+                const float4 x1 = *reinterpret_cast<const float4*>(stage + row * kStageLd2 + rd_col + 4);
                 v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
                 if (splits > 1) {
                     Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
@@ -470,6 +662,44 @@ ds_status launch_mfma(int M, int N, int K, const void* A, const void* B, void* C
 }
 
 template <int EPI>
+ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, const GemmEpi& p, float* split_ws,
+                    size_t split_ws_floats, hipStream_t st) {
+    static bool attr_set = false;
+    auto kern = gemm_bf16_nt_kernel<EPI>;
+    const int smem = NT_NS * NT_STAGE;
+    if (!attr_set) {
+        DS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        attr_set = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    const int nt = K / NT_DK;
+    int splits = 1;
+    if (EPI == DS_EPI_ACC32 && split_ws) {
+        const int tiles = tiles_m * tiles_n;
+        if (tiles < 384) {
+            splits = (512 + tiles - 1) / tiles;
+            if (splits > 16) splits = 16;
+            if (splits > nt / 16) splits = nt / 16 > 0 ? nt / 16 : 1;
+            while (splits > 1 && (size_t)splits * M * N > split_ws_floats) --splits;
+            const int per = (nt + splits - 1) / splits;       // every split must own at least one K tile
+            splits = (nt + per - 1) / per;
+        }
+    }
+    const int total = tiles_m * tiles_n * splits;
+    hipLaunchKernelGGL(kern, dim3(total), dim3(512), smem, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C,
+                       tiles_m, tiles_n, splits, split_ws, p);
+    DS_LAUNCH_CHECK();
+    if (splits > 1) {
+        long long items = (long long)M * (N / 8);
+        long long g = (items + 255) / 256;
+        if (g > 8192) g = 8192;
+        hipLaunchKernelGGL(splitk_finish_kernel<EPI>, dim3((int)g), dim3(256), 0, st, M, N, splits, split_ws, (bf16_t*)C, p);
+        DS_LAUNCH_CHECK();
+    }
+    return DS_OK;
+}
+
+template <int EPI>
 ds_status dispatch_epi(int dtype, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C,
                        const GemmEpi& p, bool force_generic, float* split_ws, size_t split_ws_floats, hipStream_t st) {
     if (dtype == DS_DTYPE_BF16 && !force_generic) {
@@ -479,7 +709,7 @@ ds_status dispatch_epi(int dtype, int ta, int tb, int M, int N, int K, const voi
         const bool aligned = ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && ((uintptr_t)C % 16 == 0);
         if (ok_n && ok_a && ok_b && aligned && M >= 1 && K >= 1) {
             if (!ta && !tb) return launch_mfma<0, 0, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
-            if (!ta && tb) return launch_mfma<0, 1, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
+            if (!ta && tb) return launch_nt<EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
             if (ta && !tb) return launch_mfma<1, 0, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
         }
     }

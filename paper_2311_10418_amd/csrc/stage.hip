@@ -55,6 +55,7 @@ struct StreamTables {          // device tables of one token stream
 struct LayerBufs {
     void *u1, *qkv, *o, *x1, *u2, *z, *a, *xout;
     float *stats1, *stats2, *lse;
+    void *wqkv_t, *wo_t, *w1_t, *w2_t;      // [out][in] copies of the layer's matrices (bf16 fast path)
 };
 
 }  // namespace
@@ -76,6 +77,8 @@ struct ds_stage {
     void *x0 = nullptr, *dyA = nullptr, *dyB = nullptr, *dz = nullptr, *du = nullptr, *dx1 = nullptr, *d_o = nullptr,
          *dqkv = nullptr;
     float *delta = nullptr, *partial = nullptr, *split_ws = nullptr;
+    void *xt = nullptr, *dyt = nullptr;     // token-major -> feature-major copies for the weight-gradient GEMMs
+    bool nt_mode = false;
     size_t split_ws_floats = 0;
     int32_t launches = 0;
     // optional per-kernel-group timing
@@ -186,6 +189,39 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
                  const void* bias, const void* Rr, void* C2, bool mask, int acc) {
         return timed(s, cat, st, [&] { return gemm(s, ta, tb, M, N, K, A, B, C, epi, bias, Rr, nullptr, C2, mask, acc, st); });
     };
+    // bf16 fast path: every GEMM runs as C = A B^T with both operands contiguous along the contraction
+    // (the direct-to-LDS kernel).  Forward uses [out][in] copies of the weights made at the top of the
+    // call; a weight gradient dW[in][out] = X^T dY uses feature-major copies of X and dY whose token
+    // dimension is zero-padded to a multiple of 64.
+    const bool nt = s->nt_mode;
+    const int Rp = (R + 63) & ~63;
+    auto FWD = [&](int N, int K, const void* X, const void* W, const void* Wt, void* C, int epi, const void* bias,
+                   const void* Rr, void* C2, bool mask) {
+        if (nt) return G(DS_PROF_GEMM_FWD, 0, 1, R, N, K, X, Wt, C, epi, bias, Rr, C2, mask, 0);
+        return G(DS_PROF_GEMM_FWD, 0, 0, R, N, K, X, W, C, epi, bias, Rr, C2, mask, 0);
+    };
+    auto WGRAD = [&](int Kin, int Nout, const void* X, const void* dY, void* dW) {
+        if (!nt) return G(DS_PROF_GEMM_WGRAD, 1, 0, Kin, Nout, R, X, dY, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, false, accumulate);
+        return timed(s, DS_PROF_GEMM_WGRAD, st, [&] {
+            DS_TRY(launch_transpose_bf16(R, Kin, Rp, X, s->xt, st));
+            DS_TRY(launch_transpose_bf16(R, Nout, Rp, dY, s->dyt, st));
+            s->launches += 2;
+            return gemm(s, 0, 1, Kin, Nout, Rp, s->xt, s->dyt, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr, false, accumulate, st);
+        });
+    };
+    if (nt) {
+        DS_TRY(timed(s, DS_PROF_GEMM_FWD, st, [&] {
+            for (int l = 0; l < L; ++l) {
+                LayerBufs& b = s->layers[l];
+                DS_TRY(launch_transpose_bf16(d, 3 * d, d, w[l].w_qkv, b.wqkv_t, st));
+                DS_TRY(launch_transpose_bf16(d, d, d, w[l].w_o, b.wo_t, st));
+                DS_TRY(launch_transpose_bf16(d, F, d, w[l].w_1, b.w1_t, st));
+                DS_TRY(launch_transpose_bf16(F, d, F, w[l].w_2, b.w2_t, st));
+                s->launches += 4;
+            }
+            return DS_OK;
+        }));
+    }
     auto colsum = [&](int n, const void* x, void* out) {
         s->launches += 2;
         return timed(s, DS_PROF_COLSUM, st, [&] { return ds_colsum(dt, R, n, x, (float*)out, s->partial, accumulate, st); });
@@ -202,16 +238,16 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         LayerBufs& b = s->layers[l];
         void* x_out = (l == L - 1) ? io->act_out : b.xout;
         DS_TRY(timed(s, DS_PROF_NORM, st, [&] { return ds_norm_fwd(dt, 0, R, d, x_in, w[l].ln1_g, w[l].ln1_b, b.u1, b.stats1, st); }));
-        DS_TRY(G(DS_PROF_GEMM_FWD, 0, 0, R, 3 * d, d, b.u1, w[l].w_qkv, b.qkv, DS_EPI_NONE, w[l].b_qkv, nullptr, nullptr, false, 0));
+        DS_TRY(FWD(3 * d, d, b.u1, w[l].w_qkv, b.wqkv_t, b.qkv, DS_EPI_NONE, w[l].b_qkv, nullptr, nullptr, false));
         AttnArgs a = self_attn_args(s, b.qkv, 1);
         a.o = b.o;
         a.lse = b.lse;
         DS_TRY(timed(s, DS_PROF_ATTN_FWD, st, [&] { return launch_attention_fwd(a, false, st); }));
         DS_TRY(timed(s, DS_PROF_OTHER, st, [&] { return zero_pad_rows(s, b.o, d, st); }));
-        DS_TRY(G(DS_PROF_GEMM_FWD, 0, 0, R, d, d, b.o, w[l].w_o, b.x1, DS_EPI_RESID, w[l].b_o, x_in, nullptr, true, 0));
+        DS_TRY(FWD(d, d, b.o, w[l].w_o, b.wo_t, b.x1, DS_EPI_RESID, w[l].b_o, x_in, nullptr, true));
         DS_TRY(timed(s, DS_PROF_NORM, st, [&] { return ds_norm_fwd(dt, 0, R, d, b.x1, w[l].ln2_g, w[l].ln2_b, b.u2, b.stats2, st); }));
-        DS_TRY(G(DS_PROF_GEMM_FWD, 0, 0, R, F, d, b.u2, w[l].w_1, b.z, DS_EPI_GELU, w[l].b_1, nullptr, b.a, false, 0));
-        DS_TRY(G(DS_PROF_GEMM_FWD, 0, 0, R, d, F, b.a, w[l].w_2, x_out, DS_EPI_RESID, w[l].b_2, b.x1, nullptr, true, 0));
+        DS_TRY(FWD(F, d, b.u2, w[l].w_1, b.w1_t, b.z, DS_EPI_GELU, w[l].b_1, nullptr, b.a, false));
+        DS_TRY(FWD(d, F, b.a, w[l].w_2, b.w2_t, x_out, DS_EPI_RESID, w[l].b_2, b.x1, nullptr, true));
         s->launches += 3;
         x_in = x_out;
     }
@@ -230,10 +266,10 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         const void* xl_in = (l == 0) ? (pad ? s->x0 : io->act_in) : s->layers[l - 1].xout;
         void* dx_in = (l == 0) ? io->grad_in : pp[flip];
         // MLP
-        DS_TRY(G(DS_PROF_GEMM_WGRAD, 1, 0, F, d, R, b.a, dy, g[l].w_2, DS_EPI_ACC32, nullptr, nullptr, nullptr, false, accumulate));
+        DS_TRY(WGRAD(F, d, b.a, dy, g[l].w_2));
         DS_TRY(colsum(d, dy, g[l].b_2));
         DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, F, d, dy, w[l].w_2, s->dz, DS_EPI_DGELU, nullptr, b.z, nullptr, false, 0));
-        DS_TRY(G(DS_PROF_GEMM_WGRAD, 1, 0, d, F, R, b.u2, s->dz, g[l].w_1, DS_EPI_ACC32, nullptr, nullptr, nullptr, false, accumulate));
+        DS_TRY(WGRAD(d, F, b.u2, s->dz, g[l].w_1));
         DS_TRY(colsum(F, s->dz, g[l].b_1));
         DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, d, F, s->dz, w[l].w_1, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr, false, 0));
         DS_TRY(timed(s, DS_PROF_NORM, st, [&] {
@@ -241,7 +277,7 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
                                (float*)g[l].ln2_b, s->partial, accumulate, st);
         }));
         // attention
-        DS_TRY(G(DS_PROF_GEMM_WGRAD, 1, 0, d, d, R, b.o, s->dx1, g[l].w_o, DS_EPI_ACC32, nullptr, nullptr, nullptr, false, accumulate));
+        DS_TRY(WGRAD(d, d, b.o, s->dx1, g[l].w_o));
         DS_TRY(colsum(d, s->dx1, g[l].b_o));
         DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, d, d, s->dx1, w[l].w_o, s->d_o, DS_EPI_NONE, nullptr, nullptr, nullptr, false, 0));
         AttnArgs a = self_attn_args(s, b.qkv, 1);
@@ -255,7 +291,7 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         a.dv = dq + (size_t)2 * d * s->es;
         DS_TRY(timed(s, DS_PROF_ATTN_BWD, st, [&] { return launch_attention_bwd(a, false, st); }));
         DS_TRY(timed(s, DS_PROF_OTHER, st, [&] { return zero_pad_rows(s, s->dqkv, 3 * d, st); }));
-        DS_TRY(G(DS_PROF_GEMM_WGRAD, 1, 0, d, 3 * d, R, b.u1, s->dqkv, g[l].w_qkv, DS_EPI_ACC32, nullptr, nullptr, nullptr, false, accumulate));
+        DS_TRY(WGRAD(d, 3 * d, b.u1, s->dqkv, g[l].w_qkv));
         DS_TRY(colsum(3 * d, s->dqkv, g[l].b_qkv));
         DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, d, 3 * d, s->dqkv, w[l].w_qkv, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr, false, 0));
         DS_TRY(timed(s, DS_PROF_NORM, st, [&] {
@@ -302,6 +338,12 @@ extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out)
     need += al(s->split_ws_floats * 4);
     need += al(R * 4) + 2 * al((size_t)cfg->max_seqs * 4);
     need += 4096;
+    s->nt_mode = cfg->dtype == DS_DTYPE_BF16 && d % 256 == 0 && F % 256 == 0;
+    const size_t Rp = (R + 63) & ~size_t(63);
+    if (s->nt_mode) {
+        need += L * (al(3 * d * d * es) + al(d * d * es) + 2 * al(d * F * es));
+        need += al(std::max(d, F) * Rp * es) + al(std::max(3 * d, F) * Rp * es);
+    }
 
     if (hipMalloc(&s->ws, need) != hipSuccess) {
         (void)hipGetLastError();
@@ -331,6 +373,17 @@ extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out)
         b.stats1 = (float*)take(R * 2 * 4);
         b.stats2 = (float*)take(R * 2 * 4);
         b.lse = (float*)take(R * h * 4);
+        b.wqkv_t = b.wo_t = b.w1_t = b.w2_t = nullptr;
+        if (s->nt_mode) {
+            b.wqkv_t = take(3 * d * d * es);
+            b.wo_t = take(d * d * es);
+            b.w1_t = take(d * F * es);
+            b.w2_t = take(d * F * es);
+        }
+    }
+    if (s->nt_mode) {
+        s->xt = take(std::max(d, F) * Rp * es);
+        s->dyt = take(std::max(3 * d, F) * Rp * es);
     }
     s->x0 = take(R * d * es);
     s->dyA = take(R * d * es);
