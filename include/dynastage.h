@@ -262,17 +262,28 @@ ds_status ds_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, in
                   const void* R, const void* R2, void* C2, const int32_t* row_valid, int32_t accumulate,
                   int32_t force_generic, void* hip_stream);
 
+/* Bytes of DEVICE scratch the bf16 matrix-core attention kernels need (feature-major copies of V
+ * forward; of Q, dO and K backward).  q_total_rows / k_total_rows: rows of the tensors holding the
+ * queries / the keys. */
+int64_t ds_attention_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t q_total_rows, int32_t k_total_rows,
+                                   int32_t n_seq);
+
 /* Variable-length attention over a packed QKV-style tensor.
  * q, k, v: row-major with row strides ldq, ldk, ldv (elements); head h uses columns
  * h*head_dim .. of each.  Query sequence s occupies rows q_row[s] .. +q_len[s]-1 of q/o, its
  * keys rows k_row[s] .. +k_len[s]-1 of k/v.  mask: 0 = none (bidirectional / cross), 1 = causal.
  * o: [rows, n_heads*head_dim] with row stride ldo; lse: float32 [n_heads, lse_stride].
- * Rows not covered by any sequence are not touched.  q_row etc. are DEVICE int32 arrays. */
+ * Rows not covered by any sequence are not touched.  q_row etc. are DEVICE int32 arrays listing
+ * the sequences in ascending row order.  scratch (DEVICE, 16-byte aligned, at least
+ * ds_attention_scratch_bytes) enables the bf16 matrix-core kernels; with scratch = NULL, or a
+ * shape they do not take, the generic kernels run.  k_total_rows: rows of the k / v tensors (the
+ * q / o tensors have lse_stride rows). */
 ds_status ds_attention_fwd(int32_t dtype, int32_t n_seq, int32_t n_heads, int32_t head_dim, int32_t mask,
                            const int32_t* q_row, const int32_t* q_len, const int32_t* k_row, const int32_t* k_len,
                            int32_t max_q_len, int32_t max_k_len,
                            const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v, int32_t ldv,
                            void* o, int32_t ldo, float* lse, int32_t lse_stride,
+                           int32_t k_total_rows, void* scratch, int64_t scratch_bytes,
                            int32_t force_generic, void* hip_stream);
 /* Backward: given dO, O, LSE produce dQ, dK, dV (same strides as q, k, v).  delta: float32
  * scratch [n_heads, lse_stride]. */
@@ -282,6 +293,7 @@ ds_status ds_attention_bwd(int32_t dtype, int32_t n_seq, int32_t n_heads, int32_
                            const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v, int32_t ldv,
                            const void* o, const void* d_o, int32_t ldo, const float* lse, float* delta, int32_t lse_stride,
                            void* dq, void* dk, void* dv,
+                           int32_t k_total_rows, void* scratch, int64_t scratch_bytes,
                            int32_t force_generic, void* hip_stream);
 
 /* Row normalisation.  rms = 0: LayerNorm (gain g, bias b, eps 1e-5, stats = mean and rstd);

@@ -27,7 +27,7 @@ _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOM
 EXPORTS = ["dp_plan", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "stage_fwd_bwd",
            "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_attention_fwd",
-           "ds_attention_bwd", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
+           "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
            "ds_version"]
 
 
@@ -97,6 +97,7 @@ def lib():
         _lib.ds_version.restype = C.c_char_p
         _lib.ds_stage_workspace_bytes.restype = C.c_int64
         _lib.ds_norm_bwd_scratch_floats.restype = C.c_int64
+        _lib.ds_attention_scratch_bytes.restype = C.c_int64
         _lib.ds_layout_free.restype = None
         _lib.ds_stage_destroy.restype = None
     return _lib
@@ -301,24 +302,34 @@ def ds_gemm(A, B, Cout, M, N, K, trans_a=False, trans_b=False, epilogue=DS_EPI_N
 
 
 def ds_attention_fwd(q, k, v, o, lse, q_row, q_len, k_row, k_len, n_heads, head_dim, causal, max_q_len, max_k_len,
-                     ldq, ldk, ldv, ldo, lse_stride, force_generic=False, stream=None):
+                     ldq, ldk, ldv, ldo, lse_stride, k_total_rows=None, scratch=None, force_generic=False, stream=None):
     """q, k, v may be views into one QKV tensor: pass data pointers via tensors created with narrow()/select or ints."""
     rc = lib().ds_attention_fwd(C.c_int32(_dtype_code(o)), C.c_int32(q_row.shape[0]), C.c_int32(n_heads),
                                 C.c_int32(head_dim), C.c_int32(int(causal)), _dp(q_row), _dp(q_len), _dp(k_row), _dp(k_len),
                                 C.c_int32(max_q_len), C.c_int32(max_k_len), _dp(q), C.c_int32(ldq), _dp(k), C.c_int32(ldk),
                                 _dp(v), C.c_int32(ldv), _dp(o), C.c_int32(ldo), _dp(lse), C.c_int32(lse_stride),
+                                C.c_int32(k_total_rows if k_total_rows is not None else lse_stride), _dp(scratch),
+                                C.c_int64(scratch.numel() * scratch.element_size() if scratch is not None else 0),
                                 C.c_int32(int(force_generic)), _stream(stream))
     _check(rc, "ds_attention_fwd")
 
 
+def ds_attention_scratch_bytes(n_heads, head_dim, q_total_rows, k_total_rows, n_seq):
+    return lib().ds_attention_scratch_bytes(C.c_int32(n_heads), C.c_int32(head_dim), C.c_int32(q_total_rows),
+                                            C.c_int32(k_total_rows), C.c_int32(n_seq))
+
+
 def ds_attention_bwd(q, k, v, o, d_o, lse, delta, dq, dk, dv, q_row, q_len, k_row, k_len, n_heads, head_dim, causal,
-                     max_q_len, max_k_len, ldq, ldk, ldv, ldo, lse_stride, force_generic=False, stream=None):
+                     max_q_len, max_k_len, ldq, ldk, ldv, ldo, lse_stride, k_total_rows=None, scratch=None,
+                     force_generic=False, stream=None):
     rc = lib().ds_attention_bwd(C.c_int32(_dtype_code(o)), C.c_int32(q_row.shape[0]), C.c_int32(n_heads),
                                 C.c_int32(head_dim), C.c_int32(int(causal)), _dp(q_row), _dp(q_len), _dp(k_row), _dp(k_len),
                                 C.c_int32(max_q_len), C.c_int32(max_k_len), _dp(q), C.c_int32(ldq), _dp(k), C.c_int32(ldk),
                                 _dp(v), C.c_int32(ldv), _dp(o), _dp(d_o), C.c_int32(ldo), _dp(lse), _dp(delta),
-                                C.c_int32(lse_stride), _dp(dq), _dp(dk), _dp(dv), C.c_int32(int(force_generic)),
-                                _stream(stream))
+                                C.c_int32(lse_stride), _dp(dq), _dp(dk), _dp(dv),
+                                C.c_int32(k_total_rows if k_total_rows is not None else lse_stride), _dp(scratch),
+                                C.c_int64(scratch.numel() * scratch.element_size() if scratch is not None else 0),
+                                C.c_int32(int(force_generic)), _stream(stream))
     _check(rc, "ds_attention_bwd")
 
 

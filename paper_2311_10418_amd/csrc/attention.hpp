@@ -16,12 +16,17 @@ struct AttnArgs {
     long long lse_stride;
     void *dq, *dk, *dv;
     float scale;
-    // work lists for the MFMA kernels (DEVICE; NULL = derive from blockIdx)
-    const int32_t* fwd_work;                          // [n_fwd_work][2] = (sequence, query block)
-    int32_t n_fwd_work;
-    const int32_t* kv_work;                           // [n_kv_work][2] = (sequence, key block)
-    int32_t n_kv_work;
+    // MFMA path: scratch for feature-major copies (V^T forward; Q^T, dO^T, K^T backward); the
+    // sequence tables must list sequences in ascending row order
+    void* scratch;
+    size_t scratch_bytes;
+    int32_t q_total_rows, k_total_rows;               // rows of the query-side / key-side streams
+    const void *qT, *kT, *vT, *doT;                   // filled by the launchers
+    long long ldTq, ldTk;
 };
+
+long long attn_ld_t(int total_rows, int n_seq);
+size_t attn_scratch_bytes(int n_heads, int head_dim, int q_total_rows, int k_total_rows, int n_seq);
 
 ds_status attn_fwd_generic(const AttnArgs& a, hipStream_t st);
 ds_status attn_bwd_generic(const AttnArgs& a, hipStream_t st);

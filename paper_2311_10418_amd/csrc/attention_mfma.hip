@@ -1,23 +1,29 @@
 // bf16 variable-length attention on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16),
 // head_dim 64 or 128, causal or unmasked (bidirectional / cross), forward and backward.
 //
-// Layout idea (all three kernels).  A wavefront owns 32 "column" items (queries in forward and
-// dQ, keys in dK/dV) and keeps them in the MFMA B operand, so that the score tile it computes
-// is TRANSPOSED: lane l holds column l%32 and 16 of the 32 rows.  Everything that is per
-// column (running max, running sum, log-sum-exp, delta, the rescale of the output accumulator)
-// is then a per-lane scalar, and row reductions are in-lane plus one exchange between lanes l
-// and l^32.  The probabilities leave the accumulator registers as the B operand of the second
-// product without any data movement: accumulator registers 8u..8u+7 of a tile ARE a valid
-// 16-deep B fragment provided the A operand lists the contraction index in the matching order,
-//     slot j of lane-half g  <->  row 16t + 8*(j/4) + 4*g + j%4           (t = 16-row step)
-// so the transposed operand tiles (V^T, K^T, Q^T, dO^T) are written to LDS in that slot order
-// by a loader that transposes 8x8 bf16 blocks in registers (v_perm_b32).
+// Register layout (all three kernels).  A wavefront owns 32 "column" items (queries in forward and
+// dQ, keys in dK/dV) and keeps them in the MFMA B operand, so that the score tile it computes is
+// TRANSPOSED: lane l holds column l%32 and 16 of the 32 rows.  Everything that is per column
+// (running max, running sum, log-sum-exp, delta, the rescale of the output accumulator) is then a
+// per-lane scalar, and row reductions are in-lane plus one exchange between lanes l and l^32.  The
+// probabilities leave the accumulator registers as the B operand of the second product without any
+// data movement: accumulator registers 8u..8u+7 of a tile ARE a valid 16-deep B fragment provided
+// the A operand lists the contraction index in the matching order,
+//     slot j of lane-half g  <->  row 16t + 8*(j/4) + 4*g + j%4           (t = 16-row step).
 //
-// K/V (forward, dQ) or Q/dO (dK/dV) tiles of 64 rows are staged in LDS with a 16-byte XOR
-// swizzle: conflict-free 16-byte fragment reads.  Backward is split into a dQ kernel and a
-// dK/dV kernel so that every output element has one owner: no atomics, results are
-// bit-reproducible.  Sequences are addressed through the (row, length) tables, so padding rows
-// cost nothing, and packed layouts (several sequences in one padded row) need no mask.
+// Memory layout.  The second product needs its A operand transposed (V^T, K^T, Q^T, dO^T).  A
+// helper kernel (seq_transpose) writes feature-major copies of those tensors once per call, each
+// sequence padded with zeros to a multiple of 64 tokens and the 64 tokens of a tile stored in the
+// slot order above, so that one 16-byte LDS read yields a whole A fragment.  With that, EVERY tile
+// an attention kernel consumes is a set of 16-byte-aligned contiguous row segments and goes
+// global -> LDS directly (global_load_lds_dwordx4): no staging registers, double-buffered, the next
+// 64-row block in flight while the current one feeds the MFMAs.  LDS tiles carry a 16-byte XOR
+// swizzle (chosen per lane at load time) that makes the 16-byte fragment reads conflict-free on
+// gfx950's 64-bank LDS.
+//
+// Backward is split into a dQ kernel and a dK/dV kernel so that every output element has one
+// owner: no atomics, results are bit-reproducible.  Sequences are addressed through (row, length)
+// tables, so padding rows cost nothing and packed layouts need no mask.
 #include "attention.hpp"
 
 namespace {
@@ -38,49 +44,6 @@ __device__ __forceinline__ int slot_row(int t, int g, int j) { return 16 * t + 8
 
 __device__ __forceinline__ uint32_t pick4(const uint4& v, int w) {
     return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w));
-}
-
-// 64 rows x HD columns, rows row0.. of a tensor with leading dimension ld, clamped to the last valid row.
-template <int HD>
-__device__ __forceinline__ void load_rows(char* __restrict__ lds, const bf16_t* __restrict__ base, long long ld, int row0,
-                                          int n_valid, int tid) {
-    constexpr int CH = HD / 8;
-#pragma unroll
-    for (int c = tid; c < 64 * CH; c += 256) {
-        const int row = c / CH, chunk = c % CH;
-        int r = row0 + row;
-        r = r < n_valid ? r : n_valid - 1;
-        *reinterpret_cast<uint4*>(lds + off_rows<HD>(row, chunk)) =
-            *reinterpret_cast<const uint4*>(base + (long long)r * ld + chunk * 8);
-    }
-}
-
-// The same 64 x HD block, transposed into [HD][64 slots] with the slot order of the header comment.
-template <int HD>
-__device__ __forceinline__ void load_rows_transposed(char* __restrict__ lds, const bf16_t* __restrict__ base, long long ld,
-                                                     int row0, int n_valid, int tid) {
-    constexpr int CH = HD / 8;
-    for (int bi = tid; bi < 8 * CH; bi += 256) {
-        const int kg = bi & 7, dc = bi >> 3;
-        const int t = kg >> 1, g = kg & 1;
-        uint4 r[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            int row = row0 + slot_row(t, g, j);
-            row = row < n_valid ? row : n_valid - 1;
-            r[j] = *reinterpret_cast<const uint4*>(base + (long long)row * ld + dc * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            uint4 o;
-            const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-            o.x = __builtin_amdgcn_perm(pick4(r[1], i >> 1), pick4(r[0], i >> 1), sel);
-            o.y = __builtin_amdgcn_perm(pick4(r[3], i >> 1), pick4(r[2], i >> 1), sel);
-            o.z = __builtin_amdgcn_perm(pick4(r[5], i >> 1), pick4(r[4], i >> 1), sel);
-            o.w = __builtin_amdgcn_perm(pick4(r[7], i >> 1), pick4(r[6], i >> 1), sel);
-            *reinterpret_cast<uint4*>(lds + off_tr(dc * 8 + i, kg)) = o;
-        }
-    }
 }
 
 // accumulator registers 8u..8u+7 of a 32x32 tile -> one bf16 B fragment
@@ -105,20 +68,108 @@ __device__ __forceinline__ void store_cols(const f32x16_t (&acc)[HD / 32], float
         }
 }
 
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// column of sequence s in a feature-major (transposed) copy; `row` is the sequence's first stream row
+__device__ __forceinline__ long long tcol(int row, int s) { return (long long)((row + 63) & ~63) + 128LL * s; }
+
+// ------------------------------------------------------------------------------------ seq_transpose
+// out[c][tcol(s) + 64*tile + p] = in[row_s + 64*tile + slot_row(p)][c]  (zero beyond the sequence's
+// length, up to the end of its last 64-token tile), for c in [0, C).  One work-group: 64 tokens x
+// 256 features; each lane loads 8 token rows x 16 bytes, transposes 8x8 in registers, stores 8
+// feature rows x 16 bytes; loads and stores form 128-byte contiguous segments.
+__global__ __launch_bounds__(256) void seq_transpose_kernel(int C, const int32_t* __restrict__ seq_row,
+                                                            const int32_t* __restrict__ seq_len,
+                                                            const bf16_t* __restrict__ in, long long ld_in,
+                                                            bf16_t* __restrict__ out, long long ld_out) {
+    const int s = blockIdx.z, tile = blockIdx.y;
+    const int len = seq_len[s];
+    if (tile * 64 >= len) return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int bx = lane & 7, by = lane >> 3;
+    const int c0 = blockIdx.x * 256 + wave * 64 + bx * 8;
+    if (c0 >= C) return;
+    const int row0 = seq_row[s];
+    const int t = by >> 1, g = by & 1;
+    uint32_t v[8][4];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int q = tile * 64 + slot_row(t, g, j);
+        uint4 x = make_uint4(0u, 0u, 0u, 0u);
+        if (q < len) x = *reinterpret_cast<const uint4*>(in + (long long)(row0 + q) * ld_in + c0);
+        v[j][0] = x.x; v[j][1] = x.y; v[j][2] = x.z; v[j][3] = x.w;
+    }
+    bf16_t* o = out + tcol(row0, s) + tile * 64 + by * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+        const int w = i >> 1;
+        uint4 r;
+        r.x = __builtin_amdgcn_perm(v[1][w], v[0][w], sel);
+        r.y = __builtin_amdgcn_perm(v[3][w], v[2][w], sel);
+        r.z = __builtin_amdgcn_perm(v[5][w], v[4][w], sel);
+        r.w = __builtin_amdgcn_perm(v[7][w], v[6][w], sel);
+        *reinterpret_cast<uint4*>(o + (long long)(c0 + i) * ld_out) = r;
+    }
+}
+
+// ------------------------------------------------------------------------------------ direct-to-LDS tile loads
+// Token-major tile: 64 rows (row0.., clamped to the last valid row) x HD columns of a row-major tensor.
+template <int HD>
+__device__ __forceinline__ void issue_rows(char* __restrict__ lds, const bf16_t* __restrict__ base, long long ld, int row0,
+                                           int n_valid, int wave, int lane) {
+    constexpr int PER_WAVE = HD / 32;                 // wavefront instructions (1 KB each) per wavefront
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+        const int u = (wave * PER_WAVE + i) * 64 + lane;
+        int row, chunk;
+        if (HD == 128) { row = u >> 4; chunk = (u & 15) ^ (row & 15); }
+        else           { row = u >> 3; chunk = (u & 7) ^ ((row >> 1) & 7); }
+        int r = row0 + row;
+        r = r < n_valid ? r : n_valid - 1;
+        __builtin_amdgcn_global_load_lds((gptr_t)(base + (long long)r * ld + chunk * 8),
+                                         (lptr_t)(lds + (wave * PER_WAVE + i) * 1024), 16, 0, 0);
+    }
+}
+// Feature-major tile: HD rows x 64 tokens (already padded and slot-ordered by seq_transpose).
+template <int HD>
+__device__ __forceinline__ void issue_cols(char* __restrict__ lds, const bf16_t* __restrict__ base_t, long long ld_t,
+                                           long long col0, int wave, int lane) {
+    constexpr int PER_WAVE = HD / 32;
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+        const int u = (wave * PER_WAVE + i) * 64 + lane;
+        const int d = u >> 3;
+        const int chunk = (u & 7) ^ ((d >> 1) & 7);
+        __builtin_amdgcn_global_load_lds((gptr_t)(base_t + (long long)d * ld_t + col0 + chunk * 8),
+                                         (lptr_t)(lds + (wave * PER_WAVE + i) * 1024), 16, 0, 0);
+    }
+}
+
+// wait for this wavefront's outstanding direct loads, then for everybody's
+__device__ __forceinline__ void wait_tiles_and_sync() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
+    __builtin_amdgcn_s_barrier();
+}
+
 // ------------------------------------------------------------------------------------ forward
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnArgs a) {
-    __shared__ __attribute__((aligned(16))) char sK[64 * HD * 2];
-    __shared__ __attribute__((aligned(16))) char sVt[HD * 128];
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int TILE = 64 * HD * 2;                  // bytes of one K tile == one V^T tile
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, g = lane >> 5;
     const int s = a.n_seq - 1 - blockIdx.z, h = blockIdx.y;
     const int ql = a.q_len[s], kl = a.k_len[s];
     const int q0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * 128;
     if (q0 >= ql) return;
+    const int krow = a.k_row[s];
     const bf16_t* Q = (const bf16_t*)a.q + (long long)a.q_row[s] * a.ldq + h * HD;
-    const bf16_t* K = (const bf16_t*)a.k + (long long)a.k_row[s] * a.ldk + h * HD;
-    const bf16_t* V = (const bf16_t*)a.v + (long long)a.k_row[s] * a.ldv + h * HD;
+    const bf16_t* K = (const bf16_t*)a.k + (long long)krow * a.ldk + h * HD;
+    const bf16_t* Vt = (const bf16_t*)a.vT + (long long)h * HD * a.ldTk;
+    const long long kcol = tcol(krow, s);
     const int qw0 = q0 + wave * 32;
     const int qi = qw0 + col;
     const int qi_c = qi < ql ? qi : ql - 1;
@@ -138,11 +189,19 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnArgs a) {
 
     const int kv_end = CAUSAL ? min(kl, q0 + 128) : kl;
     const int wave_last = CAUSAL ? min(kl - 1, qw0 + 31) : kl - 1;     // last key this wavefront can see
-    for (int kv0 = 0; kv0 < kv_end; kv0 += 64) {
-        __syncthreads();
-        load_rows<HD>(sK, K, a.ldk, kv0, kl, tid);
-        load_rows_transposed<HD>(sVt, V, a.ldv, kv0, kl, tid);
-        __syncthreads();
+    const int nb = (kv_end + 63) / 64;
+    issue_rows<HD>(smem, K, a.ldk, 0, kl, wave, lane);
+    issue_cols<HD>(smem + TILE, Vt, a.ldTk, kcol, wave, lane);
+    for (int b = 0; b < nb; ++b) {
+        const int kv0 = b * 64;
+        char* sK = smem + (b & 1) * (2 * TILE);
+        char* sVt = sK + TILE;
+        wait_tiles_and_sync();                          // block b has landed; the other stage is free
+        if (b + 1 < nb) {
+            char* nK = smem + ((b + 1) & 1) * (2 * TILE);
+            issue_rows<HD>(nK, K, a.ldk, kv0 + 64, kl, wave, lane);
+            issue_cols<HD>(nK + TILE, Vt, a.ldTk, kcol + kv0 + 64, wave, lane);
+        }
         if (kv0 > wave_last || qw0 >= ql) continue;
 
         f32x16_t sacc[2];
@@ -210,9 +269,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnArgs a) {
 // ------------------------------------------------------------------------------------ backward: dQ
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
-    __shared__ __attribute__((aligned(16))) char sK[64 * HD * 2];
-    __shared__ __attribute__((aligned(16))) char sV[64 * HD * 2];
-    __shared__ __attribute__((aligned(16))) char sKt[HD * 128];
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int TILE = 64 * HD * 2;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, g = lane >> 5;
     const int s = a.n_seq - 1 - blockIdx.z, h = blockIdx.y;
@@ -220,10 +278,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
     const int q0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * 128;
     if (q0 >= ql) return;
     const long long qrow0 = a.q_row[s];
+    const int krow = a.k_row[s];
     const bf16_t* Q = (const bf16_t*)a.q + qrow0 * a.ldq + h * HD;
     const bf16_t* dO = (const bf16_t*)a.d_o + qrow0 * a.ldo + h * HD;
-    const bf16_t* K = (const bf16_t*)a.k + (long long)a.k_row[s] * a.ldk + h * HD;
-    const bf16_t* V = (const bf16_t*)a.v + (long long)a.k_row[s] * a.ldv + h * HD;
+    const bf16_t* K = (const bf16_t*)a.k + (long long)krow * a.ldk + h * HD;
+    const bf16_t* V = (const bf16_t*)a.v + (long long)krow * a.ldv + h * HD;
+    const bf16_t* Kt = (const bf16_t*)a.kT + (long long)h * HD * a.ldTk;
+    const long long kcol = tcol(krow, s);
     const int qw0 = q0 + wave * 32;
     const int qi = qw0 + col;
     const int qi_c = qi < ql ? qi : ql - 1;
@@ -246,12 +307,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
 
     const int kv_end = CAUSAL ? min(kl, q0 + 128) : kl;
     const int wave_last = CAUSAL ? min(kl - 1, qw0 + 31) : kl - 1;
-    for (int kv0 = 0; kv0 < kv_end; kv0 += 64) {
-        __syncthreads();
-        load_rows<HD>(sK, K, a.ldk, kv0, kl, tid);
-        load_rows<HD>(sV, V, a.ldv, kv0, kl, tid);
-        load_rows_transposed<HD>(sKt, K, a.ldk, kv0, kl, tid);
-        __syncthreads();
+    const int nb = (kv_end + 63) / 64;
+    issue_rows<HD>(smem, K, a.ldk, 0, kl, wave, lane);
+    issue_rows<HD>(smem + TILE, V, a.ldv, 0, kl, wave, lane);
+    issue_cols<HD>(smem + 2 * TILE, Kt, a.ldTk, kcol, wave, lane);
+    for (int b = 0; b < nb; ++b) {
+        const int kv0 = b * 64;
+        char* sK = smem + (b & 1) * (3 * TILE);
+        char* sV = sK + TILE;
+        char* sKt = sV + TILE;
+        wait_tiles_and_sync();
+        if (b + 1 < nb) {
+            char* n = smem + ((b + 1) & 1) * (3 * TILE);
+            issue_rows<HD>(n, K, a.ldk, kv0 + 64, kl, wave, lane);
+            issue_rows<HD>(n + TILE, V, a.ldv, kv0 + 64, kl, wave, lane);
+            issue_cols<HD>(n + 2 * TILE, Kt, a.ldTk, kcol + kv0 + 64, wave, lane);
+        }
         if (kv0 > wave_last || qw0 >= ql) continue;
 
         f32x16_t sacc[2], pacc[2];
@@ -296,25 +367,25 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
 // ------------------------------------------------------------------------------------ backward: dK, dV
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
-    // dynamic LDS: Q, dO ([64][HD]), Q^T, dO^T ([HD][64 slots]), then 64 log-sum-exp and 64 delta values
-    extern __shared__ __attribute__((aligned(16))) char dkv_smem[];
-    char* sQ = dkv_smem;
-    char* sdO = sQ + 64 * HD * 2;
-    char* sQt = sdO + 64 * HD * 2;
-    char* sdOt = sQt + HD * 128;
-    float* s_lse = reinterpret_cast<float*>(sdOt + HD * 128);
-    float* s_delta = s_lse + 64;
+    // dynamic LDS, two stages of: Q, dO ([64][HD]), Q^T, dO^T ([HD][64 slots]); then 2 x (64 lse + 64 delta)
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int TILE = 64 * HD * 2;
+    float* s_stat = reinterpret_cast<float*>(smem + 8 * TILE);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, g = lane >> 5;
     const int s = a.n_seq - 1 - blockIdx.z, h = blockIdx.y;
     const int ql = a.q_len[s], kl = a.k_len[s];
     const int k0 = blockIdx.x * 128;
     if (k0 >= kl) return;
-    const long long qrow0 = a.q_row[s], krow0 = a.k_row[s];
+    const int qrow = a.q_row[s];
+    const long long qrow0 = qrow, krow0 = a.k_row[s];
     const bf16_t* Q = (const bf16_t*)a.q + qrow0 * a.ldq + h * HD;
     const bf16_t* dO = (const bf16_t*)a.d_o + qrow0 * a.ldo + h * HD;
     const bf16_t* K = (const bf16_t*)a.k + krow0 * a.ldk + h * HD;
     const bf16_t* V = (const bf16_t*)a.v + krow0 * a.ldv + h * HD;
+    const bf16_t* Qt = (const bf16_t*)a.qT + (long long)h * HD * a.ldTq;
+    const bf16_t* dOt = (const bf16_t*)a.doT + (long long)h * HD * a.ldTq;
+    const long long qcol = tcol(qrow, s);
     const int kw0 = k0 + wave * 32;
     const int ki = kw0 + col;
     const int ki_c = ki < kl ? ki : kl - 1;
@@ -333,19 +404,44 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
         for (int e = 0; e < 16; ++e) { dkacc[dt][e] = 0.f; dvacc[dt][e] = 0.f; }
 
     const int q_begin = CAUSAL ? (k0 / 64) * 64 : 0;
-    for (int q0 = q_begin; q0 < ql; q0 += 64) {
-        __syncthreads();
-        load_rows<HD>(sQ, Q, a.ldq, q0, ql, tid);
-        load_rows<HD>(sdO, dO, a.ldo, q0, ql, tid);
-        load_rows_transposed<HD>(sQt, Q, a.ldq, q0, ql, tid);
-        load_rows_transposed<HD>(sdOt, dO, a.ldo, q0, ql, tid);
+    const int nb = (ql - q_begin + 63) / 64;
+    const float* lse_row = a.lse + (size_t)h * a.lse_stride + qrow0;
+    const float* delta_row = a.delta + (size_t)h * a.lse_stride + qrow0;
+    auto issue_block = [&](int b) {
+        const int q0 = q_begin + b * 64;
+        char* n = smem + (b & 1) * (4 * TILE);
+        issue_rows<HD>(n, Q, a.ldq, q0, ql, wave, lane);
+        issue_rows<HD>(n + TILE, dO, a.ldo, q0, ql, wave, lane);
+        issue_cols<HD>(n + 2 * TILE, Qt, a.ldTq, qcol + q0, wave, lane);
+        issue_cols<HD>(n + 3 * TILE, dOt, a.ldTq, qcol + q0, wave, lane);
+    };
+    auto load_stats = [&](int b, float& l, float& dl) {
         if (tid < 64) {
-            int r = q0 + tid;
+            int r = q_begin + b * 64 + tid;
             r = r < ql ? r : ql - 1;
-            s_lse[tid] = a.lse[(size_t)h * a.lse_stride + qrow0 + r] * kLog2e;
-            s_delta[tid] = a.delta[(size_t)h * a.lse_stride + qrow0 + r];
+            l = lse_row[r] * kLog2e;
+            dl = delta_row[r];
         }
-        __syncthreads();
+    };
+    float st_l = 0.f, st_d = 0.f;
+    issue_block(0);
+    load_stats(0, st_l, st_d);
+    for (int b = 0; b < nb; ++b) {
+        const int q0 = q_begin + b * 64;
+        char* sQ = smem + (b & 1) * (4 * TILE);
+        char* sdO = sQ + TILE;
+        char* sQt = sdO + TILE;
+        char* sdOt = sQt + TILE;
+        float* s_lse = s_stat + (b & 1) * 128;
+        float* s_delta = s_lse + 64;
+        __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this block's tiles and statistics have landed
+        if (tid < 64) { s_lse[tid] = st_l; s_delta[tid] = st_d; }
+        __builtin_amdgcn_s_waitcnt(0xC07F);             // lgkmcnt(0): the statistics are in LDS
+        __builtin_amdgcn_s_barrier();
+        if (b + 1 < nb) {
+            issue_block(b + 1);
+            load_stats(b + 1, st_l, st_d);
+        }
         if (kw0 >= kl || (CAUSAL && q0 + 63 < kw0)) continue;
 
         f32x16_t sacc[2], pacc[2];
@@ -395,33 +491,66 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
     }
 }
 
+ds_status seq_transpose(int C, int n_seq, int max_len, const int32_t* row, const int32_t* len, const void* in, long long ld_in,
+                        void* out, long long ld_out, hipStream_t st) {
+    dim3 grid((C + 255) / 256, (max_len + 63) / 64, n_seq);
+    hipLaunchKernelGGL(seq_transpose_kernel, grid, dim3(256), 0, st, C, row, len, (const bf16_t*)in, ld_in, (bf16_t*)out, ld_out);
+    DS_LAUNCH_CHECK();
+    return DS_OK;
+}
+
+template <class Kern>
+ds_status set_smem(Kern kern, int bytes, bool& done) {
+    if (!done) {
+        DS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+        done = true;
+    }
+    return DS_OK;
+}
+
 template <int HD, bool CAUSAL>
 ds_status fwd_launch(const AttnArgs& a, hipStream_t st) {
+    static bool attr = false;
+    auto kern = attn_fwd_mfma_kernel<HD, CAUSAL>;
+    const int smem = 4 * (64 * HD * 2);
+    ds_status r = set_smem(kern, smem, attr);
+    if (r != DS_OK) return r;
     dim3 grid((a.max_q_len + 127) / 128, a.n_heads, a.n_seq);
-    hipLaunchKernelGGL((attn_fwd_mfma_kernel<HD, CAUSAL>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, a);
     DS_LAUNCH_CHECK();
     return DS_OK;
 }
 
 template <int HD, bool CAUSAL>
 ds_status bwd_launch(const AttnArgs& a, hipStream_t st) {
-    static bool attr_set = false;
-    auto kern = attn_bwd_dkv_mfma_kernel<HD, CAUSAL>;
-    const int smem = 2 * (64 * HD * 2) + 2 * (HD * 128) + 128 * 4;
-    if (!attr_set) {
-        DS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-        attr_set = true;
-    }
+    static bool attr_q = false, attr_kv = false;
+    auto kq = attn_bwd_dq_mfma_kernel<HD, CAUSAL>;
+    auto kkv = attn_bwd_dkv_mfma_kernel<HD, CAUSAL>;
+    const int smem_q = 6 * (64 * HD * 2);
+    const int smem_kv = 8 * (64 * HD * 2) + 256 * 4;
+    ds_status r = set_smem(kq, smem_q, attr_q);
+    if (r != DS_OK) return r;
+    r = set_smem(kkv, smem_kv, attr_kv);
+    if (r != DS_OK) return r;
     dim3 gq((a.max_q_len + 127) / 128, a.n_heads, a.n_seq);
-    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<HD, CAUSAL>), gq, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(kq, gq, dim3(256), smem_q, st, a);
     DS_LAUNCH_CHECK();
     dim3 gk((a.max_k_len + 127) / 128, a.n_heads, a.n_seq);
-    hipLaunchKernelGGL(kern, gk, dim3(256), smem, st, a);
+    hipLaunchKernelGGL(kkv, gk, dim3(256), smem_kv, st, a);
     DS_LAUNCH_CHECK();
     return DS_OK;
 }
 
 }  // namespace
+
+// Leading dimension (in tokens) of a feature-major copy of a stream of `total_rows` rows holding n_seq sequences.
+long long attn_ld_t(int total_rows, int n_seq) { return (long long)((total_rows + 63) & ~63) + 128LL * n_seq + 64; }
+
+size_t attn_scratch_bytes(int n_heads, int head_dim, int q_total_rows, int k_total_rows, int n_seq) {
+    const size_t d = (size_t)n_heads * head_dim;
+    // forward needs V^T; backward needs Q^T, dO^T (query side) and K^T (key side)
+    return 2 * d * (size_t)attn_ld_t(q_total_rows, n_seq) * 2 + d * (size_t)attn_ld_t(k_total_rows, n_seq) * 2 + 1024;
+}
 
 bool attn_mfma_supported(const AttnArgs& a) {
     if (a.dtype != DS_DTYPE_BF16) return false;
@@ -430,15 +559,38 @@ bool attn_mfma_supported(const AttnArgs& a) {
     auto al = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
     if (!al(a.q) || !al(a.k) || !al(a.v) || !al(a.o)) return false;
     if (a.d_o && (!al(a.d_o) || !al(a.dq) || !al(a.dk) || !al(a.dv))) return false;
+    if (!a.scratch || !al(a.scratch)) return false;
+    if (a.q_total_rows <= 0 || a.k_total_rows <= 0) return false;
+    if (a.scratch_bytes < attn_scratch_bytes(a.n_heads, a.head_dim, a.q_total_rows, a.k_total_rows, a.n_seq)) return false;
     return true;
 }
 
-ds_status attn_fwd_mfma(const AttnArgs& a, hipStream_t st) {
+ds_status attn_fwd_mfma(const AttnArgs& a0, hipStream_t st) {
+    AttnArgs a = a0;
+    const int d = a.n_heads * a.head_dim;
+    a.ldTk = attn_ld_t(a.k_total_rows, a.n_seq);
+    a.vT = a.scratch;
+    ds_status r = seq_transpose(d, a.n_seq, a.max_k_len, a.k_row, a.k_len, a.v, a.ldv, a.scratch, a.ldTk, st);
+    if (r != DS_OK) return r;
     if (a.head_dim == 128) return a.mask ? fwd_launch<128, true>(a, st) : fwd_launch<128, false>(a, st);
     return a.mask ? fwd_launch<64, true>(a, st) : fwd_launch<64, false>(a, st);
 }
 
-ds_status attn_bwd_mfma(const AttnArgs& a, hipStream_t st) {
+ds_status attn_bwd_mfma(const AttnArgs& a0, hipStream_t st) {
+    AttnArgs a = a0;
+    const size_t d = (size_t)a.n_heads * a.head_dim;
+    a.ldTq = attn_ld_t(a.q_total_rows, a.n_seq);
+    a.ldTk = attn_ld_t(a.k_total_rows, a.n_seq);
+    char* base = (char*)a.scratch;
+    a.qT = base;
+    a.doT = base + d * a.ldTq * 2;
+    a.kT = base + 2 * d * a.ldTq * 2;
+    ds_status r = seq_transpose((int)d, a.n_seq, a.max_q_len, a.q_row, a.q_len, a.q, a.ldq, (void*)a.qT, a.ldTq, st);
+    if (r != DS_OK) return r;
+    r = seq_transpose((int)d, a.n_seq, a.max_q_len, a.q_row, a.q_len, a.d_o, a.ldo, (void*)a.doT, a.ldTq, st);
+    if (r != DS_OK) return r;
+    r = seq_transpose((int)d, a.n_seq, a.max_k_len, a.k_row, a.k_len, a.k, a.ldk, (void*)a.kT, a.ldTk, st);
+    if (r != DS_OK) return r;
     if (a.head_dim == 128) return a.mask ? bwd_launch<128, true>(a, st) : bwd_launch<128, false>(a, st);
     return a.mask ? bwd_launch<64, true>(a, st) : bwd_launch<64, false>(a, st);
 }

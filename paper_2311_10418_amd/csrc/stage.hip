@@ -78,6 +78,8 @@ struct ds_stage {
          *dqkv = nullptr;
     float *delta = nullptr, *partial = nullptr, *split_ws = nullptr;
     void *xt = nullptr, *dyt = nullptr;     // token-major -> feature-major copies for the weight-gradient GEMMs
+    void* attn_scratch = nullptr;           // feature-major copies for the attention kernels
+    size_t attn_scratch_bytes = 0;
     bool nt_mode = false;
     size_t split_ws_floats = 0;
     int32_t launches = 0;
@@ -164,6 +166,9 @@ AttnArgs self_attn_args(ds_stage* s, const void* qkv, int mask) {
     a.ldo = d;
     a.lse_stride = s->bound_rows;
     a.scale = 1.0f / std::sqrt((float)hd);
+    a.scratch = s->attn_scratch;
+    a.scratch_bytes = s->attn_scratch_bytes;
+    a.q_total_rows = a.k_total_rows = s->bound_rows;
     return a;
 }
 
@@ -340,6 +345,10 @@ extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out)
     need += 4096;
     s->nt_mode = cfg->dtype == DS_DTYPE_BF16 && d % 256 == 0 && F % 256 == 0;
     const size_t Rp = (R + 63) & ~size_t(63);
+    if (cfg->dtype == DS_DTYPE_BF16 && (hd == 64 || hd == 128)) {
+        s->attn_scratch_bytes = attn_scratch_bytes(cfg->n_heads, hd, cfg->max_rows, cfg->max_rows, cfg->max_seqs);
+        need += al(s->attn_scratch_bytes);
+    }
     if (s->nt_mode) {
         need += L * (al(3 * d * d * es) + al(d * d * es) + 2 * al(d * F * es));
         need += al(std::max(d, F) * Rp * es) + al(std::max(3 * d, F) * Rp * es);
@@ -381,6 +390,7 @@ extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out)
             b.w2_t = take(d * F * es);
         }
     }
+    if (s->attn_scratch_bytes) s->attn_scratch = take(s->attn_scratch_bytes);
     if (s->nt_mode) {
         s->xt = take(std::max(d, F) * Rp * es);
         s->dyt = take(std::max(3 * d, F) * Rp * es);

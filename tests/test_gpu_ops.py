@@ -120,14 +120,15 @@ def test_attention_self(dt, force, hd, causal):
     ddo = to_dev(d_o, dt)
     t_rows = torch.from_numpy(rows).to(DEV)
     t_lens = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    scratch = torch.zeros(ds.ds_attention_scratch_bytes(h, hd, T, T, len(lens)), dtype=torch.uint8, device=DEV)
     es = dq.element_size()
     base = dq.data_ptr()
     ds.ds_attention_fwd(base, base + d * es, base + 2 * d * es, o, lse, t_rows, t_lens, t_rows, t_lens, h, hd, causal,
-                        max(lens), max(lens), 3 * d, 3 * d, 3 * d, d, T, force_generic=force)
+                        max(lens), max(lens), 3 * d, 3 * d, 3 * d, d, T, scratch=scratch, force_generic=force)
     gb = dqkv.data_ptr()
     ds.ds_attention_bwd(base, base + d * es, base + 2 * d * es, o, ddo, lse, delta, gb, gb + d * es, gb + 2 * d * es,
                         t_rows, t_lens, t_rows, t_lens, h, hd, causal, max(lens), max(lens), 3 * d, 3 * d, 3 * d, d, T,
-                        force_generic=force)
+                        scratch=scratch, force_generic=force)
     torch.cuda.synchronize()
     o_np, g_np, lse_np = to_np(o), to_np(dqkv), to_np(lse)
     tol = TOL[dt]
@@ -171,11 +172,12 @@ def test_attention_cross(dt, force):
     i32 = lambda a: torch.tensor(np.asarray(a), dtype=torch.int32, device=DEV)
     t_qr, t_ql, t_kr, t_kl = i32(qr), i32(ql), i32(kr), i32(kl)
     kb = tkv.data_ptr()
+    scratch = torch.zeros(ds.ds_attention_scratch_bytes(h, hd, Tq, Tk, 3), dtype=torch.uint8, device=DEV)
     ds.ds_attention_fwd(tq, kb, kb + d * es, o, lse, t_qr, t_ql, t_kr, t_kl, h, hd, False, max(ql), max(kl),
-                        d, 2 * d, 2 * d, d, Tq, force_generic=force)
+                        d, 2 * d, 2 * d, d, Tq, k_total_rows=Tk, scratch=scratch, force_generic=force)
     gb = dkv.data_ptr()
     ds.ds_attention_bwd(tq, kb, kb + d * es, o, tdo, lse, delta, dq, gb, gb + d * es, t_qr, t_ql, t_kr, t_kl, h, hd, False,
-                        max(ql), max(kl), d, 2 * d, 2 * d, d, Tq, force_generic=force)
+                        max(ql), max(kl), d, 2 * d, 2 * d, d, Tq, k_total_rows=Tk, scratch=scratch, force_generic=force)
     torch.cuda.synchronize()
     tol = TOL[dt]
     for i in range(3):
