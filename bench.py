@@ -49,7 +49,7 @@ def build_layout(ds, kind, lens, cfg):
     raise SystemExit("unknown layout " + kind)
 
 
-def cpu_baseline(cfg, lens, seed, budget_s=15.0):
+def cpu_baseline(cfg, lens, seed, budget_s=6.0):
     """The oracle, as it stands, on a bounded seeded sample of the same workload."""
     from oracle import stage as ost
     from paper_2311_10418_amd import workload as wl

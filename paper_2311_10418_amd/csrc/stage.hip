@@ -1,14 +1,20 @@
 // The stage driver: owns the device workspace, binds a layout (uploads its tables once), and
 // enqueues forward then backward of every layer over the whole layout.
 //
-// All micro-batches of the layout live in one padded token stream, so every row-wise operator
-// (norms, projections, MLP, their gradients) is ONE launch over all micro-batches, and the
-// weight-gradient GEMMs contract over the tokens of all micro-batches at once, which is the
-// paper's gradient accumulation across micro-batches (section "Background", pipeline-parallel
-// paragraph).  Only attention looks at sequence boundaries, through the layout's sequence
-// table.  Padding rows: inputs are masked to zero on entry, residual epilogues write zeros to
-// padding rows, attention never touches them, and zero rows stay zero through the backward
-// pass, so padding contributes nothing to any weight gradient.
+// All micro-batches of the layout live in one padded token stream (two for an encoder-decoder
+// stage), so every row-wise operator (norms, projections, MLP, their gradients) is ONE launch over
+// all micro-batches, and the weight-gradient GEMMs contract over the tokens of all micro-batches at
+// once, which is the paper's gradient accumulation across micro-batches (section "Background",
+// pipeline-parallel paragraph).  Only attention looks at sequence boundaries, through the layout's
+// sequence tables.  Padding rows: inputs are masked to zero on entry, residual epilogues write zeros
+// to padding rows, attention never touches them (its output buffers' padding rows are zero-filled),
+// and zero rows stay zero through the backward pass, so padding contributes nothing to any weight
+// gradient.
+//
+// bf16 fast path ("nt mode"): every GEMM runs as C = A B^T with both operands contiguous along the
+// contraction (the direct-to-LDS kernel).  Forward uses [out][in] copies of the weights made at the
+// top of the call; a weight gradient dW[in][out] = X^T dY uses feature-major copies of X and dY whose
+// token dimension is zero-padded to a multiple of 64.
 #include "attention.hpp"
 #include "gemm.hpp"
 #include "layout.hpp"
@@ -18,8 +24,6 @@
 #include <cstring>
 #include <new>
 #include <vector>
-
-
 
 namespace {
 
@@ -35,27 +39,37 @@ __global__ __launch_bounds__(256) void zero_pad_rows_kernel(int rows, int row_by
     }
 }
 
+// Bump allocator over the workspace.  With base == nullptr it only measures.
 struct Arena {
     char* base = nullptr;
-    size_t size = 0, used = 0;
+    size_t used = 0;
     void* take(size_t bytes) {
         const size_t a = (used + 255) & ~size_t(255);
-        if (a + bytes > size) return nullptr;
         used = a + bytes;
-        return base + a;
+        return base ? base + a : nullptr;
     }
 };
 
-struct StreamTables {          // device tables of one token stream
+struct Stream {                     // one padded token stream of the bound layout + its device tables
     int32_t* row_valid = nullptr;   // [max_rows]  sorted sequence position, or -1 for padding
     int32_t* seq_row = nullptr;     // [max_seqs]
     int32_t* seq_len = nullptr;     // [max_seqs]
+    int R = 0, max_len = 0;
+    bool has_pad = false;
 };
 
-struct LayerBufs {
+struct GptBufs {
     void *u1, *qkv, *o, *x1, *u2, *z, *a, *xout;
     float *stats1, *stats2, *lse;
-    void *wqkv_t, *wo_t, *w1_t, *w2_t;      // [out][in] copies of the layer's matrices (bf16 fast path)
+    void *wqkv_t, *wo_t, *w1_t, *w2_t;          // [out][in] copies of the layer's matrices (nt mode)
+};
+
+struct T5Bufs {                                  // encoder layer; a decoder layer also uses the cross-attention part
+    void *u1, *qkv, *o, *x1, *u2, *zg, *zu, *a, *xout;
+    float *stats1, *stats2, *lse;
+    void *uc, *qc, *kvc, *oc, *x2;
+    float *statsc, *lsec;
+    void *wqkv_t, *wo_t, *wg_t, *wu_t, *w2_t, *wcq_t, *wckv_t, *wco_t;
 };
 
 }  // namespace
@@ -66,16 +80,17 @@ struct ds_stage {
     void* ws = nullptr;
     size_t ws_bytes = 0;
     Arena arena;
-    StreamTables tab;
+    Stream main, tgt;
+    int32_t n_seq = 0;
     int32_t* h_tables = nullptr;       // pinned staging for table uploads
-    size_t h_tables_ints = 0;
     hipEvent_t upload_done = nullptr;
     uint64_t bound_uid = 0;
-    int32_t bound_rows = 0, bound_seqs = 0, bound_max_len = 0;
-    bool bound_has_pad = false;
-    std::vector<LayerBufs> layers;
-    void *x0 = nullptr, *dyA = nullptr, *dyB = nullptr, *dz = nullptr, *du = nullptr, *dx1 = nullptr, *d_o = nullptr,
-         *dqkv = nullptr;
+    std::vector<GptBufs> gpt;
+    std::vector<T5Bufs> enc, dec;
+    // backward temporaries (sized for the longer stream)
+    void *x0 = nullptr, *y0 = nullptr, *dyA = nullptr, *dyB = nullptr, *dz = nullptr, *dz2 = nullptr, *du = nullptr,
+         *dx1 = nullptr, *dx2 = nullptr, *d_o = nullptr, *dqkv = nullptr, *dqc = nullptr, *dkvc = nullptr, *de = nullptr,
+         *deB = nullptr;
     float *delta = nullptr, *partial = nullptr, *split_ws = nullptr;
     void *xt = nullptr, *dyt = nullptr;     // token-major -> feature-major copies for the weight-gradient GEMMs
     void* attn_scratch = nullptr;           // feature-major copies for the attention kernels
@@ -92,84 +107,141 @@ struct ds_stage {
 
 namespace {
 
-ds_status bind_layout(ds_stage* s, const ds_layout* lo, hipStream_t st) {
-    if (lo->uid == s->bound_uid) return DS_OK;
-    if (lo->has_tgt != (s->cfg.model == DS_MODEL_T5)) return DS_ELAYOUT;
-    if (lo->total_rows > s->cfg.max_rows || lo->n_seq > s->cfg.max_seqs) return DS_ELAYOUT;
-    // a previous upload may still be reading the staging buffer
-    DS_HIP_CHECK(hipEventSynchronize(s->upload_done));
-    const int R = lo->total_rows, S = lo->n_seq;
-    int32_t* rv = s->h_tables;
-    int32_t* sr = rv + s->cfg.max_rows;
-    int32_t* sl = sr + s->cfg.max_seqs;
-    std::fill(rv, rv + R, -1);
-    int max_len = 0;
-    for (int i = 0; i < S; ++i) {
-        sr[i] = lo->seq_row[i];
-        sl[i] = lo->seq_len[i];
-        max_len = std::max(max_len, lo->seq_len[i]);
-        for (int r = 0; r < lo->seq_len[i]; ++r) rv[lo->seq_row[i] + r] = i;
-    }
-    DS_HIP_CHECK(hipMemcpyAsync(s->tab.row_valid, rv, sizeof(int32_t) * R, hipMemcpyHostToDevice, st));
-    DS_HIP_CHECK(hipMemcpyAsync(s->tab.seq_row, sr, sizeof(int32_t) * S, hipMemcpyHostToDevice, st));
-    DS_HIP_CHECK(hipMemcpyAsync(s->tab.seq_len, sl, sizeof(int32_t) * S, hipMemcpyHostToDevice, st));
-    DS_HIP_CHECK(hipEventRecord(s->upload_done, st));
-    s->bound_uid = lo->uid;
-    s->bound_rows = R;
-    s->bound_seqs = S;
-    s->bound_max_len = max_len;
-    s->bound_has_pad = lo->total_tokens != (int64_t)lo->total_rows;
-    return DS_OK;
-}
-
-ds_status zero_pad_rows(ds_stage* s, void* buf, int cols, hipStream_t st) {
-    if (!s->bound_has_pad) return DS_OK;
-    const int R = s->bound_rows;
-    const int row16 = (int)((size_t)cols * s->es / 16);
-    int blocks = (R + 3) / 4;
-    if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(zero_pad_rows_kernel, dim3(blocks), dim3(256), 0, st, R, row16, (uint4*)buf, s->tab.row_valid);
-    DS_LAUNCH_CHECK();
-    s->launches++;
-    return DS_OK;
-}
-
 #define DS_TRY(expr)                    \
     do {                                \
         ds_status st__ = (expr);        \
         if (st__ != DS_OK) return st__; \
     } while (0)
 
-ds_status gemm(ds_stage* s, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C, int epi,
-               const void* bias, const void* R, const void* R2, void* C2, bool mask_rows, int accumulate, hipStream_t st) {
-    GemmEpi p{bias, R, R2, C2, mask_rows && s->bound_has_pad ? s->tab.row_valid : nullptr, accumulate};
-    s->launches++;
-    return launch_gemm(s->cfg.dtype, ta, tb, M, N, K, A, B, C, epi, p, false, s->split_ws, s->split_ws_floats, st);
+// Lays out (or, with a null arena base, measures) every workspace buffer.
+void carve(ds_stage* s) {
+    const ds_stage_config& c = s->cfg;
+    Arena& ar = s->arena;
+    ar.used = 0;
+    const size_t es = s->es, d = c.d_model, F = c.d_ff, h = c.n_heads;
+    const size_t R = c.max_rows, Rt = c.model == DS_MODEL_T5 ? c.max_rows_tgt : 0, Rm = std::max(R, Rt);
+    const size_t S = c.max_seqs;
+    const bool nt = s->nt_mode;
+    auto f32 = [&](size_t n) { return (float*)ar.take(n * 4); };
+    if (c.model == DS_MODEL_GPT) {
+        s->gpt.resize(c.n_layers);
+        for (GptBufs& b : s->gpt) {
+            b.u1 = ar.take(R * d * es); b.qkv = ar.take(R * 3 * d * es); b.o = ar.take(R * d * es);
+            b.x1 = ar.take(R * d * es); b.u2 = ar.take(R * d * es); b.z = ar.take(R * F * es);
+            b.a = ar.take(R * F * es); b.xout = ar.take(R * d * es);
+            b.stats1 = f32(2 * R); b.stats2 = f32(2 * R); b.lse = f32(R * h);
+            b.wqkv_t = b.wo_t = b.w1_t = b.w2_t = nullptr;
+            if (nt) {
+                b.wqkv_t = ar.take(3 * d * d * es); b.wo_t = ar.take(d * d * es);
+                b.w1_t = ar.take(d * F * es); b.w2_t = ar.take(d * F * es);
+            }
+        }
+    } else {
+        auto layer = [&](T5Bufs& b, size_t rows, bool is_dec) {
+            b.u1 = ar.take(rows * d * es); b.qkv = ar.take(rows * 3 * d * es); b.o = ar.take(rows * d * es);
+            b.x1 = ar.take(rows * d * es); b.u2 = ar.take(rows * d * es); b.zg = ar.take(rows * F * es);
+            b.zu = ar.take(rows * F * es); b.a = ar.take(rows * F * es); b.xout = ar.take(rows * d * es);
+            b.stats1 = f32(2 * rows); b.stats2 = f32(2 * rows); b.lse = f32(rows * h);
+            b.uc = b.qc = b.kvc = b.oc = b.x2 = nullptr;
+            b.statsc = b.lsec = nullptr;
+            if (is_dec) {
+                b.uc = ar.take(rows * d * es); b.qc = ar.take(rows * d * es); b.kvc = ar.take(R * 2 * d * es);
+                b.oc = ar.take(rows * d * es); b.x2 = ar.take(rows * d * es);
+                b.statsc = f32(2 * rows); b.lsec = f32(rows * h);
+            }
+            b.wqkv_t = b.wo_t = b.wg_t = b.wu_t = b.w2_t = b.wcq_t = b.wckv_t = b.wco_t = nullptr;
+            if (nt) {
+                b.wqkv_t = ar.take(3 * d * d * es); b.wo_t = ar.take(d * d * es);
+                b.wg_t = ar.take(d * F * es); b.wu_t = ar.take(d * F * es); b.w2_t = ar.take(d * F * es);
+                if (is_dec) {
+                    b.wcq_t = ar.take(d * d * es); b.wckv_t = ar.take(2 * d * d * es); b.wco_t = ar.take(d * d * es);
+                }
+            }
+        };
+        s->enc.resize(c.n_layers);
+        s->dec.resize(c.n_dec_layers);
+        for (T5Bufs& b : s->enc) layer(b, R, false);
+        for (T5Bufs& b : s->dec) layer(b, Rt, true);
+    }
+    s->x0 = ar.take(R * d * es);
+    s->dyA = ar.take(Rm * d * es); s->dyB = ar.take(Rm * d * es);
+    s->du = ar.take(Rm * d * es); s->dx1 = ar.take(Rm * d * es); s->d_o = ar.take(Rm * d * es);
+    s->dz = ar.take(Rm * F * es); s->dqkv = ar.take(Rm * 3 * d * es);
+    s->delta = f32(Rm * h);
+    if (c.model == DS_MODEL_T5) {
+        s->y0 = ar.take(Rt * d * es);
+        s->dz2 = ar.take(Rm * F * es); s->dx2 = ar.take(Rt * d * es);
+        s->dqc = ar.take(Rt * d * es); s->dkvc = ar.take(R * 2 * d * es);
+        s->de = ar.take(R * d * es); s->deB = ar.take(R * d * es);
+    }
+    const size_t partial_floats = std::max<size_t>((size_t)ds_norm_bwd_scratch_floats(1, (int)d), (size_t)2048 * 1024);
+    s->partial = f32(partial_floats);
+    s->split_ws_floats = 3 * std::max(d * 3 * d, d * F);
+    s->split_ws = f32(s->split_ws_floats);
+    s->main.row_valid = (int32_t*)ar.take(R * 4);
+    s->main.seq_row = (int32_t*)ar.take(S * 4);
+    s->main.seq_len = (int32_t*)ar.take(S * 4);
+    if (Rt) {
+        s->tgt.row_valid = (int32_t*)ar.take(Rt * 4);
+        s->tgt.seq_row = (int32_t*)ar.take(S * 4);
+        s->tgt.seq_len = (int32_t*)ar.take(S * 4);
+    }
+    const int hd = c.d_model / c.n_heads;
+    s->attn_scratch = nullptr;
+    s->attn_scratch_bytes = 0;
+    if (c.dtype == DS_DTYPE_BF16 && (hd == 64 || hd == 128)) {
+        s->attn_scratch_bytes = attn_scratch_bytes(c.n_heads, hd, (int)Rm, (int)Rm, (int)S);
+        s->attn_scratch = ar.take(s->attn_scratch_bytes);
+    }
+    if (nt) {
+        const size_t Rp = (Rm + 63) & ~size_t(63);
+        s->xt = ar.take(std::max(d, F) * Rp * es);
+        s->dyt = ar.take(std::max(3 * d, F) * Rp * es);
+    }
+    ar.take(4096);
 }
 
-AttnArgs self_attn_args(ds_stage* s, const void* qkv, int mask) {
-    const int d = s->cfg.d_model, h = s->cfg.n_heads, hd = d / h;
-    AttnArgs a{};
-    a.dtype = s->cfg.dtype;
-    a.n_seq = s->bound_seqs;
-    a.n_heads = h;
-    a.head_dim = hd;
-    a.mask = mask;
-    a.q_row = a.k_row = s->tab.seq_row;
-    a.q_len = a.k_len = s->tab.seq_len;
-    a.max_q_len = a.max_k_len = s->bound_max_len;
-    const char* base = (const char*)qkv;
-    a.q = base;
-    a.k = base + (size_t)d * s->es;
-    a.v = base + (size_t)2 * d * s->es;
-    a.ldq = a.ldk = a.ldv = 3 * d;
-    a.ldo = d;
-    a.lse_stride = s->bound_rows;
-    a.scale = 1.0f / std::sqrt((float)hd);
-    a.scratch = s->attn_scratch;
-    a.scratch_bytes = s->attn_scratch_bytes;
-    a.q_total_rows = a.k_total_rows = s->bound_rows;
-    return a;
+ds_status upload_stream(ds_stage* s, Stream& sm, int32_t* host, int max_rows, int R, int S, const std::vector<int32_t>& row,
+                        const std::vector<int32_t>& len, int64_t tokens, hipStream_t st) {
+    int32_t* rv = host;
+    int32_t* sr = rv + max_rows;
+    int32_t* sl = sr + s->cfg.max_seqs;
+    std::fill(rv, rv + R, -1);
+    int max_len = 0;
+    for (int i = 0; i < S; ++i) {
+        sr[i] = row[i];
+        sl[i] = len[i];
+        max_len = std::max(max_len, len[i]);
+        if (i > 0 && row[i] < row[i - 1]) return DS_ELAYOUT;        // the attention kernels need ascending rows
+        for (int r = 0; r < len[i]; ++r) rv[row[i] + r] = i;
+    }
+    DS_HIP_CHECK(hipMemcpyAsync(sm.row_valid, rv, sizeof(int32_t) * R, hipMemcpyHostToDevice, st));
+    DS_HIP_CHECK(hipMemcpyAsync(sm.seq_row, sr, sizeof(int32_t) * S, hipMemcpyHostToDevice, st));
+    DS_HIP_CHECK(hipMemcpyAsync(sm.seq_len, sl, sizeof(int32_t) * S, hipMemcpyHostToDevice, st));
+    sm.R = R;
+    sm.max_len = max_len;
+    sm.has_pad = tokens != (int64_t)R;
+    return DS_OK;
+}
+
+ds_status bind_layout(ds_stage* s, const ds_layout* lo, hipStream_t st) {
+    if (lo->uid == s->bound_uid) return DS_OK;
+    const bool t5 = s->cfg.model == DS_MODEL_T5;
+    if (lo->has_tgt != t5) return DS_ELAYOUT;
+    if (lo->total_rows > s->cfg.max_rows || lo->n_seq > s->cfg.max_seqs) return DS_ELAYOUT;
+    if (t5 && lo->total_rows_tgt > s->cfg.max_rows_tgt) return DS_ELAYOUT;
+    // a previous upload may still be reading the staging buffer
+    DS_HIP_CHECK(hipEventSynchronize(s->upload_done));
+    s->bound_uid = 0;
+    DS_TRY(upload_stream(s, s->main, s->h_tables, s->cfg.max_rows, lo->total_rows, lo->n_seq, lo->seq_row, lo->seq_len,
+                         lo->total_tokens, st));
+    if (t5)
+        DS_TRY(upload_stream(s, s->tgt, s->h_tables + s->cfg.max_rows + 2 * (size_t)s->cfg.max_seqs, s->cfg.max_rows_tgt,
+                             lo->total_rows_tgt, lo->n_seq, lo->seq_row_tgt, lo->seq_len_tgt, lo->total_tokens_tgt, st));
+    DS_HIP_CHECK(hipEventRecord(s->upload_done, st));
+    s->n_seq = lo->n_seq;
+    s->bound_uid = lo->uid;
+    return DS_OK;
 }
 
 // Runs fn, bracketed by a pair of HIP events on the stream when profiling is on.
@@ -185,126 +257,384 @@ ds_status timed(ds_stage* s, int cat, hipStream_t st, F&& fn) {
     return r;
 }
 
+// The operators both model kinds are built from, each one launch (group) over a whole stream.
+struct Ops {
+    ds_stage* s;
+    hipStream_t st;
+    int accumulate;
+    int dt, d, F;
+    bool nt;
+
+    ds_status gemm_raw(int cat, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C, int epi,
+                       const void* bias, const void* R, const void* R2, void* C2, const int32_t* row_valid, int acc) {
+        return timed(s, cat, st, [&] {
+            GemmEpi p{bias, R, R2, C2, row_valid, acc};
+            s->launches++;
+            return launch_gemm(dt, ta, tb, M, N, K, A, B, C, epi, p, false, s->split_ws, s->split_ws_floats, st);
+        });
+    }
+    // Y[rows,N] = X[rows,K] W[K,N] (+ epilogue); Wt = the [N][K] copy used in nt mode
+    ds_status fwd(const Stream& sm, int N, int K, const void* X, const void* W, const void* Wt, void* C, int epi,
+                  const void* bias, const void* R, void* C2, bool mask) {
+        const int32_t* rv = mask && sm.has_pad ? sm.row_valid : nullptr;
+        if (nt) return gemm_raw(DS_PROF_GEMM_FWD, 0, 1, sm.R, N, K, X, Wt, C, epi, bias, R, nullptr, C2, rv, 0);
+        return gemm_raw(DS_PROF_GEMM_FWD, 0, 0, sm.R, N, K, X, W, C, epi, bias, R, nullptr, C2, rv, 0);
+    }
+    // dX[rows,K] = dY[rows,N] W[K,N]^T (+ epilogue)
+    ds_status dgrad(const Stream& sm, int K, int N, const void* dY, const void* W, void* C, int epi, const void* R,
+                    const void* R2, void* C2) {
+        return gemm_raw(DS_PROF_GEMM_DGRAD, 0, 1, sm.R, K, N, dY, W, C, epi, nullptr, R, R2, C2, nullptr, 0);
+    }
+    // dW[K,N] (+)= X[rows,K]^T dY[rows,N]
+    ds_status wgrad(const Stream& sm, int K, int N, const void* X, const void* dY, void* dW) {
+        if (!nt)
+            return gemm_raw(DS_PROF_GEMM_WGRAD, 1, 0, K, N, sm.R, X, dY, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr,
+                            nullptr, accumulate);
+        return timed(s, DS_PROF_GEMM_WGRAD, st, [&] {
+            const int Rp = (sm.R + 63) & ~63;
+            DS_TRY(launch_transpose_bf16(sm.R, K, Rp, X, s->xt, st));
+            DS_TRY(launch_transpose_bf16(sm.R, N, Rp, dY, s->dyt, st));
+            s->launches += 3;
+            GemmEpi p{nullptr, nullptr, nullptr, nullptr, nullptr, accumulate};
+            return launch_gemm(dt, 0, 1, K, N, Rp, s->xt, s->dyt, dW, DS_EPI_ACC32, p, false, s->split_ws, s->split_ws_floats, st);
+        });
+    }
+    ds_status weight_t(int K, int N, const void* W, void* Wt) {      // [K][N] -> [N][K]
+        s->launches++;
+        return launch_transpose_bf16(K, N, K, W, Wt, st);
+    }
+    ds_status colsum(const Stream& sm, int n, const void* x, void* out) {
+        s->launches += 2;
+        return timed(s, DS_PROF_COLSUM, st, [&] { return ds_colsum(dt, sm.R, n, x, (float*)out, s->partial, accumulate, st); });
+    }
+    ds_status norm_fwd(const Stream& sm, int rms, const void* x, const void* g, const void* b, void* y, float* stats) {
+        s->launches++;
+        return timed(s, DS_PROF_NORM, st, [&] { return ds_norm_fwd(dt, rms, sm.R, d, x, g, b, y, stats, st); });
+    }
+    ds_status norm_bwd(const Stream& sm, int rms, const void* dy, const void* x, const void* g, const float* stats,
+                       const void* resid, void* dx, void* dg, void* db) {
+        s->launches += 3;
+        return timed(s, DS_PROF_NORM, st, [&] {
+            return ds_norm_bwd(dt, rms, sm.R, d, dy, x, g, stats, resid, dx, (float*)dg, (float*)db, s->partial, accumulate, st);
+        });
+    }
+    ds_status mask_rows(const Stream& sm, const void* in, void* out) {
+        s->launches++;
+        return timed(s, DS_PROF_OTHER, st, [&] { return launch_mask_rows(dt, sm.R, d, in, out, sm.row_valid, st); });
+    }
+    ds_status zero_pad(const Stream& sm, void* buf, int cols) {
+        if (!sm.has_pad) return DS_OK;
+        return timed(s, DS_PROF_OTHER, st, [&] {
+            const int row16 = (int)((size_t)cols * s->es / 16);
+            int blocks = (sm.R + 3) / 4;
+            if (blocks > 4096) blocks = 4096;
+            hipLaunchKernelGGL(zero_pad_rows_kernel, dim3(blocks), dim3(256), 0, st, sm.R, row16, (uint4*)buf, sm.row_valid);
+            DS_LAUNCH_CHECK();
+            s->launches++;
+            return DS_OK;
+        });
+    }
+    AttnArgs attn_args(const Stream& q, const Stream& k, int mask) {
+        const int h = s->cfg.n_heads, hd = d / h;
+        AttnArgs a{};
+        a.dtype = dt;
+        a.n_seq = s->n_seq;
+        a.n_heads = h;
+        a.head_dim = hd;
+        a.mask = mask;
+        a.q_row = q.seq_row; a.q_len = q.seq_len;
+        a.k_row = k.seq_row; a.k_len = k.seq_len;
+        a.max_q_len = q.max_len; a.max_k_len = k.max_len;
+        a.ldo = d;
+        a.lse_stride = q.R;
+        a.scale = 1.0f / std::sqrt((float)hd);
+        a.scratch = s->attn_scratch;
+        a.scratch_bytes = s->attn_scratch_bytes;
+        a.q_total_rows = q.R;
+        a.k_total_rows = k.R;
+        return a;
+    }
+    // self-attention over a packed [rows, 3d] tensor
+    ds_status self_fwd(const Stream& sm, int mask, const void* qkv, void* o, float* lse) {
+        AttnArgs a = attn_args(sm, sm, mask);
+        const char* base = (const char*)qkv;
+        a.q = base; a.k = base + (size_t)d * s->es; a.v = base + (size_t)2 * d * s->es;
+        a.ldq = a.ldk = a.ldv = 3 * d;
+        a.o = o; a.lse = lse;
+        s->launches += 2;
+        DS_TRY(timed(s, DS_PROF_ATTN_FWD, st, [&] { return launch_attention_fwd(a, false, st); }));
+        return zero_pad(sm, o, d);
+    }
+    ds_status self_bwd(const Stream& sm, int mask, const void* qkv, const void* o, const void* d_o, const float* lse, void* dqkv) {
+        AttnArgs a = attn_args(sm, sm, mask);
+        const char* base = (const char*)qkv;
+        a.q = base; a.k = base + (size_t)d * s->es; a.v = base + (size_t)2 * d * s->es;
+        a.ldq = a.ldk = a.ldv = 3 * d;
+        a.o = const_cast<void*>(o); a.d_o = d_o; a.lse = const_cast<float*>(lse); a.delta = s->delta;
+        char* g = (char*)dqkv;
+        a.dq = g; a.dk = g + (size_t)d * s->es; a.dv = g + (size_t)2 * d * s->es;
+        s->launches += 6;
+        DS_TRY(timed(s, DS_PROF_ATTN_BWD, st, [&] { return launch_attention_bwd(a, false, st); }));
+        return zero_pad(sm, dqkv, 3 * d);
+    }
+};
+
+// ------------------------------------------------------------------------------------ GPT
 ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io, const ds_gpt_layer* g, int accumulate,
                       hipStream_t st) {
-    const int R = s->bound_rows, d = s->cfg.d_model, F = s->cfg.d_ff, L = s->cfg.n_layers;
-    const int dt = s->cfg.dtype;
-    const bool pad = s->bound_has_pad;
-    auto G = [&](int cat, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C, int epi,
-                 const void* bias, const void* Rr, void* C2, bool mask, int acc) {
-        return timed(s, cat, st, [&] { return gemm(s, ta, tb, M, N, K, A, B, C, epi, bias, Rr, nullptr, C2, mask, acc, st); });
-    };
-    // bf16 fast path: every GEMM runs as C = A B^T with both operands contiguous along the contraction
-    // (the direct-to-LDS kernel).  Forward uses [out][in] copies of the weights made at the top of the
-    // call; a weight gradient dW[in][out] = X^T dY uses feature-major copies of X and dY whose token
-    // dimension is zero-padded to a multiple of 64.
-    const bool nt = s->nt_mode;
-    const int Rp = (R + 63) & ~63;
-    auto FWD = [&](int N, int K, const void* X, const void* W, const void* Wt, void* C, int epi, const void* bias,
-                   const void* Rr, void* C2, bool mask) {
-        if (nt) return G(DS_PROF_GEMM_FWD, 0, 1, R, N, K, X, Wt, C, epi, bias, Rr, C2, mask, 0);
-        return G(DS_PROF_GEMM_FWD, 0, 0, R, N, K, X, W, C, epi, bias, Rr, C2, mask, 0);
-    };
-    auto WGRAD = [&](int Kin, int Nout, const void* X, const void* dY, void* dW) {
-        if (!nt) return G(DS_PROF_GEMM_WGRAD, 1, 0, Kin, Nout, R, X, dY, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, false, accumulate);
-        return timed(s, DS_PROF_GEMM_WGRAD, st, [&] {
-            DS_TRY(launch_transpose_bf16(R, Kin, Rp, X, s->xt, st));
-            DS_TRY(launch_transpose_bf16(R, Nout, Rp, dY, s->dyt, st));
-            s->launches += 2;
-            return gemm(s, 0, 1, Kin, Nout, Rp, s->xt, s->dyt, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr, false, accumulate, st);
-        });
-    };
-    if (nt) {
+    const int d = s->cfg.d_model, F = s->cfg.d_ff, L = s->cfg.n_layers;
+    const Stream& sm = s->main;
+    Ops op{s, st, accumulate, s->cfg.dtype, d, F, s->nt_mode};
+    if (op.nt) {
         DS_TRY(timed(s, DS_PROF_GEMM_FWD, st, [&] {
             for (int l = 0; l < L; ++l) {
-                LayerBufs& b = s->layers[l];
-                DS_TRY(launch_transpose_bf16(d, 3 * d, d, w[l].w_qkv, b.wqkv_t, st));
-                DS_TRY(launch_transpose_bf16(d, d, d, w[l].w_o, b.wo_t, st));
-                DS_TRY(launch_transpose_bf16(d, F, d, w[l].w_1, b.w1_t, st));
-                DS_TRY(launch_transpose_bf16(F, d, F, w[l].w_2, b.w2_t, st));
-                s->launches += 4;
+                GptBufs& b = s->gpt[l];
+                DS_TRY(op.weight_t(d, 3 * d, w[l].w_qkv, b.wqkv_t));
+                DS_TRY(op.weight_t(d, d, w[l].w_o, b.wo_t));
+                DS_TRY(op.weight_t(d, F, w[l].w_1, b.w1_t));
+                DS_TRY(op.weight_t(F, d, w[l].w_2, b.w2_t));
             }
             return DS_OK;
         }));
     }
-    auto colsum = [&](int n, const void* x, void* out) {
-        s->launches += 2;
-        return timed(s, DS_PROF_COLSUM, st, [&] { return ds_colsum(dt, R, n, x, (float*)out, s->partial, accumulate, st); });
-    };
 
     // ---------------- forward (ForwardPass of every micro-batch)
     const void* x_in = io->act_in;
-    if (pad) {
-        DS_TRY(timed(s, DS_PROF_OTHER, st, [&] { return launch_mask_rows(dt, R, d, io->act_in, s->x0, s->tab.row_valid, st); }));
-        s->launches++;
+    if (sm.has_pad) {
+        DS_TRY(op.mask_rows(sm, io->act_in, s->x0));
         x_in = s->x0;
     }
+    const void* x0 = x_in;
     for (int l = 0; l < L; ++l) {
-        LayerBufs& b = s->layers[l];
+        GptBufs& b = s->gpt[l];
         void* x_out = (l == L - 1) ? io->act_out : b.xout;
-        DS_TRY(timed(s, DS_PROF_NORM, st, [&] { return ds_norm_fwd(dt, 0, R, d, x_in, w[l].ln1_g, w[l].ln1_b, b.u1, b.stats1, st); }));
-        DS_TRY(FWD(3 * d, d, b.u1, w[l].w_qkv, b.wqkv_t, b.qkv, DS_EPI_NONE, w[l].b_qkv, nullptr, nullptr, false));
-        AttnArgs a = self_attn_args(s, b.qkv, 1);
-        a.o = b.o;
-        a.lse = b.lse;
-        DS_TRY(timed(s, DS_PROF_ATTN_FWD, st, [&] { return launch_attention_fwd(a, false, st); }));
-        DS_TRY(timed(s, DS_PROF_OTHER, st, [&] { return zero_pad_rows(s, b.o, d, st); }));
-        DS_TRY(FWD(d, d, b.o, w[l].w_o, b.wo_t, b.x1, DS_EPI_RESID, w[l].b_o, x_in, nullptr, true));
-        DS_TRY(timed(s, DS_PROF_NORM, st, [&] { return ds_norm_fwd(dt, 0, R, d, b.x1, w[l].ln2_g, w[l].ln2_b, b.u2, b.stats2, st); }));
-        DS_TRY(FWD(F, d, b.u2, w[l].w_1, b.w1_t, b.z, DS_EPI_GELU, w[l].b_1, nullptr, b.a, false));
-        DS_TRY(FWD(d, F, b.a, w[l].w_2, b.w2_t, x_out, DS_EPI_RESID, w[l].b_2, b.x1, nullptr, true));
-        s->launches += 3;
+        DS_TRY(op.norm_fwd(sm, 0, x_in, w[l].ln1_g, w[l].ln1_b, b.u1, b.stats1));
+        DS_TRY(op.fwd(sm, 3 * d, d, b.u1, w[l].w_qkv, b.wqkv_t, b.qkv, DS_EPI_NONE, w[l].b_qkv, nullptr, nullptr, false));
+        DS_TRY(op.self_fwd(sm, 1, b.qkv, b.o, b.lse));
+        DS_TRY(op.fwd(sm, d, d, b.o, w[l].w_o, b.wo_t, b.x1, DS_EPI_RESID, w[l].b_o, x_in, nullptr, true));
+        DS_TRY(op.norm_fwd(sm, 0, b.x1, w[l].ln2_g, w[l].ln2_b, b.u2, b.stats2));
+        DS_TRY(op.fwd(sm, F, d, b.u2, w[l].w_1, b.w1_t, b.z, DS_EPI_GELU, w[l].b_1, nullptr, b.a, false));
+        DS_TRY(op.fwd(sm, d, F, b.a, w[l].w_2, b.w2_t, x_out, DS_EPI_RESID, w[l].b_2, b.x1, nullptr, true));
         x_in = x_out;
     }
 
     // ---------------- backward (BackwardPass of every micro-batch; weight gradients summed over all of them)
     const void* dy = io->grad_out;
-    if (pad) {
-        DS_TRY(timed(s, DS_PROF_OTHER, st, [&] { return launch_mask_rows(dt, R, d, io->grad_out, s->dyA, s->tab.row_valid, st); }));
-        s->launches++;
+    if (sm.has_pad) {
+        DS_TRY(op.mask_rows(sm, io->grad_out, s->dyA));
         dy = s->dyA;
     }
     void* pp[2] = {s->dyB, s->dyA};
     int flip = 0;
     for (int l = L - 1; l >= 0; --l) {
-        LayerBufs& b = s->layers[l];
-        const void* xl_in = (l == 0) ? (pad ? s->x0 : io->act_in) : s->layers[l - 1].xout;
+        GptBufs& b = s->gpt[l];
+        const void* xl_in = (l == 0) ? x0 : s->gpt[l - 1].xout;
         void* dx_in = (l == 0) ? io->grad_in : pp[flip];
         // MLP
-        DS_TRY(WGRAD(F, d, b.a, dy, g[l].w_2));
-        DS_TRY(colsum(d, dy, g[l].b_2));
-        DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, F, d, dy, w[l].w_2, s->dz, DS_EPI_DGELU, nullptr, b.z, nullptr, false, 0));
-        DS_TRY(WGRAD(d, F, b.u2, s->dz, g[l].w_1));
-        DS_TRY(colsum(F, s->dz, g[l].b_1));
-        DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, d, F, s->dz, w[l].w_1, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr, false, 0));
-        DS_TRY(timed(s, DS_PROF_NORM, st, [&] {
-            return ds_norm_bwd(dt, 0, R, d, s->du, b.x1, w[l].ln2_g, b.stats2, dy, s->dx1, (float*)g[l].ln2_g,
-                               (float*)g[l].ln2_b, s->partial, accumulate, st);
-        }));
+        DS_TRY(op.wgrad(sm, F, d, b.a, dy, g[l].w_2));
+        DS_TRY(op.colsum(sm, d, dy, g[l].b_2));
+        DS_TRY(op.dgrad(sm, F, d, dy, w[l].w_2, s->dz, DS_EPI_DGELU, b.z, nullptr, nullptr));
+        DS_TRY(op.wgrad(sm, d, F, b.u2, s->dz, g[l].w_1));
+        DS_TRY(op.colsum(sm, F, s->dz, g[l].b_1));
+        DS_TRY(op.dgrad(sm, d, F, s->dz, w[l].w_1, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr));
+        DS_TRY(op.norm_bwd(sm, 0, s->du, b.x1, w[l].ln2_g, b.stats2, dy, s->dx1, g[l].ln2_g, g[l].ln2_b));
         // attention
-        DS_TRY(WGRAD(d, d, b.o, s->dx1, g[l].w_o));
-        DS_TRY(colsum(d, s->dx1, g[l].b_o));
-        DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, d, d, s->dx1, w[l].w_o, s->d_o, DS_EPI_NONE, nullptr, nullptr, nullptr, false, 0));
-        AttnArgs a = self_attn_args(s, b.qkv, 1);
-        a.o = b.o;
-        a.d_o = s->d_o;
-        a.lse = b.lse;
-        a.delta = s->delta;
-        char* dq = (char*)s->dqkv;
-        a.dq = dq;
-        a.dk = dq + (size_t)d * s->es;
-        a.dv = dq + (size_t)2 * d * s->es;
-        DS_TRY(timed(s, DS_PROF_ATTN_BWD, st, [&] { return launch_attention_bwd(a, false, st); }));
-        DS_TRY(timed(s, DS_PROF_OTHER, st, [&] { return zero_pad_rows(s, s->dqkv, 3 * d, st); }));
-        DS_TRY(WGRAD(d, 3 * d, b.u1, s->dqkv, g[l].w_qkv));
-        DS_TRY(colsum(3 * d, s->dqkv, g[l].b_qkv));
-        DS_TRY(G(DS_PROF_GEMM_DGRAD, 0, 1, R, d, 3 * d, s->dqkv, w[l].w_qkv, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr, false, 0));
-        DS_TRY(timed(s, DS_PROF_NORM, st, [&] {
-            return ds_norm_bwd(dt, 0, R, d, s->du, xl_in, w[l].ln1_g, b.stats1, s->dx1, dx_in, (float*)g[l].ln1_g,
-                               (float*)g[l].ln1_b, s->partial, accumulate, st);
-        }));
-        s->launches += 2 * 3 + 3;
+        DS_TRY(op.wgrad(sm, d, d, b.o, s->dx1, g[l].w_o));
+        DS_TRY(op.colsum(sm, d, s->dx1, g[l].b_o));
+        DS_TRY(op.dgrad(sm, d, d, s->dx1, w[l].w_o, s->d_o, DS_EPI_NONE, nullptr, nullptr, nullptr));
+        DS_TRY(op.self_bwd(sm, 1, b.qkv, b.o, s->d_o, b.lse, s->dqkv));
+        DS_TRY(op.wgrad(sm, d, 3 * d, b.u1, s->dqkv, g[l].w_qkv));
+        DS_TRY(op.colsum(sm, 3 * d, s->dqkv, g[l].b_qkv));
+        DS_TRY(op.dgrad(sm, d, 3 * d, s->dqkv, w[l].w_qkv, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr));
+        DS_TRY(op.norm_bwd(sm, 0, s->du, xl_in, w[l].ln1_g, b.stats1, s->dx1, dx_in, g[l].ln1_g, g[l].ln1_b));
         dy = dx_in;
+        flip ^= 1;
+    }
+    return DS_OK;
+}
+
+// ------------------------------------------------------------------------------------ T5
+// Self-attention sub-block forward: x1 = x + Attn(RMS1(x)) Wo
+ds_status t5_self_fwd(Ops& op, const Stream& sm, int mask, const void* x, T5Bufs& b, const void* ln1_g, const void* w_qkv,
+                      const void* w_o) {
+    const int d = op.d;
+    DS_TRY(op.norm_fwd(sm, 1, x, ln1_g, nullptr, b.u1, b.stats1));
+    DS_TRY(op.fwd(sm, 3 * d, d, b.u1, w_qkv, b.wqkv_t, b.qkv, DS_EPI_NONE, nullptr, nullptr, nullptr, false));
+    DS_TRY(op.self_fwd(sm, mask, b.qkv, b.o, b.lse));
+    return op.fwd(sm, d, d, b.o, w_o, b.wo_t, b.x1, DS_EPI_RESID, nullptr, x, nullptr, true);
+}
+// Gated-GELU MLP forward: out = xin + (GELU(u Wg) * (u Wu)) W2,  u = RMS2(xin)
+ds_status t5_mlp_fwd(Ops& op, const Stream& sm, const void* xin, void* out, T5Bufs& b, const void* ln2_g, const void* w_g,
+                     const void* w_u, const void* w_2) {
+    const int d = op.d, F = op.F;
+    DS_TRY(op.norm_fwd(sm, 1, xin, ln2_g, nullptr, b.u2, b.stats2));
+    DS_TRY(op.fwd(sm, F, d, b.u2, w_g, b.wg_t, b.zg, DS_EPI_NONE, nullptr, nullptr, nullptr, false));
+    DS_TRY(op.fwd(sm, F, d, b.u2, w_u, b.wu_t, b.zu, DS_EPI_GATE, nullptr, b.zg, b.a, false));
+    return op.fwd(sm, d, F, b.a, w_2, b.w2_t, out, DS_EPI_RESID, nullptr, xin, nullptr, true);
+}
+// MLP backward: dy = gradient of the MLP output; writes dy + RMS2-backward(...) (the gradient of xin) into dxin
+ds_status t5_mlp_bwd(Ops& op, const Stream& sm, const void* dy, const void* xin, void* dxin, T5Bufs& b, const void* ln2_g,
+                     const void* w_g, const void* w_u, const void* w_2, void* g_ln2, void* g_wg, void* g_wu, void* g_w2) {
+    ds_stage* s = op.s;
+    const int d = op.d, F = op.F;
+    DS_TRY(op.wgrad(sm, F, d, b.a, dy, g_w2));
+    DS_TRY(op.dgrad(sm, F, d, dy, w_2, s->dz, DS_EPI_DGATE, b.zg, b.zu, s->dz2));      // dz = d zg, dz2 = d zu
+    DS_TRY(op.wgrad(sm, d, F, b.u2, s->dz, g_wg));
+    DS_TRY(op.wgrad(sm, d, F, b.u2, s->dz2, g_wu));
+    DS_TRY(op.dgrad(sm, d, F, s->dz, w_g, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr));
+    DS_TRY(op.dgrad(sm, d, F, s->dz2, w_u, s->d_o, DS_EPI_RESID, s->du, nullptr, nullptr));   // d_o = du + dzu Wu^T
+    return op.norm_bwd(sm, 1, s->d_o, xin, ln2_g, b.stats2, dy, dxin, g_ln2, nullptr);
+}
+// Self-attention sub-block backward: dy = gradient of x1; writes the gradient of x into dx
+ds_status t5_self_bwd(Ops& op, const Stream& sm, int mask, const void* dy, const void* x, void* dx, T5Bufs& b,
+                      const void* ln1_g, const void* w_qkv, const void* w_o, void* g_ln1, void* g_wqkv, void* g_wo) {
+    ds_stage* s = op.s;
+    const int d = op.d;
+    DS_TRY(op.wgrad(sm, d, d, b.o, dy, g_wo));
+    DS_TRY(op.dgrad(sm, d, d, dy, w_o, s->d_o, DS_EPI_NONE, nullptr, nullptr, nullptr));
+    DS_TRY(op.self_bwd(sm, mask, b.qkv, b.o, s->d_o, b.lse, s->dqkv));
+    DS_TRY(op.wgrad(sm, d, 3 * d, b.u1, s->dqkv, g_wqkv));
+    DS_TRY(op.dgrad(sm, d, 3 * d, s->dqkv, w_qkv, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr));
+    return op.norm_bwd(sm, 1, s->du, x, ln1_g, b.stats1, dy, dx, g_ln1, nullptr);
+}
+
+ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_layer* wd, const ds_stage_io* io,
+                     const ds_t5_enc_layer* ge, const ds_t5_dec_layer* gd, int accumulate, hipStream_t st) {
+    const int d = s->cfg.d_model, F = s->cfg.d_ff, Le = s->cfg.n_layers, Ld = s->cfg.n_dec_layers;
+    const Stream& E = s->main;
+    const Stream& D = s->tgt;
+    Ops op{s, st, accumulate, s->cfg.dtype, d, F, s->nt_mode};
+    if (op.nt) {
+        DS_TRY(timed(s, DS_PROF_GEMM_FWD, st, [&] {
+            for (int l = 0; l < Le; ++l) {
+                T5Bufs& b = s->enc[l];
+                DS_TRY(op.weight_t(d, 3 * d, we[l].w_qkv, b.wqkv_t));
+                DS_TRY(op.weight_t(d, d, we[l].w_o, b.wo_t));
+                DS_TRY(op.weight_t(d, F, we[l].w_g, b.wg_t));
+                DS_TRY(op.weight_t(d, F, we[l].w_u, b.wu_t));
+                DS_TRY(op.weight_t(F, d, we[l].w_2, b.w2_t));
+            }
+            for (int l = 0; l < Ld; ++l) {
+                T5Bufs& b = s->dec[l];
+                DS_TRY(op.weight_t(d, 3 * d, wd[l].w_qkv, b.wqkv_t));
+                DS_TRY(op.weight_t(d, d, wd[l].w_o, b.wo_t));
+                DS_TRY(op.weight_t(d, d, wd[l].w_cq, b.wcq_t));
+                DS_TRY(op.weight_t(d, 2 * d, wd[l].w_ckv, b.wckv_t));
+                DS_TRY(op.weight_t(d, d, wd[l].w_co, b.wco_t));
+                DS_TRY(op.weight_t(d, F, wd[l].w_g, b.wg_t));
+                DS_TRY(op.weight_t(d, F, wd[l].w_u, b.wu_t));
+                DS_TRY(op.weight_t(F, d, wd[l].w_2, b.w2_t));
+            }
+            return DS_OK;
+        }));
+    }
+
+    // ---------------- forward: encoder layers over the input stream
+    const void* x_in = io->act_in;
+    if (E.has_pad) {
+        DS_TRY(op.mask_rows(E, io->act_in, s->x0));
+        x_in = s->x0;
+    }
+    const void* x0 = x_in;
+    for (int l = 0; l < Le; ++l) {
+        T5Bufs& b = s->enc[l];
+        DS_TRY(t5_self_fwd(op, E, 0, x_in, b, we[l].ln1_g, we[l].w_qkv, we[l].w_o));
+        DS_TRY(t5_mlp_fwd(op, E, b.x1, b.xout, b, we[l].ln2_g, we[l].w_g, we[l].w_u, we[l].w_2));
+        x_in = b.xout;
+    }
+    const void* enc_out = x_in;
+
+    // ---------------- forward: decoder layers over the target stream
+    const void* y_in = io->act_in_tgt;
+    if (D.has_pad) {
+        DS_TRY(op.mask_rows(D, io->act_in_tgt, s->y0));
+        y_in = s->y0;
+    }
+    const void* y0 = y_in;
+    for (int l = 0; l < Ld; ++l) {
+        T5Bufs& b = s->dec[l];
+        void* y_out = (l == Ld - 1) ? io->act_out : b.xout;
+        DS_TRY(t5_self_fwd(op, D, 1, y_in, b, wd[l].ln1_g, wd[l].w_qkv, wd[l].w_o));
+        // cross-attention: queries from the decoder stream, keys / values from the encoder output
+        DS_TRY(op.norm_fwd(D, 1, b.x1, wd[l].lnc_g, nullptr, b.uc, b.statsc));
+        DS_TRY(op.fwd(D, d, d, b.uc, wd[l].w_cq, b.wcq_t, b.qc, DS_EPI_NONE, nullptr, nullptr, nullptr, false));
+        DS_TRY(op.fwd(E, 2 * d, d, enc_out, wd[l].w_ckv, b.wckv_t, b.kvc, DS_EPI_NONE, nullptr, nullptr, nullptr, false));
+        {
+            AttnArgs a = op.attn_args(D, E, 0);
+            a.q = b.qc; a.ldq = d;
+            a.k = b.kvc; a.v = (const char*)b.kvc + (size_t)d * s->es; a.ldk = a.ldv = 2 * d;
+            a.o = b.oc; a.lse = b.lsec;
+            s->launches += 2;
+            DS_TRY(timed(s, DS_PROF_ATTN_FWD, st, [&] { return launch_attention_fwd(a, false, st); }));
+            DS_TRY(op.zero_pad(D, b.oc, d));
+        }
+        DS_TRY(op.fwd(D, d, d, b.oc, wd[l].w_co, b.wco_t, b.x2, DS_EPI_RESID, nullptr, b.x1, nullptr, true));
+        DS_TRY(t5_mlp_fwd(op, D, b.x2, y_out, b, wd[l].ln2_g, wd[l].w_g, wd[l].w_u, wd[l].w_2));
+        y_in = y_out;
+    }
+
+    // ---------------- backward: decoder layers (last to first); de accumulates the gradient of the encoder output
+    const void* dy = io->grad_out;
+    if (D.has_pad) {
+        DS_TRY(op.mask_rows(D, io->grad_out, s->dyA));
+        dy = s->dyA;
+    }
+    void* pp[2] = {s->dyB, s->dyA};
+    int flip = 0;
+    bool de_set = false;
+    void* de_cur = s->de;
+    void* de_alt = s->deB;
+    for (int l = Ld - 1; l >= 0; --l) {
+        T5Bufs& b = s->dec[l];
+        const void* yl_in = (l == 0) ? y0 : s->dec[l - 1].xout;
+        void* dy_in = (l == 0) ? io->grad_in_tgt : pp[flip];
+        // MLP: gradient of x2 into dx2
+        DS_TRY(t5_mlp_bwd(op, D, dy, b.x2, s->dx2, b, wd[l].ln2_g, wd[l].w_g, wd[l].w_u, wd[l].w_2, gd[l].ln2_g, gd[l].w_g,
+                          gd[l].w_u, gd[l].w_2));
+        // cross-attention: gradient of x1 into dx1, of the encoder output into de
+        DS_TRY(op.wgrad(D, d, d, b.oc, s->dx2, gd[l].w_co));
+        DS_TRY(op.dgrad(D, d, d, s->dx2, wd[l].w_co, s->d_o, DS_EPI_NONE, nullptr, nullptr, nullptr));
+        {
+            AttnArgs a = op.attn_args(D, E, 0);
+            a.q = b.qc; a.ldq = d;
+            a.k = b.kvc; a.v = (const char*)b.kvc + (size_t)d * s->es; a.ldk = a.ldv = 2 * d;
+            a.o = b.oc; a.d_o = s->d_o; a.lse = b.lsec; a.delta = s->delta;
+            a.dq = s->dqc; a.dk = s->dkvc; a.dv = (char*)s->dkvc + (size_t)d * s->es;
+            s->launches += 6;
+            DS_TRY(timed(s, DS_PROF_ATTN_BWD, st, [&] { return launch_attention_bwd(a, false, st); }));
+            DS_TRY(op.zero_pad(D, s->dqc, d));
+            DS_TRY(op.zero_pad(E, s->dkvc, 2 * d));
+        }
+        DS_TRY(op.wgrad(D, d, d, b.uc, s->dqc, gd[l].w_cq));
+        DS_TRY(op.wgrad(E, d, 2 * d, enc_out, s->dkvc, gd[l].w_ckv));
+        if (!de_set) {
+            DS_TRY(op.dgrad(E, d, 2 * d, s->dkvc, wd[l].w_ckv, de_cur, DS_EPI_NONE, nullptr, nullptr, nullptr));
+            de_set = true;
+        } else {
+            DS_TRY(op.dgrad(E, d, 2 * d, s->dkvc, wd[l].w_ckv, de_alt, DS_EPI_RESID, de_cur, nullptr, nullptr));
+            std::swap(de_cur, de_alt);
+        }
+        DS_TRY(op.dgrad(D, d, d, s->dqc, wd[l].w_cq, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr));
+        DS_TRY(op.norm_bwd(D, 1, s->du, b.x1, wd[l].lnc_g, b.statsc, s->dx2, s->dx1, gd[l].lnc_g, nullptr));
+        // causal self-attention: gradient of the layer input
+        DS_TRY(t5_self_bwd(op, D, 1, s->dx1, yl_in, dy_in, b, wd[l].ln1_g, wd[l].w_qkv, wd[l].w_o, gd[l].ln1_g, gd[l].w_qkv,
+                           gd[l].w_o));
+        dy = dy_in;
+        flip ^= 1;
+    }
+
+    // ---------------- backward: encoder layers.  The ping-pong buffers are free again.
+    const void* dx = de_cur;
+    flip = 0;
+    for (int l = Le - 1; l >= 0; --l) {
+        T5Bufs& b = s->enc[l];
+        const void* xl_in = (l == 0) ? x0 : s->enc[l - 1].xout;
+        void* dx_in = (l == 0) ? io->grad_in : pp[flip];
+        DS_TRY(t5_mlp_bwd(op, E, dx, b.x1, s->dx1, b, we[l].ln2_g, we[l].w_g, we[l].w_u, we[l].w_2, ge[l].ln2_g, ge[l].w_g,
+                          ge[l].w_u, ge[l].w_2));
+        DS_TRY(t5_self_bwd(op, E, 0, s->dx1, xl_in, dx_in, b, we[l].ln1_g, we[l].w_qkv, we[l].w_o, ge[l].ln1_g, ge[l].w_qkv,
+                           ge[l].w_o));
+        dx = dx_in;
         flip ^= 1;
     }
     return DS_OK;
@@ -322,38 +652,21 @@ extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out)
     const int hd = cfg->d_model / cfg->n_heads;
     if (hd > 128 || hd % 8) return DS_EINVAL;
     if (cfg->max_rows <= 0 || cfg->max_seqs <= 0) return DS_EINVAL;
-    if (cfg->model == DS_MODEL_T5) return DS_EINVAL;   // encoder-decoder stage: not built yet
     if (cfg->model == DS_MODEL_GPT && (cfg->n_dec_layers != 0 || cfg->max_rows_tgt != 0)) return DS_EINVAL;
+    if (cfg->model == DS_MODEL_T5 && (cfg->n_dec_layers <= 0 || cfg->max_rows_tgt <= 0)) return DS_EINVAL;
 
     ds_stage* s = new (std::nothrow) ds_stage();
     if (!s) return DS_ENOMEM;
     s->cfg = *cfg;
     s->es = dtype_size(cfg->dtype);
-    const size_t R = (size_t)cfg->max_rows, d = cfg->d_model, F = cfg->d_ff, h = cfg->n_heads, L = cfg->n_layers;
-    const size_t es = s->es;
-    auto al = [](size_t b) { return (b + 255) & ~size_t(255); };
-    size_t need = 0;
-    const size_t per_layer = al(R * d * es) * 5 + al(R * 3 * d * es) + al(R * F * es) * 2 + al(R * 2 * 4) * 2 + al(R * h * 4);
-    need += per_layer * L;
-    need += al(R * d * es) * 6 + al(R * F * es) + al(R * 3 * d * es);       // x0 dyA dyB du dx1 d_o, dz, dqkv
-    need += al(R * h * 4);                                                  // delta
-    const size_t partial_floats = std::max<size_t>((size_t)ds_norm_bwd_scratch_floats(1, (int)d), (size_t)2048 * 1024);
-    need += al(partial_floats * 4);
-    s->split_ws_floats = 3 * std::max(d * 3 * d, d * F);
-    need += al(s->split_ws_floats * 4);
-    need += al(R * 4) + 2 * al((size_t)cfg->max_seqs * 4);
-    need += 4096;
-    s->nt_mode = cfg->dtype == DS_DTYPE_BF16 && d % 256 == 0 && F % 256 == 0;
-    const size_t Rp = (R + 63) & ~size_t(63);
-    if (cfg->dtype == DS_DTYPE_BF16 && (hd == 64 || hd == 128)) {
-        s->attn_scratch_bytes = attn_scratch_bytes(cfg->n_heads, hd, cfg->max_rows, cfg->max_rows, cfg->max_seqs);
-        need += al(s->attn_scratch_bytes);
+    s->nt_mode = cfg->dtype == DS_DTYPE_BF16 && cfg->d_model % 256 == 0 && cfg->d_ff % 256 == 0;
+    try {
+        carve(s);                                   // measuring pass
+    } catch (const std::bad_alloc&) {
+        delete s;
+        return DS_ENOMEM;
     }
-    if (s->nt_mode) {
-        need += L * (al(3 * d * d * es) + al(d * d * es) + 2 * al(d * F * es));
-        need += al(std::max(d, F) * Rp * es) + al(std::max(3 * d, F) * Rp * es);
-    }
-
+    const size_t need = s->arena.used;
     if (hipMalloc(&s->ws, need) != hipSuccess) {
         (void)hipGetLastError();
         delete s;
@@ -361,60 +674,13 @@ extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out)
     }
     s->ws_bytes = need;
     s->arena.base = (char*)s->ws;
-    s->arena.size = need;
-    bool ok = true;
-    auto take = [&](size_t bytes) {
-        void* p = s->arena.take(bytes);
-        if (!p) ok = false;
-        return p;
-    };
-    s->layers.resize(L);
-    for (size_t l = 0; l < L; ++l) {
-        LayerBufs& b = s->layers[l];
-        b.u1 = take(R * d * es);
-        b.qkv = take(R * 3 * d * es);
-        b.o = take(R * d * es);
-        b.x1 = take(R * d * es);
-        b.u2 = take(R * d * es);
-        b.z = take(R * F * es);
-        b.a = take(R * F * es);
-        b.xout = take(R * d * es);
-        b.stats1 = (float*)take(R * 2 * 4);
-        b.stats2 = (float*)take(R * 2 * 4);
-        b.lse = (float*)take(R * h * 4);
-        b.wqkv_t = b.wo_t = b.w1_t = b.w2_t = nullptr;
-        if (s->nt_mode) {
-            b.wqkv_t = take(3 * d * d * es);
-            b.wo_t = take(d * d * es);
-            b.w1_t = take(d * F * es);
-            b.w2_t = take(d * F * es);
-        }
-    }
-    if (s->attn_scratch_bytes) s->attn_scratch = take(s->attn_scratch_bytes);
-    if (s->nt_mode) {
-        s->xt = take(std::max(d, F) * Rp * es);
-        s->dyt = take(std::max(3 * d, F) * Rp * es);
-    }
-    s->x0 = take(R * d * es);
-    s->dyA = take(R * d * es);
-    s->dyB = take(R * d * es);
-    s->du = take(R * d * es);
-    s->dx1 = take(R * d * es);
-    s->d_o = take(R * d * es);
-    s->dz = take(R * F * es);
-    s->dqkv = take(R * 3 * d * es);
-    s->delta = (float*)take(R * h * 4);
-    s->partial = (float*)take(partial_floats * 4);
-    s->split_ws = (float*)take(s->split_ws_floats * 4);
-    s->tab.row_valid = (int32_t*)take(R * 4);
-    s->tab.seq_row = (int32_t*)take((size_t)cfg->max_seqs * 4);
-    s->tab.seq_len = (int32_t*)take((size_t)cfg->max_seqs * 4);
-    s->h_tables_ints = R + 2 * (size_t)cfg->max_seqs;
-    if (!ok || hipHostMalloc((void**)&s->h_tables, s->h_tables_ints * 4, hipHostMallocDefault) != hipSuccess ||
+    carve(s);
+    const size_t ints = (size_t)cfg->max_rows + (size_t)cfg->max_rows_tgt + 4 * (size_t)cfg->max_seqs;
+    if (hipHostMalloc((void**)&s->h_tables, ints * 4, hipHostMallocDefault) != hipSuccess ||
         hipEventCreateWithFlags(&s->upload_done, hipEventDisableTiming) != hipSuccess) {
         (void)hipGetLastError();
         ds_stage_destroy(s);
-        return ok ? DS_EHIP : DS_ENOMEM;
+        return DS_EHIP;
     }
     *out = s;
     return DS_OK;
@@ -468,15 +734,15 @@ extern "C" ds_status stage_fwd_bwd(ds_stage* s, const ds_layout* lo, const void*
                                    void* hip_stream) {
     if (!s || !lo || !weights || !io || !grads) return DS_EINVAL;
     if (!io->act_in || !io->grad_out || !io->act_out || !io->grad_in) return DS_EINVAL;
-    (void)weights_dec;
-    (void)grads_dec;
+    const bool t5 = s->cfg.model == DS_MODEL_T5;
+    if (t5 && (!weights_dec || !grads_dec || !io->act_in_tgt || !io->grad_in_tgt)) return DS_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     ds_status r = bind_layout(s, lo, st);
     if (r != DS_OK) return r;
     s->launches = 0;
-    if (s->cfg.model == DS_MODEL_GPT)
-        return gpt_fwd_bwd(s, (const ds_gpt_layer*)weights, io, (const ds_gpt_layer*)grads, accumulate ? 1 : 0, st);
-    return DS_EINVAL;
+    if (!t5) return gpt_fwd_bwd(s, (const ds_gpt_layer*)weights, io, (const ds_gpt_layer*)grads, accumulate ? 1 : 0, st);
+    return t5_fwd_bwd(s, (const ds_t5_enc_layer*)weights, (const ds_t5_dec_layer*)weights_dec, io,
+                      (const ds_t5_enc_layer*)grads, (const ds_t5_dec_layer*)grads_dec, accumulate ? 1 : 0, st);
 }
 
 // ---------------------------------------------------------------------------- pack / unpack

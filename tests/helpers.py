@@ -89,3 +89,32 @@ def run_gpt_stage(layout, cfg, params, xs, dys, dtype_code, stage=None, fill=flo
 
 def cat(seqs):
     return np.concatenate([np.asarray(s, dtype=np.float64) for s in seqs], axis=0)
+
+
+def run_t5_stage(layout, cfg, enc_params, dec_params, enc_xs, dec_xs, ddec, dtype_code, fill=float("nan")):
+    """Encoder-decoder stage on a two-stream layout.  Returns dict of per-sequence outputs / gradients,
+    weight gradients (numpy) and the padding rows of every output stream."""
+    dt = tdtype(dtype_code)
+    d = cfg["d_model"]
+    stage = ds.Stage(ds.DS_MODEL_T5, dtype_code, cfg["n_layers"], d, cfg["n_heads"], cfg["d_ff"],
+                     max_rows=layout.total_rows, max_seqs=layout.n_seq, n_dec_layers=cfg["n_dec_layers"],
+                     max_rows_tgt=layout.total_rows_tgt)
+    we, wd = params_to_dev(enc_params, dt), params_to_dev(dec_params, dt)
+    ge, gd = zero_grads_like(we), zero_grads_like(wd)
+    x = stream_from_seqs(enc_xs, layout, d, dt, fill, which=0)
+    y = stream_from_seqs(dec_xs, layout, d, dt, fill, which=1)
+    dy = stream_from_seqs(ddec, layout, d, dt, fill, which=1)
+    out = torch.full_like(y, 7.0)
+    dx = torch.full_like(x, 7.0)
+    dyin = torch.full_like(y, 7.0)
+    ds.stage_fwd_bwd(stage, layout, we, x, dy, out, dx, ge, weights_dec=wd, grads_dec=gd, act_in_tgt=y, grad_in_tgt=dyin)
+    torch.cuda.synchronize()
+    outs, pad_o = seqs_from_stream(out, layout, which=1)
+    d_enc, pad_e = seqs_from_stream(dx, layout, which=0)
+    d_dec, pad_d = seqs_from_stream(dyin, layout, which=1)
+    res = {"outs": outs, "d_enc": d_enc, "d_dec": d_dec,
+           "eg": [{k: to_np(v) for k, v in layer.items()} for layer in ge],
+           "dg": [{k: to_np(v) for k, v in layer.items()} for layer in gd],
+           "pads": [pad_o, pad_e, pad_d]}
+    stage.close()
+    return res
