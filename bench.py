@@ -178,6 +178,13 @@ def main():
     log("useful MFMA utilisation (all algorithmic flops / step time / %.0f TFLOP/s): %.4f" % (PEAK_BF16_TFLOPS, useful_util))
     log("padding efficiency %.4f, executed GEMM flops / algorithmic %.3f" % (tokens / R, executed_lin / lin_flops))
 
+    # HBM-side bytes per GEMM launch from the committed rocprofv3 --pmc summary of this same command, if it
+    # covers this workload (FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size); else null.
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gemm_traffic_%s.json" % args.config)
+    if args.layout == "dp" and os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+
     result = {
         "metric": "non-pad tokens/s, stage fwd+bwd bf16 on 1 MI355X",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -188,12 +195,19 @@ def main():
                    "n_micro_batches": int(layout.n_mb), "padding_efficiency": tokens / R,
                    "dp_plan_ms": plan_ms, "useful_mfma_utilisation": useful_util,
                    "ms_per_step_by_group": breakdown},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_mfma_kernel (all projections: forward, dgrad, wgrad)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt_kernel (all projections: forward, dgrad, wgrad)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "launches_per_step": int(gemm_launches), "ms_per_step": gemm_ms,
                      "algorithmic_flops_per_step": lin_flops},
     }
+    # One plain device copy of known size (256 MiB read + 256 MiB written), outside the timed region: the
+    # reference dispatch against which FETCH_SIZE / WRITE_SIZE counters of a profiler run are scaled.
+    cal_src = torch.ones(64 * 2 ** 20, dtype=torch.float32, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
     stage.close()
     del x, dy, out, dx, weights, grads
     torch.cuda.empty_cache()

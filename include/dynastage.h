@@ -220,7 +220,8 @@ ds_status stage_fwd_bwd(ds_stage* stage, const ds_layout* layout,
  * milliseconds and the number of groups since the last read (HOST arrays of DS_PROF_COUNT
  * entries) and clears the record. */
 enum { DS_PROF_GEMM_FWD = 0, DS_PROF_GEMM_DGRAD = 1, DS_PROF_GEMM_WGRAD = 2, DS_PROF_ATTN_FWD = 3,
-       DS_PROF_ATTN_BWD = 4, DS_PROF_NORM = 5, DS_PROF_COLSUM = 6, DS_PROF_OTHER = 7, DS_PROF_COUNT = 8 };
+       DS_PROF_ATTN_BWD = 4, DS_PROF_NORM = 5, DS_PROF_COLSUM = 6, DS_PROF_OTHER = 7, DS_PROF_TRANSPOSE = 8,
+       DS_PROF_COUNT = 9 };
 ds_status ds_stage_profile_enable(ds_stage* stage, int32_t enable);
 ds_status ds_stage_profile_read(ds_stage* stage, float* ms, int32_t* count);
 

@@ -19,7 +19,7 @@ DS_MODEL_GPT, DS_MODEL_T5 = 0, 1
 DS_DTYPE_F32, DS_DTYPE_BF16 = 0, 1
 DS_EPI_NONE, DS_EPI_GELU, DS_EPI_RESID, DS_EPI_DGELU, DS_EPI_ACC32, DS_EPI_GATE, DS_EPI_DGATE = range(7)
 
-PROF_KINDS = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "norm", "colsum", "other")
+PROF_KINDS = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "norm", "colsum", "other", "transpose")
 
 _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOMEM", -4: "DS_EOVERFLOW",
                  -5: "DS_EHIP", -6: "DS_ELAYOUT"}
@@ -242,8 +242,8 @@ class Stage:
 
     def profile_read(self):
         """-> dict kind -> (milliseconds, groups) summed since the last read."""
-        ms = (C.c_float * 8)()
-        cnt = (C.c_int32 * 8)()
+        ms = (C.c_float * len(PROF_KINDS))()
+        cnt = (C.c_int32 * len(PROF_KINDS))()
         _check(lib().ds_stage_profile_read(self.handle, ms, cnt), "ds_stage_profile_read")
         return {k: (ms[i], cnt[i]) for i, k in enumerate(PROF_KINDS)}
 

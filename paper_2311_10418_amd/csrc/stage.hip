@@ -290,14 +290,14 @@ struct Ops {
         if (!nt)
             return gemm_raw(DS_PROF_GEMM_WGRAD, 1, 0, K, N, sm.R, X, dY, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr,
                             nullptr, accumulate);
-        return timed(s, DS_PROF_GEMM_WGRAD, st, [&] {
-            const int Rp = (sm.R + 63) & ~63;
+        const int Rp = (sm.R + 63) & ~63;
+        DS_TRY(timed(s, DS_PROF_TRANSPOSE, st, [&] {
             DS_TRY(launch_transpose_bf16(sm.R, K, Rp, X, s->xt, st));
-            DS_TRY(launch_transpose_bf16(sm.R, N, Rp, dY, s->dyt, st));
-            s->launches += 3;
-            GemmEpi p{nullptr, nullptr, nullptr, nullptr, nullptr, accumulate};
-            return launch_gemm(dt, 0, 1, K, N, Rp, s->xt, s->dyt, dW, DS_EPI_ACC32, p, false, s->split_ws, s->split_ws_floats, st);
-        });
+            s->launches += 2;
+            return launch_transpose_bf16(sm.R, N, Rp, dY, s->dyt, st);
+        }));
+        return gemm_raw(DS_PROF_GEMM_WGRAD, 0, 1, K, N, Rp, s->xt, s->dyt, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr,
+                        nullptr, accumulate);
     }
     ds_status weight_t(int K, int N, const void* W, void* Wt) {      // [K][N] -> [N][K]
         s->launches++;
@@ -386,7 +386,7 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
     const Stream& sm = s->main;
     Ops op{s, st, accumulate, s->cfg.dtype, d, F, s->nt_mode};
     if (op.nt) {
-        DS_TRY(timed(s, DS_PROF_GEMM_FWD, st, [&] {
+        DS_TRY(timed(s, DS_PROF_TRANSPOSE, st, [&] {
             for (int l = 0; l < L; ++l) {
                 GptBufs& b = s->gpt[l];
                 DS_TRY(op.weight_t(d, 3 * d, w[l].w_qkv, b.wqkv_t));
@@ -505,7 +505,7 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
     const Stream& D = s->tgt;
     Ops op{s, st, accumulate, s->cfg.dtype, d, F, s->nt_mode};
     if (op.nt) {
-        DS_TRY(timed(s, DS_PROF_GEMM_FWD, st, [&] {
+        DS_TRY(timed(s, DS_PROF_TRANSPOSE, st, [&] {
             for (int l = 0; l < Le; ++l) {
                 T5Bufs& b = s->enc[l];
                 DS_TRY(op.weight_t(d, 3 * d, we[l].w_qkv, b.wqkv_t));

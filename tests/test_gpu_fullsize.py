@@ -1,0 +1,121 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (DP plan of the
+whole seeded global batch, full model).  The oracle cannot run 65 K tokens through a 200 M-parameter
+stage in test time, so:
+  * stage outputs and input gradients are per-sequence independent, hence checked against the oracle
+    on SAMPLED sequences (their rows come from the seeded generator, all other rows are device noise);
+  * weight gradients are sums over sequences: the oracle checks them on the sampled sub-batch run
+    through the full-size model, and additivity over disjoint halves of the batch ties the
+    full-batch gradients to sub-batch ones.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stage as ost
+from paper_2311_10418_amd import binding as ds
+from paper_2311_10418_amd import workload as wl
+from helpers import DEV, cat, params_to_dev, rel_err, to_np, zero_grads_like
+
+pytestmark = pytest.mark.gpu
+
+
+def _rows_for(lens, idx, d, seed, tag):
+    """Seeded rows of one original-order sequence (same values draw_rows gives it)."""
+    rng = np.random.default_rng([seed, tag, int(idx)])
+    return wl.to_bf16_grid(rng.standard_normal((int(lens[idx]), d), dtype=np.float32))
+
+
+def _run(stage, layout, w, x, dy):
+    out = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    g = zero_grads_like(w)
+    ds.stage_fwd_bwd(stage, layout, w, x, dy, out, dx, g)
+    torch.cuda.synchronize()
+    return out, dx, g
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,sample_tokens,long_len", [("gpt_2048_bf16", 700, 1100), ("gpt_4096_longtail_bf16", 350, 700)])
+def test_full_size_configuration(name, sample_tokens, long_len):
+    cfg = wl.CONFIGS[name]
+    d, F, L, H = cfg["d_model"], cfg["d_ff"], cfg["n_layers"], cfg["n_heads"]
+    lens, _ = wl.draw_lengths(cfg["lengths"], seed=0)
+    layout = ds.dp_plan(lens, ds.make_cost_model(), cfg["cap"], cfg["num_stages"])
+    assert layout.total_rows == layout.total_tokens == int(lens.sum())
+    R = layout.total_rows
+    params = wl.draw_params(wl.GPT_KEYS, L, d, F, seed=0, bf16=True)
+    w = params_to_dev(params, torch.bfloat16)
+
+    # sampled sequences: the shortest, one near the median, one long enough to span many attention
+    # blocks, and mid-length ones up to the token budget
+    order = np.argsort(lens, kind="stable")
+    pick = [int(order[0]), int(order[len(order) // 2]), int(np.argmin(np.abs(lens.astype(np.int64) - long_len)))]
+    sample_tokens += int(lens[pick[2]])
+    tok = int(lens[pick].sum())
+    for i in order[len(order) // 2 + 1:]:
+        if tok + int(lens[i]) > sample_tokens:
+            break
+        pick.append(int(i))
+        tok += int(lens[i])
+    print(name, "sampled sequences", pick, "lengths", [int(lens[i]) for i in pick])
+
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(1)
+    x = torch.randn((R, d), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    dy = torch.randn((R, d), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    pos_of = {int(layout.perm[s]): s for s in range(layout.n_seq)}
+    xs, dys = [], []
+    for i in pick:
+        s = pos_of[i]
+        r0 = int(layout.seq_row[s])
+        xi, dyi = _rows_for(lens, i, d, 0, 3), _rows_for(lens, i, d, 0, 5)
+        xs.append(xi)
+        dys.append(dyi)
+        x[r0:r0 + xi.shape[0]] = torch.from_numpy(xi).to(DEV).to(torch.bfloat16)
+        dy[r0:r0 + xi.shape[0]] = torch.from_numpy(dyi).to(DEV).to(torch.bfloat16)
+
+    stage = ds.Stage(ds.DS_MODEL_GPT, ds.DS_DTYPE_BF16, L, d, H, F, max_rows=R, max_seqs=len(lens))
+    out, dx, g_full = _run(stage, layout, w, x, dy)
+
+    # 1. sampled sequences against the oracle
+    r_outs, r_dxs, r_grads = ost.gpt_stage_fwd_bwd(xs, dys, params, H)
+    for j, i in enumerate(pick):
+        s = pos_of[i]
+        r0, l = int(layout.seq_row[s]), int(lens[i])
+        e_o = rel_err(to_np(out[r0:r0 + l]), r_outs[j])
+        e_g = rel_err(to_np(dx[r0:r0 + l]), r_dxs[j])
+        print("  seq", i, "len", l, "act_out %.2e grad_in %.2e" % (e_o, e_g))
+        assert e_o <= 2e-2 and e_g <= 2e-2
+
+    # 2. the sampled sub-batch through the full-size model: weight gradients against the oracle
+    sub_lens = lens[pick]
+    lo_sub = ds.dp_plan(sub_lens, ds.make_cost_model(), cfg["cap"], cfg["num_stages"])
+    xsub = torch.cat([torch.from_numpy(xs[int(lo_sub.perm[s])]) for s in range(lo_sub.n_seq)]).to(DEV).to(torch.bfloat16)
+    dysub = torch.cat([torch.from_numpy(dys[int(lo_sub.perm[s])]) for s in range(lo_sub.n_seq)]).to(DEV).to(torch.bfloat16)
+    _, _, g_sub = _run(stage, lo_sub, w, xsub.contiguous(), dysub.contiguous())
+    worst = 0.0
+    for li in range(L):
+        for k, v in r_grads[li].items():
+            e = rel_err(to_np(g_sub[li][k]), v)
+            worst = max(worst, e)
+            assert e <= 2e-2, (li, k, e)
+    print("  sub-batch weight gradients, worst %.2e" % worst)
+
+    # 3. additivity over disjoint halves of the batch (even / odd sorted positions)
+    halves = []
+    for par in (0, 1):
+        pos = [s for s in range(layout.n_seq) if s % 2 == par]
+        rows = torch.cat([torch.arange(int(layout.seq_row[s]), int(layout.seq_row[s]) + int(layout.seq_len[s])) for s in pos]).to(DEV)
+        hl = np.array([int(layout.seq_len[s]) for s in pos], dtype=np.int32)
+        lo_h = ds.ds_layout_from_cuts(hl, list(range(len(hl) + 1)))          # already sorted: one sequence per micro-batch
+        _, _, g_h = _run(stage, lo_h, w, x.index_select(0, rows).contiguous(), dy.index_select(0, rows).contiguous())
+        halves.append(g_h)
+    worst = 0.0
+    for li in range(L):
+        for k in g_full[li]:
+            ref = to_np(g_full[li][k])
+            e = rel_err(to_np(halves[0][li][k]) + to_np(halves[1][li][k]), ref)
+            worst = max(worst, e)
+            assert e <= 2e-3, (li, k, e)
+    print("  additivity of weight gradients over halves, worst %.2e" % worst)
+    stage.close()
