@@ -27,12 +27,19 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_flops(cfg, lens):
+def algorithmic_flops(cfg, lens, tgts=None):
     """Forward+backward flops the method must execute on non-pad tokens (causal half only)."""
     d, F, L = cfg["d_model"], cfg["d_ff"], cfg["n_layers"]
     tokens = int(lens.sum())
-    linear = 3 * 2 * (4 * d * d + 2 * d * F) * tokens * L
-    attn = 3 * sum(2 * d * int(l) * (int(l) + 1) for l in lens) * L
+    if cfg["kind"] == "gpt":
+        linear = 3 * 2 * (4 * d * d + 2 * d * F) * tokens * L
+        attn = 3 * sum(2 * d * int(l) * (int(l) + 1) for l in lens) * L
+        return linear, attn
+    Ld = cfg["n_dec_layers"]
+    ttok = int(tgts.sum())
+    linear = 3 * (2 * (4 * d * d + 3 * d * F) * tokens * L + (2 * (6 * d * d + 3 * d * F) * ttok + 2 * 2 * d * d * tokens) * Ld)
+    attn = 3 * (sum(4 * d * int(l) ** 2 for l in lens) * L +
+                sum(2 * d * int(t) * (int(t) + 1) + 4 * d * int(t) * int(l) for l, t in zip(lens, tgts)) * Ld)
     return linear, attn
 
 
@@ -109,13 +116,18 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(3)
     cfg = wl.CONFIGS[args.config]
-    if cfg["kind"] != "gpt":
-        raise SystemExit("bench.py times the decoder-only stage")
+    t5 = cfg["kind"] == "t5"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    lens, _ = wl.draw_lengths(cfg["lengths"], seed=args.seed)
+    lens, tgts = wl.draw_lengths(cfg["lengths"], seed=args.seed)
     t0 = time.perf_counter()
-    layout, layout_desc = build_layout(ds, args.layout, lens, cfg)
+    if t5:
+        if args.layout != "dp":
+            raise SystemExit("only the DP-planned layout is timed for the encoder-decoder stage")
+        layout = ds.dp_plan(lens, ds.make_cost_model(kind=ds.DS_COST_POLY_T5), cfg["cap"], cfg["num_stages"], lengths_tgt=tgts)
+        layout_desc = "dp_plan c=%d cap=%d encoder-decoder cost" % (cfg["num_stages"], cfg["cap"])
+    else:
+        layout, layout_desc = build_layout(ds, args.layout, lens, cfg)
     plan_ms = (time.perf_counter() - t0) * 1e3
     d, F, L, H = cfg["d_model"], cfg["d_ff"], cfg["n_layers"], cfg["n_heads"]
     bf16 = cfg["dtype"] == "bf16"
@@ -128,27 +140,47 @@ def main():
     gen = torch.Generator(device=dev)
     gen.manual_seed(args.seed)
     shapes = {"ln1_g": (d,), "ln1_b": (d,), "w_qkv": (d, 3 * d), "b_qkv": (3 * d,), "w_o": (d, d), "b_o": (d,),
-              "ln2_g": (d,), "ln2_b": (d,), "w_1": (d, F), "b_1": (F,), "w_2": (F, d), "b_2": (d,)}
-    weights, grads = [], []
-    for _ in range(L):
-        w, g = {}, {}
-        for k in ds.GPT_KEYS:
-            v = torch.randn(shapes[k], generator=gen, device=dev, dtype=torch.float32) * 0.02
-            if k.endswith("_g"):
-                v = v + 1.0
-            w[k] = v.to(tdt).contiguous()
-            g[k] = torch.zeros(shapes[k], device=dev, dtype=torch.float32)
-        weights.append(w)
-        grads.append(g)
-    x = torch.randn((R, d), generator=gen, device=dev, dtype=torch.float32).to(tdt)
-    dy = torch.randn((R, d), generator=gen, device=dev, dtype=torch.float32).to(tdt)
-    out = torch.empty_like(x)
-    dx = torch.empty_like(x)
-    stage = ds.Stage(ds.DS_MODEL_GPT, code, L, d, H, F, max_rows=R, max_seqs=len(lens))
-    log("workspace %.2f GB" % (stage.workspace_bytes() / 2 ** 30))
+              "ln2_g": (d,), "ln2_b": (d,), "w_1": (d, F), "b_1": (F,), "w_2": (F, d), "b_2": (d,),
+              "lnc_g": (d,), "w_g": (d, F), "w_u": (d, F), "w_cq": (d, d), "w_ckv": (d, 2 * d), "w_co": (d, d)}
 
-    def step():
-        ds.stage_fwd_bwd(stage, layout, weights, x, dy, out, dx, grads, accumulate=False)
+    def make_layers(keys, n):
+        ws, gs = [], []
+        for _ in range(n):
+            w, g = {}, {}
+            for k in keys:
+                v = torch.randn(shapes[k], generator=gen, device=dev, dtype=torch.float32) * 0.02
+                if k.endswith("_g") and k.startswith("ln"):
+                    v = v + 1.0
+                w[k] = v.to(tdt).contiguous()
+                g[k] = torch.zeros(shapes[k], device=dev, dtype=torch.float32)
+            ws.append(w)
+            gs.append(g)
+        return ws, gs
+
+    def rnd(rows):
+        return torch.randn((rows, d), generator=gen, device=dev, dtype=torch.float32).to(tdt)
+
+    if t5:
+        Rt = layout.total_rows_tgt
+        weights, grads = make_layers(ds.T5_ENC_KEYS, L)
+        weights_d, grads_d = make_layers(ds.T5_DEC_KEYS, cfg["n_dec_layers"])
+        x, y, dy = rnd(R), rnd(Rt), rnd(Rt)
+        out, dx, dyin = torch.empty_like(y), torch.empty_like(x), torch.empty_like(y)
+        stage = ds.Stage(ds.DS_MODEL_T5, code, L, d, H, F, max_rows=R, max_seqs=len(lens),
+                         n_dec_layers=cfg["n_dec_layers"], max_rows_tgt=Rt)
+
+        def step():
+            ds.stage_fwd_bwd(stage, layout, weights, x, dy, out, dx, grads, accumulate=False, weights_dec=weights_d,
+                             grads_dec=grads_d, act_in_tgt=y, grad_in_tgt=dyin)
+    else:
+        weights, grads = make_layers(ds.GPT_KEYS, L)
+        x, dy = rnd(R), rnd(R)
+        out, dx = torch.empty_like(x), torch.empty_like(x)
+        stage = ds.Stage(ds.DS_MODEL_GPT, code, L, d, H, F, max_rows=R, max_seqs=len(lens))
+
+        def step():
+            ds.stage_fwd_bwd(stage, layout, weights, x, dy, out, dx, grads, accumulate=False)
+    log("workspace %.2f GB" % (stage.workspace_bytes() / 2 ** 30))
 
     for _ in range(args.warmup):
         step()
@@ -163,10 +195,10 @@ def main():
     prof = stage.profile_read()
     stage.profile_enable(False)
     ms_per_step = elapsed * 1e3 / args.steps
-    tokens = int(layout.total_tokens)
+    tokens = int(layout.total_tokens) + int(layout.total_tokens_tgt)
     value = tokens / (elapsed / args.steps)
 
-    lin_flops, attn_flops = algorithmic_flops(cfg, lens)
+    lin_flops, attn_flops = algorithmic_flops(cfg, lens, tgts)
     gemm_ms = sum(prof[k][0] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) / args.steps
     gemm_launches = sum(prof[k][1] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) // args.steps
     achieved = lin_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
@@ -174,9 +206,9 @@ def main():
     log("per-step ms by kernel group:", json.dumps(breakdown))
     log("launches per step: %d" % stage.last_launch_count())
     useful_util = (lin_flops + attn_flops) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
-    executed_lin = lin_flops * R / max(tokens, 1)
+    all_rows = R + int(layout.total_rows_tgt)
     log("useful MFMA utilisation (all algorithmic flops / step time / %.0f TFLOP/s): %.4f" % (PEAK_BF16_TFLOPS, useful_util))
-    log("padding efficiency %.4f, executed GEMM flops / algorithmic %.3f" % (tokens / R, executed_lin / lin_flops))
+    log("padding efficiency %.4f" % (tokens / all_rows))
 
     # HBM-side bytes per GEMM launch from the committed rocprofv3 --pmc summary of this same command, if it
     # covers this workload (FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size); else null.
@@ -191,8 +223,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": args.config, "model": "%d layers d_model %d heads %d d_ff %d causal" % (L, d, H, F),
-                   "layout": layout_desc, "n_seq": int(len(lens)), "non_pad_tokens": tokens, "rows": int(R),
-                   "n_micro_batches": int(layout.n_mb), "padding_efficiency": tokens / R,
+                   "layout": layout_desc, "n_seq": int(len(lens)), "non_pad_tokens": tokens, "rows": int(all_rows),
+                   "n_micro_batches": int(layout.n_mb), "padding_efficiency": tokens / all_rows,
                    "dp_plan_ms": plan_ms, "useful_mfma_utilisation": useful_util,
                    "ms_per_step_by_group": breakdown},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt_kernel (all projections: forward, dgrad, wgrad)",
@@ -209,9 +241,8 @@ def main():
     torch.cuda.synchronize()
     del cal_src, cal_dst
     stage.close()
-    del x, dy, out, dx, weights, grads
     torch.cuda.empty_cache()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not t5:
         result["cpu_baseline"] = cpu_baseline(cfg, lens, args.seed)
     print(json.dumps(result), flush=True)
 
