@@ -443,19 +443,28 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_mfma_kernel(int M, int N, in
 // 40-50 GB/s from L2 however many loads it keeps in flight, which is what a 256x256x(bf16) tile
 // needs at full MFMA rate; the rate scales with the number of wavefronts on the CU.
 constexpr int NT_DK = 32, NT_NS = 4, NT_HALF = 256 * NT_DK * 2, NT_STAGE = 2 * NT_HALF;
-constexpr int kStageLd2 = 68;
+#ifndef NT_WM
+#define NT_WM 2
+#define NT_WN 4
+#endif
 
-template <int EPI>
-__global__ __launch_bounds__(512, 1) void gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
-                                                              const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
-                                                              int tiles_m, int tiles_n, int splits,
-                                                              float* __restrict__ split_ws, GemmEpi p) {
+// WM x WN wavefronts per work-group; each owns a (256/WM) x (256/WN) accumulator block.
+template <int EPI, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
+                                                                       const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
+                                                                       int tiles_m, int tiles_n, int splits,
+                                                                       float* __restrict__ split_ws, GemmEpi p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     typedef const __attribute__((address_space(1))) void* gptr_t;
     typedef __attribute__((address_space(3))) void* lptr_t;
+    constexpr int NW = WM * WN;                    // wavefronts
+    constexpr int TM = 256 / WM / 32, TN = 256 / WN / 32;   // 32x32 MFMA tiles per wavefront
+    constexpr int LPW = 16 / NW;                   // direct-load instructions per operand per wavefront per K tile
+    static_assert(16 % NW == 0 && LPW >= 1, "wavefront count must divide 16");
+    constexpr int STG_LD = TN * 32 + 4;            // fp32 row stride of the epilogue staging block
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave / WN, wn = wave % WN;
 
     // ---- work-group id -> (tile_m, tile_n, split): contiguous runs per XCD, groups of 8 tile rows
     const int total = tiles_m * tiles_n * splits;
@@ -486,19 +495,19 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_nt_kernel(int M, int N, int 
     const int t_begin = split * per_split;
     const int t_end = (t_begin + per_split) < nt_total ? (t_begin + per_split) : nt_total;
 
-    f32x16_t acc[4][2];
+    f32x16_t acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     if (t_begin < t_end) {
-        uint32_t offA[2], offB[2];
+        uint32_t offA[LPW], offB[LPW];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int u = (wave * 2 + i) * 64 + lane;              // 16-byte unit of the 256x4 tile
+        for (int i = 0; i < LPW; ++i) {
+            const int u = (wave * LPW + i) * 64 + lane;            // 16-byte unit of the 256x4 tile
             const int row = u >> 2, slot = u & 3;
             const int chunk = slot ^ ((row >> 2) & 3);
             int ra_ = m0 + row;
@@ -514,10 +523,10 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_nt_kernel(int M, int N, int 
             tile = tile < t_last ? tile : t_last;
             const char* ga = pa + (long long)tile * (NT_DK * 2);
             const char* gb = pb + (long long)tile * (NT_DK * 2);
-            char* la = smem + stage * NT_STAGE + wave * 2048;
+            char* la = smem + stage * NT_STAGE + wave * (LPW * 1024);
             char* lb = la + NT_HALF;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < LPW; ++i) {
                 __builtin_amdgcn_global_load_lds((gptr_t)(ga + offA[i]), (lptr_t)(la + i * 1024), 16, 0, 0);
                 __builtin_amdgcn_global_load_lds((gptr_t)(gb + offB[i]), (lptr_t)(lb + i * 1024), 16, 0, 0);
             }
@@ -529,54 +538,57 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_nt_kernel(int M, int N, int 
         issue(t_begin + 2, 2);
         for (int tl = t_begin; tl < t_end; ++tl) {
             const int st_ = (tl - t_begin) & (NT_NS - 1);
-            __builtin_amdgcn_s_waitcnt(0x0F78);                     // vmcnt(8): this wavefront's part of tile tl has landed
+            // this wavefront's part of tile tl has landed: at most the two newest tiles (2 * 2 * LPW loads) outstanding
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * LPW));
             __builtin_amdgcn_s_barrier();                           // ... and everyone's; stage (tl-1)%4 is free again
             issue(tl + 3, (st_ + 3) & (NT_NS - 1));
             const char* a_base = smem + st_ * NT_STAGE;
             const char* b_base = a_base + NT_HALF;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                bf16x8_t fa[4], fb[2];
+                bf16x8_t fa[TM], fb[TN];
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off32(wm * 128 + i * 32 + frag_row, ks * 2 + frag_half));
+                for (int i = 0; i < TM; ++i)
+                    fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off32(wm * (TM * 32) + i * 32 + frag_row, ks * 2 + frag_half));
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off32(wn * 64 + j * 32 + frag_row, ks * 2 + frag_half));
+                for (int j = 0; j < TN; ++j)
+                    fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off32(wn * (TN * 32) + j * 32 + frag_row, ks * 2 + frag_half));
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < TN; ++j)
+                        // operands swapped on purpose: the accumulator tile is C^T (rows = n, columns = m), so a
+                        // lane holds 4 CONSECUTIVE n per register group and the epilogue stages with 16-byte writes
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
             }
         }
         __syncthreads();          // drains the redundant tail loads before LDS is reused by the epilogue
     }
 
-    // ---- epilogue through LDS: per wavefront a [32][kStageLd2] fp32 staging block
-    float* stage = reinterpret_cast<float*>(smem) + wave * (32 * kStageLd2);
+    // ---- epilogue through LDS: per wavefront a [32][STG_LD] fp32 staging block
+    float* stage = reinterpret_cast<float*>(smem) + wave * (32 * STG_LD);
     const int col_l = lane & 31, half = lane >> 5;
-    const int rd_row = lane >> 3, rd_col = (lane & 7) * 8;
+    constexpr int LPR = TN * 4;                    // lanes per staged row (8 columns each)
+    const int rd_row = lane / LPR, rd_col = (lane % LPR) * 8;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < TM; ++i) {
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = 8 * (e >> 2) + 4 * half + (e & 3);
-                stage[row * kStageLd2 + j * 32 + col_l] = acc[i][j][e];
-            }
+            for (int q = 0; q < 4; ++q)     // lane = row m (col_l); registers 4q..4q+3 = columns 8q + 4*half + 0..3
+                *reinterpret_cast<float4*>(stage + col_l * STG_LD + j * 32 + 8 * q + 4 * half) =
+                    make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
         __syncthreads();
 #pragma unroll
-        for (int pss = 0; pss < 4; ++pss) {
-            const int row = pss * 8 + rd_row;
-            const int m = m0 + wm * 128 + i * 32 + row;
-            const int n = n0 + wn * 64 + rd_col;
+        for (int pss = 0; pss < 32 / (64 / LPR); ++pss) {
+            const int row = pss * (64 / LPR) + rd_row;
+            const int m = m0 + wm * (TM * 32) + i * 32 + row;
+            const int n = n0 + wn * (TN * 32) + rd_col;
             if (m < M) {
                 float v[8];
-                const float4 x0 = *reinterpret_cast<const float4*>(stage + row * kStageLd2 + rd_col);
-                const float4 x1 = *reinterpret_cast<const float4*>(stage + row * kStageLd2 + rd_col + 4);
+                const float4 x0 = *reinterpret_cast<const float4*>(stage + row * STG_LD + rd_col);
+                const float4 x1 = *reinterpret_cast<const float4*>(stage + row * STG_LD + rd_col + 4);
                 v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
                 if (splits > 1) {
                     Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
@@ -665,8 +677,10 @@ template <int EPI>
 ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, const GemmEpi& p, float* split_ws,
                     size_t split_ws_floats, hipStream_t st) {
     static bool attr_set = false;
-    auto kern = gemm_bf16_nt_kernel<EPI>;
-    const int smem = NT_NS * NT_STAGE;
+    constexpr int WM = NT_WM, WN = NT_WN;
+    auto kern = gemm_bf16_nt_kernel<EPI, WM, WN>;
+    constexpr int stg = WM * WN * 32 * ((256 / WN) + 4) * 4;
+    const int smem = NT_NS * NT_STAGE > stg ? NT_NS * NT_STAGE : stg;
     if (!attr_set) {
         DS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
         attr_set = true;
@@ -686,7 +700,7 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
         }
     }
     const int total = tiles_m * tiles_n * splits;
-    hipLaunchKernelGGL(kern, dim3(total), dim3(512), smem, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C,
+    hipLaunchKernelGGL(kern, dim3(total), dim3(WM * WN * 64), smem, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C,
                        tiles_m, tiles_n, splits, split_ws, p);
     DS_LAUNCH_CHECK();
     if (splits > 1) {
