@@ -16,17 +16,18 @@ struct AttnArgs {
     long long lse_stride;
     void *dq, *dk, *dv;
     float scale;
-    // MFMA path: scratch for feature-major copies (V^T forward; Q^T, dO^T, K^T backward); the
-    // sequence tables must list sequences in ascending row order
+    // MFMA path: scratch holds the work lists (see attn_scratch_bytes); filled in by attn_prepare_lists
     void* scratch;
     size_t scratch_bytes;
     int32_t q_total_rows, k_total_rows;               // rows of the query-side / key-side streams
-    const void *qT, *kT, *vT, *doT;                   // filled by the launchers
-    long long ldTq, ldTk;
+    int32_t lists_ready;                              // the scratch already holds this call's work lists
+    const int32_t* n_items;                           // DEVICE [2]: query-side, key-side item counts
+    const int2 *items_q, *items_k;                    // DEVICE (sequence, 128-row block), longest first
+    int32_t max_items_q, max_items_k;                 // host upper bounds = grid sizes
 };
 
-long long attn_ld_t(int total_rows, int n_seq);
 size_t attn_scratch_bytes(int n_heads, int head_dim, int q_total_rows, int k_total_rows, int n_seq);
+ds_status attn_prepare_lists(AttnArgs& a, bool need_key_side, hipStream_t st);
 
 ds_status attn_fwd_generic(const AttnArgs& a, hipStream_t st);
 ds_status attn_bwd_generic(const AttnArgs& a, hipStream_t st);

@@ -23,9 +23,9 @@ ds_status launch_attention_bwd(const AttnArgs& a, bool force_generic, hipStream_
     ds_status s = check(a);
     if (s != DS_OK) return s;
     if (!a.d_o || !a.delta || !a.dq || !a.dk || !a.dv) return DS_EINVAL;
+    if (!force_generic && attn_mfma_supported(a)) return attn_bwd_mfma(a, st);      // computes delta itself
     s = attn_delta(a, st);
     if (s != DS_OK) return s;
-    if (!force_generic && attn_mfma_supported(a)) return attn_bwd_mfma(a, st);
     return attn_bwd_generic(a, st);
 }
 

@@ -11,15 +11,26 @@
 // the A operand lists the contraction index in the matching order,
 //     slot j of lane-half g  <->  row 16t + 8*(j/4) + 4*g + j%4           (t = 16-row step).
 //
-// Memory layout.  The second product needs its A operand transposed (V^T, K^T, Q^T, dO^T).  A
-// helper kernel (seq_transpose) writes feature-major copies of those tensors once per call, each
-// sequence padded with zeros to a multiple of 64 tokens and the 64 tokens of a tile stored in the
-// slot order above, so that one 16-byte LDS read yields a whole A fragment.  With that, EVERY tile
-// an attention kernel consumes is a set of 16-byte-aligned contiguous row segments and goes
-// global -> LDS directly (global_load_lds_dwordx4): no staging registers, double-buffered, the next
-// 64-row block in flight while the current one feeds the MFMAs.  LDS tiles carry a 16-byte XOR
-// swizzle (chosen per lane at load time) that makes the 16-byte fragment reads conflict-free on
-// gfx950's 64-bank LDS.
+// Memory.  Every tile is a block of 64 token rows x head_dim and goes global -> LDS directly
+// (global_load_lds_dwordx4): no staging registers, double-buffered, the next block in flight while
+// the current one feeds the MFMAs.  The first product reads its A fragments along the rows
+// (ds_read_b128).  The second product needs the same tile TRANSPOSED (V^T, K^T, Q^T, dO^T as the A
+// operand: 8 tokens in slot order for one feature per lane); gfx950's LDS transpose read
+// (ds_read_b64_tr_b16: within 16 lanes, lane i receives element i%4 of the 8 bytes addressed by
+// lanes i/4, 4+i/4, 8+i/4, 12+i/4) delivers exactly that from the token-major tile: two reads per
+// fragment, 4 consecutive tokens each.  No transposed copies exist in HBM.  Tiles carry a 16-byte
+// XOR swizzle (applied by choosing which global chunk each lane fetches) that keeps both access
+// patterns free of bank conflicts on the 64-bank LDS.
+//
+// Scheduling.  A small kernel lists the (sequence, 128-row block) work items of a call in descending
+// order of their trip count; the attention grids walk that list, heads fastest, so that long items
+// start first, equal items spread over the XCDs, and no work-group is launched for nothing.
+//
+// VALU economy (the matrix pipe is only as fast as the scalar work between its instructions): the
+// softmax scale rides in one FMA with the running max, the accumulator is rescaled only when some
+// lane's max moved, delta = rowsum(dO * O) is computed in the dQ kernel's prologue, and the dK/dV
+// kernel gets "score - lse/scale" and "dP - delta" straight from the matrix pipe by appending
+// [hi, lo] bf16 splits of the statistics to the contraction against a constant [-1, -1].
 //
 // Backward is split into a dQ kernel and a dK/dV kernel so that every output element has one
 // owner: no atomics, results are bit-reproducible.  Sequences are addressed through (row, length)
@@ -31,19 +42,21 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// LDS swizzles.  gfx950 serves a 16-byte LDS read for 16 lanes per cycle (64 banks), so 16
-// consecutive rows read at the same chunk index must fall into 16 different 16-byte units of a
-// 256-byte window: 256-byte rows XOR the chunk with row%16, 128-byte rows with (row/2)%8.
-template <int HD> __device__ __forceinline__ int off_rows(int row, int chunk) {      // [row][HD] tile
-    return HD == 128 ? row * 256 + ((chunk ^ (row & 15)) << 4) : row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
-}
-__device__ __forceinline__ int off_tr(int d, int kg) {                                // [d][64 slots] tile
-    return d * 128 + ((kg ^ ((d >> 1) & 7)) << 4);
-}
-__device__ __forceinline__ int slot_row(int t, int g, int j) { return 16 * t + 8 * (j >> 2) + 4 * g + (j & 3); }
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
 
-__device__ __forceinline__ uint32_t pick4(const uint4& v, int w) {
-    return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w));
+// LDS swizzle: the 16-byte chunk index of a row is XORed with swz(row).  Row-wise fragment reads
+// (16 lanes = 16 consecutive rows, same chunk) need the 16 rows in 16 different 16-byte units of a
+// 256-byte window; transpose reads (32 lanes = 4 consecutive rows x 64 bytes) need the 4 rows in 4
+// different 64-byte units.  Both hold for these bijections of the low row bits.
+template <int HD> __device__ __forceinline__ int swz(int row) {
+    return HD == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
+template <int HD> __device__ __forceinline__ int off_rows(int row, int chunk) {      // [row][HD] tile, 16-byte chunk
+    return row * (HD * 2) + ((chunk ^ swz<HD>(row)) << 4);
 }
 
 // accumulator registers 8u..8u+7 of a 32x32 tile -> one bf16 B fragment
@@ -52,6 +65,73 @@ __device__ __forceinline__ bf16x8_t frag_from_acc(const f32x16_t& a, int u) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) f[j] = (bf16_t)a[8 * u + j];
     return f;
+}
+
+// Per-lane byte offsets of the transposed A fragments of a token-major tile: fragment (t, dt) lists,
+// for feature dt*32 + lane%32, the tokens 16t + 4g + {0..3} (low read) and 16t + 8 + 4g + {0..3} (high read).
+template <int HD> struct TrOffsets {
+    int lo[HD / 32], hi[HD / 32];
+    __device__ __forceinline__ void init(int lane) {
+        const int i = lane & 15, halfd = (lane >> 4) & 1, g = lane >> 5;
+        const int r_lo = 4 * g + (i >> 2), r_hi = r_lo + 8;
+        const int c2 = halfd * 2 + ((i >> 1) & 1), byte = (i & 1) * 8;
+#pragma unroll
+        for (int dt = 0; dt < HD / 32; ++dt) {
+            lo[dt] = off_rows<HD>(r_lo, dt * 4 + c2) + byte;
+            hi[dt] = off_rows<HD>(r_hi, dt * 4 + c2) + byte;
+        }
+    }
+};
+template <int HD>
+__device__ __forceinline__ bf16x8_t read_tr(const char* tile, const TrOffsets<HD>& o, int t, int dt) {
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tile + t * (16 * HD * 2) + o.lo[dt]));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tile + t * (16 * HD * 2) + o.hi[dt]));
+    const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// Direct-to-LDS loader of 64-row tiles of one row-major tensor: each wavefront issues HD/32
+// instructions of 64 x 16 bytes per tile; the per-lane source pointers step by 64 rows.
+template <int HD> struct TileLoader {
+    static constexpr int PW = HD / 32;
+    const char* p[PW];
+    const bf16_t* base;
+    long long ld;
+    int n_valid, wave, lane;
+    __device__ __forceinline__ void setup(const bf16_t* base_, long long ld_, int n_valid_, int wave_, int lane_) {
+        base = base_; ld = ld_; n_valid = n_valid_; wave = wave_; lane = lane_;
+    }
+    // rows r0 .. r0+63, clamped to the last valid row (the duplicates are masked by the consumers)
+    __device__ __forceinline__ void seek(int r0) {
+#pragma unroll
+        for (int i = 0; i < PW; ++i) {
+            const int u = (wave * PW + i) * 64 + lane;
+            const int row = HD == 128 ? (u >> 4) : (u >> 3);
+            const int chunk = (HD == 128 ? (u & 15) : (u & 7)) ^ swz<HD>(row);
+            int r = r0 + row;
+            r = r < n_valid ? r : n_valid - 1;
+            p[i] = (const char*)(base + (long long)r * ld + chunk * 8);
+        }
+    }
+    __device__ __forceinline__ void next() {            // only when the next 64 rows are all valid
+        const long long step = 64 * ld * 2;
+#pragma unroll
+        for (int i = 0; i < PW; ++i) p[i] += step;
+    }
+    __device__ __forceinline__ void issue(char* lds) const {
+#pragma unroll
+        for (int i = 0; i < PW; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)p[i], (lptr_t)(lds + (wave * PW + i) * 1024), 16, 0, 0);
+    }
+    __device__ __forceinline__ void advance_to(int r0) {
+        if (r0 + 64 <= n_valid) next(); else seek(r0);
+    }
+};
+
+// this wavefront's direct loads have landed, then everybody's; the stage read in the previous step is free
+__device__ __forceinline__ void wait_tiles_and_sync() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
+    __builtin_amdgcn_s_barrier();
 }
 
 // store a transposed [HD x 32] accumulator block: lane column = row `row` of the output, 4 consecutive d per group
@@ -68,108 +148,68 @@ __device__ __forceinline__ void store_cols(const f32x16_t (&acc)[HD / 32], float
         }
 }
 
-
-typedef const __attribute__((address_space(1))) void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-// column of sequence s in a feature-major (transposed) copy; `row` is the sequence's first stream row
-__device__ __forceinline__ long long tcol(int row, int s) { return (long long)((row + 63) & ~63) + 128LL * s; }
-
-// ------------------------------------------------------------------------------------ seq_transpose
-// out[c][tcol(s) + 64*tile + p] = in[row_s + 64*tile + slot_row(p)][c]  (zero beyond the sequence's
-// length, up to the end of its last 64-token tile), for c in [0, C).  One work-group: 64 tokens x
-// 256 features; each lane loads 8 token rows x 16 bytes, transposes 8x8 in registers, stores 8
-// feature rows x 16 bytes; loads and stores form 128-byte contiguous segments.
-__global__ __launch_bounds__(256) void seq_transpose_kernel(int C, const int32_t* __restrict__ seq_row,
-                                                            const int32_t* __restrict__ seq_len,
-                                                            const bf16_t* __restrict__ in, long long ld_in,
-                                                            bf16_t* __restrict__ out, long long ld_out) {
-    const int s = blockIdx.z, tile = blockIdx.y;
-    const int len = seq_len[s];
-    if (tile * 64 >= len) return;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int bx = lane & 7, by = lane >> 3;
-    const int c0 = blockIdx.x * 256 + wave * 64 + bx * 8;
-    if (c0 >= C) return;
-    const int row0 = seq_row[s];
-    const int t = by >> 1, g = by & 1;
-    uint32_t v[8][4];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int q = tile * 64 + slot_row(t, g, j);
-        uint4 x = make_uint4(0u, 0u, 0u, 0u);
-        if (q < len) x = *reinterpret_cast<const uint4*>(in + (long long)(row0 + q) * ld_in + c0);
-        v[j][0] = x.x; v[j][1] = x.y; v[j][2] = x.z; v[j][3] = x.w;
+// ------------------------------------------------------------------------------------ work lists
+// items[0 .. n): (sequence, block) pairs of `block` rows each, in descending order of the number of
+// 64-row steps the block's work-group will take; n is written to *n_items.  One work-group.
+__global__ __launch_bounds__(1024) void attn_worklist_kernel(int n_seq, const int32_t* __restrict__ own_len,
+                                                             const int32_t* __restrict__ other_len, int causal,
+                                                             int key_side, int max_items, int2* __restrict__ items,
+                                                             int32_t* __restrict__ n_items) {
+    constexpr int NB = 1024;
+    __shared__ int hist[NB];
+    __shared__ int start[NB];
+    const int tid = threadIdx.x;
+    auto steps_of = [&](int own, int other, int blk) {
+        int n;
+        if (!key_side) {                               // query block: key steps it visits
+            const int end = causal ? min(other, (blk + 1) * 128) : other;
+            n = (end + 63) >> 6;
+        } else {                                       // key block: query steps it visits
+            const int begin = causal ? blk * 128 : 0;
+            n = (other - begin + 63) >> 6;
+        }
+        (void)own;
+        return min(max(n, 0), NB - 1);
+    };
+    hist[tid] = 0;
+    __syncthreads();
+    for (int s = tid; s < n_seq; s += NB) {
+        const int own = own_len[s], other = other_len[s];
+        for (int blk = 0; blk * 128 < own; ++blk) atomicAdd(&hist[steps_of(own, other, blk)], 1);
     }
-    bf16_t* o = out + tcol(row0, s) + tile * 64 + by * 8;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-        const int w = i >> 1;
-        uint4 r;
-        r.x = __builtin_amdgcn_perm(v[1][w], v[0][w], sel);
-        r.y = __builtin_amdgcn_perm(v[3][w], v[2][w], sel);
-        r.z = __builtin_amdgcn_perm(v[5][w], v[4][w], sel);
-        r.w = __builtin_amdgcn_perm(v[7][w], v[6][w], sel);
-        *reinterpret_cast<uint4*>(o + (long long)(c0 + i) * ld_out) = r;
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int b = NB - 1; b >= 0; --b) { start[b] = run; run += hist[b]; }
+        n_items[0] = min(run, max_items);
     }
-}
-
-// ------------------------------------------------------------------------------------ direct-to-LDS tile loads
-// Token-major tile: 64 rows (row0.., clamped to the last valid row) x HD columns of a row-major tensor.
-template <int HD>
-__device__ __forceinline__ void issue_rows(char* __restrict__ lds, const bf16_t* __restrict__ base, long long ld, int row0,
-                                           int n_valid, int wave, int lane) {
-    constexpr int PER_WAVE = HD / 32;                 // wavefront instructions (1 KB each) per wavefront
-#pragma unroll
-    for (int i = 0; i < PER_WAVE; ++i) {
-        const int u = (wave * PER_WAVE + i) * 64 + lane;
-        int row, chunk;
-        if (HD == 128) { row = u >> 4; chunk = (u & 15) ^ (row & 15); }
-        else           { row = u >> 3; chunk = (u & 7) ^ ((row >> 1) & 7); }
-        int r = row0 + row;
-        r = r < n_valid ? r : n_valid - 1;
-        __builtin_amdgcn_global_load_lds((gptr_t)(base + (long long)r * ld + chunk * 8),
-                                         (lptr_t)(lds + (wave * PER_WAVE + i) * 1024), 16, 0, 0);
+    __syncthreads();
+    for (int s = tid; s < n_seq; s += NB) {
+        const int own = own_len[s], other = other_len[s];
+        for (int blk = 0; blk * 128 < own; ++blk) {
+            const int pos = atomicAdd(&start[steps_of(own, other, blk)], 1);
+            if (pos < max_items) items[pos] = make_int2(s, blk);
+        }
     }
-}
-// Feature-major tile: HD rows x 64 tokens (already padded and slot-ordered by seq_transpose).
-template <int HD>
-__device__ __forceinline__ void issue_cols(char* __restrict__ lds, const bf16_t* __restrict__ base_t, long long ld_t,
-                                           long long col0, int wave, int lane) {
-    constexpr int PER_WAVE = HD / 32;
-#pragma unroll
-    for (int i = 0; i < PER_WAVE; ++i) {
-        const int u = (wave * PER_WAVE + i) * 64 + lane;
-        const int d = u >> 3;
-        const int chunk = (u & 7) ^ ((d >> 1) & 7);
-        __builtin_amdgcn_global_load_lds((gptr_t)(base_t + (long long)d * ld_t + col0 + chunk * 8),
-                                         (lptr_t)(lds + (wave * PER_WAVE + i) * 1024), 16, 0, 0);
-    }
-}
-
-// wait for this wavefront's outstanding direct loads, then for everybody's
-__device__ __forceinline__ void wait_tiles_and_sync() {
-    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
-    __builtin_amdgcn_s_barrier();
 }
 
 // ------------------------------------------------------------------------------------ forward
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    constexpr int TILE = 64 * HD * 2;                  // bytes of one K tile == one V^T tile
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int TILE = 64 * HD * 2;                  // bytes of one K tile == one V tile
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, g = lane >> 5;
-    const int s = a.n_seq - 1 - blockIdx.z, h = blockIdx.y;
+    const int item = blockIdx.x / a.n_heads, h = blockIdx.x - item * a.n_heads;
+    if (item >= a.n_items[0]) return;
+    const int2 it = a.items_q[item];
+    const int s = it.x, q0 = it.y * 128;
     const int ql = a.q_len[s], kl = a.k_len[s];
-    const int q0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * 128;
-    if (q0 >= ql) return;
-    const int krow = a.k_row[s];
-    const bf16_t* Q = (const bf16_t*)a.q + (long long)a.q_row[s] * a.ldq + h * HD;
-    const bf16_t* K = (const bf16_t*)a.k + (long long)krow * a.ldk + h * HD;
-    const bf16_t* Vt = (const bf16_t*)a.vT + (long long)h * HD * a.ldTk;
-    const long long kcol = tcol(krow, s);
+    const long long qrow0 = a.q_row[s];
+    const bf16_t* Q = (const bf16_t*)a.q + qrow0 * a.ldq + h * HD;
+    const bf16_t* K = (const bf16_t*)a.k + (long long)a.k_row[s] * a.ldk + h * HD;
+    const bf16_t* V = (const bf16_t*)a.v + (long long)a.k_row[s] * a.ldv + h * HD;
     const int qw0 = q0 + wave * 32;
     const int qi = qw0 + col;
     const int qi_c = qi < ql ? qi : ql - 1;
@@ -179,28 +219,40 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnArgs a) {
     for (int ks = 0; ks < HD / 16; ++ks)
         qf[ks] = *reinterpret_cast<const bf16x8_t*>(Q + (long long)qi_c * a.ldq + ks * 16 + g * 8);
 
+    TileLoader<HD> ldK, ldV;
+    ldK.setup(K, a.ldk, kl, wave, lane);
+    ldV.setup(V, a.ldv, kl, wave, lane);
+    TrOffsets<HD> tro;
+    tro.init(lane);
+    const int rbase = col * (HD * 2);
+    const int rsw = swz<HD>(col);
+
     f32x16_t oacc[HD / 32];
 #pragma unroll
     for (int dt = 0; dt < HD / 32; ++dt)
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[dt][e] = 0.f;
-    float m = -INFINITY, lsum = 0.f;
+    float m = -INFINITY, lsum = 0.f;                   // running max (in the exp2 domain) and sum
     const float c = a.scale * kLog2e;
 
     const int kv_end = CAUSAL ? min(kl, q0 + 128) : kl;
     const int wave_last = CAUSAL ? min(kl - 1, qw0 + 31) : kl - 1;     // last key this wavefront can see
     const int nb = (kv_end + 63) / 64;
-    issue_rows<HD>(smem, K, a.ldk, 0, kl, wave, lane);
-    issue_cols<HD>(smem + TILE, Vt, a.ldTk, kcol, wave, lane);
+    ldK.seek(0);
+    ldV.seek(0);
+    ldK.issue(smem);
+    ldV.issue(smem + TILE);
     for (int b = 0; b < nb; ++b) {
         const int kv0 = b * 64;
         char* sK = smem + (b & 1) * (2 * TILE);
-        char* sVt = sK + TILE;
+        char* sV = sK + TILE;
         wait_tiles_and_sync();                          // block b has landed; the other stage is free
         if (b + 1 < nb) {
             char* nK = smem + ((b + 1) & 1) * (2 * TILE);
-            issue_rows<HD>(nK, K, a.ldk, kv0 + 64, kl, wave, lane);
-            issue_cols<HD>(nK + TILE, Vt, a.ldTk, kcol + kv0 + 64, wave, lane);
+            ldK.advance_to(kv0 + 64);
+            ldV.advance_to(kv0 + 64);
+            ldK.issue(nK);
+            ldV.issue(nK + TILE);
         }
         if (kv0 > wave_last || qw0 >= ql) continue;
 
@@ -213,91 +265,112 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnArgs a) {
         for (int ks = 0; ks < HD / 16; ++ks)
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
-                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sK + off_rows<HD>(kt * 32 + col, ks * 2 + g));
+                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sK + kt * (32 * HD * 2) + rbase + (((ks * 2 + g) ^ rsw) << 4));
                 sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kt], 0, 0, 0);
             }
         const bool need_mask = (kv0 + 64 > kl) || (CAUSAL && kv0 + 63 > qw0);
+        if (need_mask) {
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int key = kv0 + kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+                    if (key >= kl || (CAUSAL && key > qi)) sacc[kt][e] = -INFINITY;
+                }
+        }
         float mx = -INFINITY;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float v = sacc[kt][e] * c;
-                if (need_mask) {
-                    const int key = kv0 + kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                    if (key >= kl || (CAUSAL && key > qi)) v = -INFINITY;
-                }
-                sacc[kt][e] = v;
-                mx = fmaxf(mx, v);
-            }
+            for (int e = 0; e < 16; e += 2) mx = fmaxf(mx, fmaxf(sacc[kt][e], sacc[kt][e + 1]));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        const float m_new = fmaxf(m, mx * c);
         float rs = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(sacc[kt][e] - m_new);
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt][e], c, -m_new));
                 sacc[kt][e] = p;
                 rs += p;
             }
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
         lsum = lsum * alpha + rs;
+        if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {      // some column's max moved: rescale the accumulator
+#pragma unroll
+            for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[dt][e] *= alpha;
+        }
         m = m_new;
-#pragma unroll
-        for (int dt = 0; dt < HD / 32; ++dt)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[dt][e] *= alpha;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const bf16x8_t pf = frag_from_acc(sacc[t >> 1], t & 1);
 #pragma unroll
             for (int dt = 0; dt < HD / 32; ++dt) {
-                const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(sVt + off_tr(dt * 32 + col, 2 * t + g));
+                const bf16x8_t vf = read_tr<HD>(sV, tro, t, dt);
                 oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[dt], 0, 0, 0);
             }
         }
     }
     lsum += __shfl_xor(lsum, 32, 64);
     if (qi < ql) {
-        const long long row = (long long)a.q_row[s] + qi;
-        store_cols<HD>(oacc, 1.0f / lsum, (bf16_t*)a.o + row * a.ldo + h * HD, g);
+        const long long row = qrow0 + qi;
+        store_cols<HD>(oacc, lsum > 0.f ? 1.0f / lsum : 0.f, (bf16_t*)a.o + row * a.ldo + h * HD, g);
         if (g == 0) a.lse[(size_t)h * a.lse_stride + row] = (m + __builtin_amdgcn_logf(lsum)) * kLn2;
     }
 }
 
-// ------------------------------------------------------------------------------------ backward: dQ
+// ------------------------------------------------------------------------------------ backward: dQ (and delta)
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TILE = 64 * HD * 2;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, g = lane >> 5;
-    const int s = a.n_seq - 1 - blockIdx.z, h = blockIdx.y;
+    const int item = blockIdx.x / a.n_heads, h = blockIdx.x - item * a.n_heads;
+    if (item >= a.n_items[0]) return;
+    const int2 it = a.items_q[item];
+    const int s = it.x, q0 = it.y * 128;
     const int ql = a.q_len[s], kl = a.k_len[s];
-    const int q0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * 128;
-    if (q0 >= ql) return;
     const long long qrow0 = a.q_row[s];
-    const int krow = a.k_row[s];
     const bf16_t* Q = (const bf16_t*)a.q + qrow0 * a.ldq + h * HD;
     const bf16_t* dO = (const bf16_t*)a.d_o + qrow0 * a.ldo + h * HD;
-    const bf16_t* K = (const bf16_t*)a.k + (long long)krow * a.ldk + h * HD;
-    const bf16_t* V = (const bf16_t*)a.v + (long long)krow * a.ldv + h * HD;
-    const bf16_t* Kt = (const bf16_t*)a.kT + (long long)h * HD * a.ldTk;
-    const long long kcol = tcol(krow, s);
+    const bf16_t* O = (const bf16_t*)a.o + qrow0 * a.ldo + h * HD;
+    const bf16_t* K = (const bf16_t*)a.k + (long long)a.k_row[s] * a.ldk + h * HD;
+    const bf16_t* V = (const bf16_t*)a.v + (long long)a.k_row[s] * a.ldv + h * HD;
     const int qw0 = q0 + wave * 32;
     const int qi = qw0 + col;
     const int qi_c = qi < ql ? qi : ql - 1;
 
+    TileLoader<HD> ldK, ldV;
+    ldK.setup(K, a.ldk, kl, wave, lane);
+    ldV.setup(V, a.ldv, kl, wave, lane);
+    ldK.seek(0);
+    ldV.seek(0);
+    ldK.issue(smem);
+    ldV.issue(smem + TILE);
+
     bf16x8_t qf[HD / 16], dof[HD / 16];
+    float delta = 0.f;                                  // rowsum(dO * O) of this lane's query, this head
 #pragma unroll
     for (int ks = 0; ks < HD / 16; ++ks) {
         qf[ks] = *reinterpret_cast<const bf16x8_t*>(Q + (long long)qi_c * a.ldq + ks * 16 + g * 8);
         dof[ks] = *reinterpret_cast<const bf16x8_t*>(dO + (long long)qi_c * a.ldo + ks * 16 + g * 8);
+        const bf16x8_t of = *reinterpret_cast<const bf16x8_t*>(O + (long long)qi_c * a.ldo + ks * 16 + g * 8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) delta = __builtin_fmaf((float)of[j], (float)dof[ks][j], delta);
     }
+    delta += __shfl_xor(delta, 32, 64);
+    if (g == 0 && qi < ql) a.delta[(size_t)h * a.lse_stride + qrow0 + qi] = delta;      // for the dK/dV kernel
     const float lse2 = a.lse[(size_t)h * a.lse_stride + qrow0 + qi_c] * kLog2e;
-    const float delta = a.delta[(size_t)h * a.lse_stride + qrow0 + qi_c];
     const float c = a.scale * kLog2e;
+
+    TrOffsets<HD> tro;
+    tro.init(lane);
+    const int rbase = col * (HD * 2);
+    const int rsw = swz<HD>(col);
 
     f32x16_t gacc[HD / 32];
 #pragma unroll
@@ -308,56 +381,51 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
     const int kv_end = CAUSAL ? min(kl, q0 + 128) : kl;
     const int wave_last = CAUSAL ? min(kl - 1, qw0 + 31) : kl - 1;
     const int nb = (kv_end + 63) / 64;
-    issue_rows<HD>(smem, K, a.ldk, 0, kl, wave, lane);
-    issue_rows<HD>(smem + TILE, V, a.ldv, 0, kl, wave, lane);
-    issue_cols<HD>(smem + 2 * TILE, Kt, a.ldTk, kcol, wave, lane);
     for (int b = 0; b < nb; ++b) {
         const int kv0 = b * 64;
-        char* sK = smem + (b & 1) * (3 * TILE);
+        char* sK = smem + (b & 1) * (2 * TILE);
         char* sV = sK + TILE;
-        char* sKt = sV + TILE;
         wait_tiles_and_sync();
         if (b + 1 < nb) {
-            char* n = smem + ((b + 1) & 1) * (3 * TILE);
-            issue_rows<HD>(n, K, a.ldk, kv0 + 64, kl, wave, lane);
-            issue_rows<HD>(n + TILE, V, a.ldv, kv0 + 64, kl, wave, lane);
-            issue_cols<HD>(n + 2 * TILE, Kt, a.ldTk, kcol + kv0 + 64, wave, lane);
+            char* n = smem + ((b + 1) & 1) * (2 * TILE);
+            ldK.advance_to(kv0 + 64);
+            ldV.advance_to(kv0 + 64);
+            ldK.issue(n);
+            ldV.issue(n + TILE);
         }
         if (kv0 > wave_last || qw0 >= ql) continue;
-
-        f32x16_t sacc[2], pacc[2];
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) { sacc[kt][e] = 0.f; pacc[kt][e] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < HD / 16; ++ks)
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sK + off_rows<HD>(kt * 32 + col, ks * 2 + g));
-                sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kt], 0, 0, 0);
-                const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(sV + off_rows<HD>(kt * 32 + col, ks * 2 + g));
-                pacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], pacc[kt], 0, 0, 0);
-            }
         const bool need_mask = (kv0 + 64 > kl) || (CAUSAL && kv0 + 63 > qw0);
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < 2; ++kt) {
+            if (kv0 + kt * 32 > wave_last) continue;                    // the half beyond the last key this wavefront sees
+            f32x16_t sacc, pacc;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < HD / 16; ++ks) {
+                const int o = kt * (32 * HD * 2) + rbase + (((ks * 2 + g) ^ rsw) << 4);
+                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sK + o);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
+                const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(sV + o);
+                pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], pacc, 0, 0, 0);
+            }
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                float p = __builtin_amdgcn_exp2f(sacc[kt][e] * c - lse2);
+                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[e], c, -lse2));
                 if (need_mask) {
                     const int key = kv0 + kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
                     if (key >= kl || (CAUSAL && key > qi)) p = 0.f;
                 }
-                sacc[kt][e] = p * (pacc[kt][e] - delta);          // dS^T
+                sacc[e] = p * (pacc[e] - delta);                          // dS^T
             }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const bf16x8_t dsf = frag_from_acc(sacc[t >> 1], t & 1);
+            for (int u = 0; u < 2; ++u) {
+                const bf16x8_t dsf = frag_from_acc(sacc, u);
 #pragma unroll
-            for (int dt = 0; dt < HD / 32; ++dt) {
-                const bf16x8_t kt_f = *reinterpret_cast<const bf16x8_t*>(sKt + off_tr(dt * 32 + col, 2 * t + g));
-                gacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_f, dsf, gacc[dt], 0, 0, 0);
+                for (int dt = 0; dt < HD / 32; ++dt) {
+                    const bf16x8_t kt_f = read_tr<HD>(sK, tro, 2 * kt + u, dt);
+                    gacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_f, dsf, gacc[dt], 0, 0, 0);
+                }
             }
         }
     }
@@ -365,30 +433,59 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------ backward: dK, dV
+// LDS, two stages of: Q tile, dO tile ([64][HD]) and the two statistics tiles ([64 rows][8] bf16:
+// {hi, lo, 0 x 6} of lse/scale and of delta).
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
-    // dynamic LDS, two stages of: Q, dO ([64][HD]), Q^T, dO^T ([HD][64 slots]); then 2 x (64 lse + 64 delta)
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TILE = 64 * HD * 2;
-    float* s_stat = reinterpret_cast<float*>(smem + 8 * TILE);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int STAGE = 2 * TILE + 2048;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, g = lane >> 5;
-    const int s = a.n_seq - 1 - blockIdx.z, h = blockIdx.y;
+    const int item = blockIdx.x / a.n_heads, h = blockIdx.x - item * a.n_heads;
+    if (item >= a.n_items[1]) return;
+    const int2 it = a.items_k[item];
+    const int s = it.x, k0 = it.y * 128;
     const int ql = a.q_len[s], kl = a.k_len[s];
-    const int k0 = blockIdx.x * 128;
-    if (k0 >= kl) return;
-    const int qrow = a.q_row[s];
-    const long long qrow0 = qrow, krow0 = a.k_row[s];
+    const long long qrow0 = a.q_row[s], krow0 = a.k_row[s];
     const bf16_t* Q = (const bf16_t*)a.q + qrow0 * a.ldq + h * HD;
     const bf16_t* dO = (const bf16_t*)a.d_o + qrow0 * a.ldo + h * HD;
     const bf16_t* K = (const bf16_t*)a.k + krow0 * a.ldk + h * HD;
     const bf16_t* V = (const bf16_t*)a.v + krow0 * a.ldv + h * HD;
-    const bf16_t* Qt = (const bf16_t*)a.qT + (long long)h * HD * a.ldTq;
-    const bf16_t* dOt = (const bf16_t*)a.doT + (long long)h * HD * a.ldTq;
-    const long long qcol = tcol(qrow, s);
     const int kw0 = k0 + wave * 32;
     const int ki = kw0 + col;
     const int ki_c = ki < kl ? ki : kl - 1;
+
+    const int q_begin = CAUSAL ? k0 : 0;
+    const int nb = (ql - q_begin + 63) / 64;            // >= 1: a key block exists only below the query count when causal
+    TileLoader<HD> ldQ, ldO;
+    ldQ.setup(Q, a.ldq, ql, wave, lane);
+    ldO.setup(dO, a.ldo, ql, wave, lane);
+    if (nb > 0) {
+        ldQ.seek(q_begin);
+        ldO.seek(q_begin);
+        ldQ.issue(smem);
+        ldO.issue(smem + TILE);
+    }
+    const float* lse_row = a.lse + (size_t)h * a.lse_stride + qrow0;
+    const float* delta_row = a.delta + (size_t)h * a.lse_stride + qrow0;
+    const float inv_scale = 1.0f / a.scale;
+    auto load_stats = [&](int b, float& l, float& dl) {
+        if (tid < 64) {
+            int r = q_begin + b * 64 + tid;
+            r = r < ql ? r : ql - 1;
+            l = lse_row[r] * inv_scale;
+            dl = delta_row[r];
+        }
+    };
+    auto split = [](float v) {                          // {hi, lo} bf16 with hi + lo = v to ~2^-17 relative
+        const bf16_t hi = (bf16_t)v;
+        const bf16_t lo = (bf16_t)(v - (float)hi);
+        return (uint32_t)__builtin_bit_cast(unsigned short, hi) | ((uint32_t)__builtin_bit_cast(unsigned short, lo) << 16);
+    };
+    float st_l = 0.f, st_d = 0.f;
+    if (nb > 0) load_stats(0, st_l, st_d);
 
     bf16x8_t kf[HD / 16], vf[HD / 16];
 #pragma unroll
@@ -396,92 +493,86 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
         kf[ks] = *reinterpret_cast<const bf16x8_t*>(K + (long long)ki_c * a.ldk + ks * 16 + g * 8);
         vf[ks] = *reinterpret_cast<const bf16x8_t*>(V + (long long)ki_c * a.ldv + ks * 16 + g * 8);
     }
+    bf16x8_t neg_ones;                                  // contraction slots 0, 1 (lane half 0) pick -hi - lo
+#pragma unroll
+    for (int j = 0; j < 8; ++j) neg_ones[j] = (bf16_t)((g == 0 && j < 2) ? -1.0f : 0.0f);
     const float c = a.scale * kLog2e;
+
+    TrOffsets<HD> tro;
+    tro.init(lane);
+    const int rbase = col * (HD * 2);
+    const int rsw = swz<HD>(col);
+
     f32x16_t dkacc[HD / 32], dvacc[HD / 32];
 #pragma unroll
     for (int dt = 0; dt < HD / 32; ++dt)
 #pragma unroll
         for (int e = 0; e < 16; ++e) { dkacc[dt][e] = 0.f; dvacc[dt][e] = 0.f; }
 
-    const int q_begin = CAUSAL ? (k0 / 64) * 64 : 0;
-    const int nb = (ql - q_begin + 63) / 64;
-    const float* lse_row = a.lse + (size_t)h * a.lse_stride + qrow0;
-    const float* delta_row = a.delta + (size_t)h * a.lse_stride + qrow0;
-    auto issue_block = [&](int b) {
-        const int q0 = q_begin + b * 64;
-        char* n = smem + (b & 1) * (4 * TILE);
-        issue_rows<HD>(n, Q, a.ldq, q0, ql, wave, lane);
-        issue_rows<HD>(n + TILE, dO, a.ldo, q0, ql, wave, lane);
-        issue_cols<HD>(n + 2 * TILE, Qt, a.ldTq, qcol + q0, wave, lane);
-        issue_cols<HD>(n + 3 * TILE, dOt, a.ldTq, qcol + q0, wave, lane);
-    };
-    auto load_stats = [&](int b, float& l, float& dl) {
-        if (tid < 64) {
-            int r = q_begin + b * 64 + tid;
-            r = r < ql ? r : ql - 1;
-            l = lse_row[r] * kLog2e;
-            dl = delta_row[r];
-        }
-    };
-    float st_l = 0.f, st_d = 0.f;
-    issue_block(0);
-    load_stats(0, st_l, st_d);
     for (int b = 0; b < nb; ++b) {
         const int q0 = q_begin + b * 64;
-        char* sQ = smem + (b & 1) * (4 * TILE);
+        char* sQ = smem + (b & 1) * STAGE;
         char* sdO = sQ + TILE;
-        char* sQt = sdO + TILE;
-        char* sdOt = sQt + TILE;
-        float* s_lse = s_stat + (b & 1) * 128;
-        float* s_delta = s_lse + 64;
+        char* s_lse = sdO + TILE;
+        char* s_delta = s_lse + 1024;
         __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this block's tiles and statistics have landed
-        if (tid < 64) { s_lse[tid] = st_l; s_delta[tid] = st_d; }
+        if (tid < 64) {
+            *reinterpret_cast<uint4*>(s_lse + tid * 16) = make_uint4(split(st_l), 0u, 0u, 0u);
+            *reinterpret_cast<uint4*>(s_delta + tid * 16) = make_uint4(split(st_d), 0u, 0u, 0u);
+        }
         __builtin_amdgcn_s_waitcnt(0xC07F);             // lgkmcnt(0): the statistics are in LDS
         __builtin_amdgcn_s_barrier();
         if (b + 1 < nb) {
-            issue_block(b + 1);
+            char* n = smem + ((b + 1) & 1) * STAGE;
+            ldQ.advance_to(q0 + 64);
+            ldO.advance_to(q0 + 64);
+            ldQ.issue(n);
+            ldO.issue(n + TILE);
             load_stats(b + 1, st_l, st_d);
         }
         if (kw0 >= kl || (CAUSAL && q0 + 63 < kw0)) continue;
-
-        f32x16_t sacc[2], pacc[2];
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) { sacc[qt][e] = 0.f; pacc[qt][e] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < HD / 16; ++ks)
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt) {
-                const bf16x8_t qf = *reinterpret_cast<const bf16x8_t*>(sQ + off_rows<HD>(qt * 32 + col, ks * 2 + g));
-                sacc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ks], sacc[qt], 0, 0, 0);
-                const bf16x8_t dof = *reinterpret_cast<const bf16x8_t*>(sdO + off_rows<HD>(qt * 32 + col, ks * 2 + g));
-                pacc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dof, vf[ks], pacc[qt], 0, 0, 0);
-            }
         const bool need_mask = (q0 + 64 > ql) || (CAUSAL && q0 < kw0 + 31);
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
+        for (int qt = 0; qt < 2; ++qt) {
+            if (q0 + qt * 32 >= ql || (CAUSAL && q0 + qt * 32 + 31 < kw0)) continue;   // a half with no visible query
+            f32x16_t sacc, pacc;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int qloc = qt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                float p = __builtin_amdgcn_exp2f(sacc[qt][e] * c - s_lse[qloc]);
-                if (need_mask) {
-                    const int q = q0 + qloc;
-                    if (q >= ql || (CAUSAL && q < ki)) p = 0.f;
-                }
-                sacc[qt][e] = p;                                       // P
-                pacc[qt][e] = p * (pacc[qt][e] - s_delta[qloc]);       // dS
+            for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < HD / 16; ++ks) {
+                const int o = qt * (32 * HD * 2) + rbase + (((ks * 2 + g) ^ rsw) << 4);
+                const bf16x8_t qf = *reinterpret_cast<const bf16x8_t*>(sQ + o);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ks], sacc, 0, 0, 0);
+                const bf16x8_t dof = *reinterpret_cast<const bf16x8_t*>(sdO + o);
+                pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dof, vf[ks], pacc, 0, 0, 0);
+            }
+            {
+                const bf16x8_t la = *reinterpret_cast<const bf16x8_t*>(s_lse + (qt * 32 + col) * 16);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(la, neg_ones, sacc, 0, 0, 0);       // score - lse/scale
+                const bf16x8_t da = *reinterpret_cast<const bf16x8_t*>(s_delta + (qt * 32 + col) * 16);
+                pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, neg_ones, pacc, 0, 0, 0);       // dP - delta
             }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const bf16x8_t pf = frag_from_acc(sacc[t >> 1], t & 1);
-            const bf16x8_t dsf = frag_from_acc(pacc[t >> 1], t & 1);
+            for (int e = 0; e < 16; ++e) {
+                float p = __builtin_amdgcn_exp2f(sacc[e] * c);
+                if (need_mask) {
+                    const int q = q0 + qt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+                    if (q >= ql || (CAUSAL && q < ki)) p = 0.f;
+                }
+                sacc[e] = p;                                           // P
+                pacc[e] = p * pacc[e];                                 // dS
+            }
 #pragma unroll
-            for (int dt = 0; dt < HD / 32; ++dt) {
-                const bf16x8_t dot_f = *reinterpret_cast<const bf16x8_t*>(sdOt + off_tr(dt * 32 + col, 2 * t + g));
-                dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot_f, pf, dvacc[dt], 0, 0, 0);
-                const bf16x8_t qt_f = *reinterpret_cast<const bf16x8_t*>(sQt + off_tr(dt * 32 + col, 2 * t + g));
-                dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt_f, dsf, dkacc[dt], 0, 0, 0);
+            for (int u = 0; u < 2; ++u) {
+                const bf16x8_t pf = frag_from_acc(sacc, u);
+                const bf16x8_t dsf = frag_from_acc(pacc, u);
+#pragma unroll
+                for (int dt = 0; dt < HD / 32; ++dt) {
+                    const bf16x8_t dot_f = read_tr<HD>(sdO, tro, 2 * qt + u, dt);
+                    dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot_f, pf, dvacc[dt], 0, 0, 0);
+                    const bf16x8_t qt_f = read_tr<HD>(sQ, tro, 2 * qt + u, dt);
+                    dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt_f, dsf, dkacc[dt], 0, 0, 0);
+                }
             }
         }
     }
@@ -489,14 +580,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
         store_cols<HD>(dkacc, a.scale, (bf16_t*)a.dk + (krow0 + ki) * a.ldk + h * HD, g);
         store_cols<HD>(dvacc, 1.0f, (bf16_t*)a.dv + (krow0 + ki) * a.ldv + h * HD, g);
     }
-}
-
-ds_status seq_transpose(int C, int n_seq, int max_len, const int32_t* row, const int32_t* len, const void* in, long long ld_in,
-                        void* out, long long ld_out, hipStream_t st) {
-    dim3 grid((C + 255) / 256, (max_len + 63) / 64, n_seq);
-    hipLaunchKernelGGL(seq_transpose_kernel, grid, dim3(256), 0, st, C, row, len, (const bf16_t*)in, ld_in, (bf16_t*)out, ld_out);
-    DS_LAUNCH_CHECK();
-    return DS_OK;
 }
 
 template <class Kern>
@@ -515,8 +598,7 @@ ds_status fwd_launch(const AttnArgs& a, hipStream_t st) {
     const int smem = 4 * (64 * HD * 2);
     ds_status r = set_smem(kern, smem, attr);
     if (r != DS_OK) return r;
-    dim3 grid((a.max_q_len + 127) / 128, a.n_heads, a.n_seq);
-    hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)a.max_items_q * a.n_heads), dim3(256), smem, st, a);
     DS_LAUNCH_CHECK();
     return DS_OK;
 }
@@ -526,30 +608,27 @@ ds_status bwd_launch(const AttnArgs& a, hipStream_t st) {
     static bool attr_q = false, attr_kv = false;
     auto kq = attn_bwd_dq_mfma_kernel<HD, CAUSAL>;
     auto kkv = attn_bwd_dkv_mfma_kernel<HD, CAUSAL>;
-    const int smem_q = 6 * (64 * HD * 2);
-    const int smem_kv = 8 * (64 * HD * 2) + 256 * 4;
+    const int smem_q = 4 * (64 * HD * 2);
+    const int smem_kv = 2 * (2 * (64 * HD * 2) + 2048);
     ds_status r = set_smem(kq, smem_q, attr_q);
     if (r != DS_OK) return r;
     r = set_smem(kkv, smem_kv, attr_kv);
     if (r != DS_OK) return r;
-    dim3 gq((a.max_q_len + 127) / 128, a.n_heads, a.n_seq);
-    hipLaunchKernelGGL(kq, gq, dim3(256), smem_q, st, a);
+    hipLaunchKernelGGL(kq, dim3((unsigned)a.max_items_q * a.n_heads), dim3(256), smem_q, st, a);
     DS_LAUNCH_CHECK();
-    dim3 gk((a.max_k_len + 127) / 128, a.n_heads, a.n_seq);
-    hipLaunchKernelGGL(kkv, gk, dim3(256), smem_kv, st, a);
+    hipLaunchKernelGGL(kkv, dim3((unsigned)a.max_items_k * a.n_heads), dim3(256), smem_kv, st, a);
     DS_LAUNCH_CHECK();
     return DS_OK;
 }
 
+int items_bound(int total_rows, int n_seq) { return total_rows / 128 + n_seq; }
+
 }  // namespace
 
-// Leading dimension (in tokens) of a feature-major copy of a stream of `total_rows` rows holding n_seq sequences.
-long long attn_ld_t(int total_rows, int n_seq) { return (long long)((total_rows + 63) & ~63) + 128LL * n_seq + 64; }
-
+// Scratch: two work lists (query-side and key-side blocks) and their two counters.
 size_t attn_scratch_bytes(int n_heads, int head_dim, int q_total_rows, int k_total_rows, int n_seq) {
-    const size_t d = (size_t)n_heads * head_dim;
-    // forward needs V^T; backward needs Q^T, dO^T (query side) and K^T (key side)
-    return 2 * d * (size_t)attn_ld_t(q_total_rows, n_seq) * 2 + d * (size_t)attn_ld_t(k_total_rows, n_seq) * 2 + 1024;
+    (void)n_heads; (void)head_dim;
+    return 256 + sizeof(int2) * ((size_t)items_bound(q_total_rows, n_seq) + (size_t)items_bound(k_total_rows, n_seq));
 }
 
 bool attn_mfma_supported(const AttnArgs& a) {
@@ -562,15 +641,34 @@ bool attn_mfma_supported(const AttnArgs& a) {
     if (!a.scratch || !al(a.scratch)) return false;
     if (a.q_total_rows <= 0 || a.k_total_rows <= 0) return false;
     if (a.scratch_bytes < attn_scratch_bytes(a.n_heads, a.head_dim, a.q_total_rows, a.k_total_rows, a.n_seq)) return false;
+    if ((long long)items_bound(a.q_total_rows, a.n_seq) * a.n_heads > 0x7fffffffLL) return false;
+    if ((long long)items_bound(a.k_total_rows, a.n_seq) * a.n_heads > 0x7fffffffLL) return false;
     return true;
+}
+
+// Lay the work lists out in the scratch buffer and, unless the caller says they are already there, build them.
+ds_status attn_prepare_lists(AttnArgs& a, bool need_key_side, hipStream_t st) {
+    char* base = (char*)a.scratch;
+    a.n_items = (const int32_t*)base;
+    a.max_items_q = items_bound(a.q_total_rows, a.n_seq);
+    a.max_items_k = items_bound(a.k_total_rows, a.n_seq);
+    a.items_q = (const int2*)(base + 256);
+    a.items_k = a.items_q + a.max_items_q;
+    if (a.lists_ready) return DS_OK;
+    hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(1024), 0, st, a.n_seq, a.q_len, a.k_len, a.mask, 0, a.max_items_q,
+                       (int2*)a.items_q, (int32_t*)base);
+    DS_LAUNCH_CHECK();
+    if (need_key_side) {
+        hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(1024), 0, st, a.n_seq, a.k_len, a.q_len, a.mask, 1, a.max_items_k,
+                           (int2*)a.items_k, (int32_t*)base + 1);
+        DS_LAUNCH_CHECK();
+    }
+    return DS_OK;
 }
 
 ds_status attn_fwd_mfma(const AttnArgs& a0, hipStream_t st) {
     AttnArgs a = a0;
-    const int d = a.n_heads * a.head_dim;
-    a.ldTk = attn_ld_t(a.k_total_rows, a.n_seq);
-    a.vT = a.scratch;
-    ds_status r = seq_transpose(d, a.n_seq, a.max_k_len, a.k_row, a.k_len, a.v, a.ldv, a.scratch, a.ldTk, st);
+    ds_status r = attn_prepare_lists(a, false, st);
     if (r != DS_OK) return r;
     if (a.head_dim == 128) return a.mask ? fwd_launch<128, true>(a, st) : fwd_launch<128, false>(a, st);
     return a.mask ? fwd_launch<64, true>(a, st) : fwd_launch<64, false>(a, st);
@@ -578,18 +676,7 @@ ds_status attn_fwd_mfma(const AttnArgs& a0, hipStream_t st) {
 
 ds_status attn_bwd_mfma(const AttnArgs& a0, hipStream_t st) {
     AttnArgs a = a0;
-    const size_t d = (size_t)a.n_heads * a.head_dim;
-    a.ldTq = attn_ld_t(a.q_total_rows, a.n_seq);
-    a.ldTk = attn_ld_t(a.k_total_rows, a.n_seq);
-    char* base = (char*)a.scratch;
-    a.qT = base;
-    a.doT = base + d * a.ldTq * 2;
-    a.kT = base + 2 * d * a.ldTq * 2;
-    ds_status r = seq_transpose((int)d, a.n_seq, a.max_q_len, a.q_row, a.q_len, a.q, a.ldq, (void*)a.qT, a.ldTq, st);
-    if (r != DS_OK) return r;
-    r = seq_transpose((int)d, a.n_seq, a.max_q_len, a.q_row, a.q_len, a.d_o, a.ldo, (void*)a.doT, a.ldTq, st);
-    if (r != DS_OK) return r;
-    r = seq_transpose((int)d, a.n_seq, a.max_k_len, a.k_row, a.k_len, a.k, a.ldk, (void*)a.kT, a.ldTk, st);
+    ds_status r = attn_prepare_lists(a, true, st);
     if (r != DS_OK) return r;
     if (a.head_dim == 128) return a.mask ? bwd_launch<128, true>(a, st) : bwd_launch<128, false>(a, st);
     return a.mask ? bwd_launch<64, true>(a, st) : bwd_launch<64, false>(a, st);

@@ -373,7 +373,7 @@ struct Ops {
         a.o = const_cast<void*>(o); a.d_o = d_o; a.lse = const_cast<float*>(lse); a.delta = s->delta;
         char* g = (char*)dqkv;
         a.dq = g; a.dk = g + (size_t)d * s->es; a.dv = g + (size_t)2 * d * s->es;
-        s->launches += 6;
+        s->launches += 4;
         DS_TRY(timed(s, DS_PROF_ATTN_BWD, st, [&] { return launch_attention_bwd(a, false, st); }));
         return zero_pad(sm, dqkv, 3 * d);
     }
@@ -600,7 +600,7 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
             a.k = b.kvc; a.v = (const char*)b.kvc + (size_t)d * s->es; a.ldk = a.ldv = 2 * d;
             a.o = b.oc; a.d_o = s->d_o; a.lse = b.lsec; a.delta = s->delta;
             a.dq = s->dqc; a.dk = s->dkvc; a.dv = (char*)s->dkvc + (size_t)d * s->es;
-            s->launches += 6;
+            s->launches += 4;
             DS_TRY(timed(s, DS_PROF_ATTN_BWD, st, [&] { return launch_attention_bwd(a, false, st); }));
             DS_TRY(op.zero_pad(D, s->dqc, d));
             DS_TRY(op.zero_pad(E, s->dkvc, 2 * d));
