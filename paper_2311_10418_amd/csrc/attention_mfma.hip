@@ -44,8 +44,6 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
-typedef const __attribute__((address_space(1))) void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
 typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
 
 // LDS swizzle: the 16-byte chunk index of a row is XORed with swz(row).  Row-wise fragment reads
@@ -121,7 +119,7 @@ template <int HD> struct TileLoader {
     __device__ __forceinline__ void issue(char* lds) const {
 #pragma unroll
         for (int i = 0; i < PW; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)p[i], (lptr_t)(lds + (wave * PW + i) * 1024), 16, 0, 0);
+            lds_dma16(p[i], lds + (wave * PW + i) * 1024);
     }
     __device__ __forceinline__ void advance_to(int r0) {
         if (r0 + 64 <= n_valid) next(); else seek(r0);

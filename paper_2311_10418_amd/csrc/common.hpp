@@ -87,6 +87,18 @@ __device__ __forceinline__ float gelu_grad_f(float z) {
     return 0.5f * (1.0f + t) + 0.5f * z * (1.0f - t * t) * du;
 }
 
+// One direct global -> LDS transfer, 16 bytes per lane (global_load_lds_dwordx4): the wavefront's 64 chunks land at
+// lds_addr + 16 * lane.  lds_addr must be wavefront-uniform.  Issued through inline assembly on purpose: the
+// compiler orders every later LDS read it cannot disambiguate (all transpose reads) behind a FULL vector-memory
+// wait when it sees such a transfer in flight, which would serialise the prefetch pipelines built on it.  Every
+// consumer here synchronises explicitly instead (s_waitcnt vmcnt(n) for its own transfers, then s_barrier).
+// Compiler-generated vmcnt waits for ordinary loads stay correct: unseen transfers only make them wait longer.
+__device__ __forceinline__ void lds_dma16(const void* gptr, const void* lds_ptr) {
+    const uint32_t lds_addr =
+        __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds_ptr);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_addr) : "memory", "m0");
+}
+
 static inline size_t dtype_size(int32_t dtype) { return dtype == DS_DTYPE_BF16 ? 2 : 4; }
 
 // ---- launchers shared between translation units (all enqueue on `st`, return ds_status)

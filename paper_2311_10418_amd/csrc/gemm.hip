@@ -448,15 +448,23 @@ constexpr int NT_DK = 32, NT_NS = 4, NT_HALF = 256 * NT_DK * 2, NT_STAGE = 2 * N
 #define NT_WN 4
 #endif
 
+// 16 zero bytes: the source of every chunk past the end of a ragged contraction (TN form)
+__device__ uint4 g_zero16;
+
 // WM x WN wavefronts per work-group; each owns a (256/WM) x (256/WN) accumulator block.
-template <int EPI, int WM, int WN>
+//
+// TN form (weight gradients): C[M,N] = A[K,M]^T * B[K,N], both operands row-major with the
+// contraction index (tokens) as the ROW.  A K tile is then 32 rows of 512 contiguous bytes per
+// operand, fetched as whole rows, and the MFMA fragments (8 consecutive k for one m or n per lane)
+// come out of LDS through the transpose read ds_read_b64_tr_b16, 4 k-rows per read; both operands
+// use the same k order, so the contraction is unchanged.  K may be ragged: rows past the end read
+// zeros.  This form needs no transposed copies of the activations.
+template <int EPI, int WM, int WN, bool TNF>
 __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
                                                                        const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
                                                                        int tiles_m, int tiles_n, int splits,
                                                                        float* __restrict__ split_ws, GemmEpi p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    typedef const __attribute__((address_space(1))) void* gptr_t;
-    typedef __attribute__((address_space(3))) void* lptr_t;
     constexpr int NW = WM * WN;                    // wavefronts
     constexpr int TM = 256 / WM / 32, TN = 256 / WN / 32;   // 32x32 MFMA tiles per wavefront
     constexpr int LPW = 16 / NW;                   // direct-load instructions per operand per wavefront per K tile
@@ -490,7 +498,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
     }
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const int nt_total = K / NT_DK;
+    const int nt_total = TNF ? (K + NT_DK - 1) / NT_DK : K / NT_DK;
     const int per_split = (nt_total + splits - 1) / splits;
     const int t_begin = split * per_split;
     const int t_end = (t_begin + per_split) < nt_total ? (t_begin + per_split) : nt_total;
@@ -505,34 +513,68 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
 
     if (t_begin < t_end) {
         uint32_t offA[LPW], offB[LPW];
+        int krow[LPW];                                              // TN: k-row of this lane's chunk within a tile
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int u = (wave * LPW + i) * 64 + lane;            // 16-byte unit of the 256x4 tile
-            const int row = u >> 2, slot = u & 3;
-            const int chunk = slot ^ ((row >> 2) & 3);
-            int ra_ = m0 + row;
-            ra_ = ra_ < M ? ra_ : M - 1;                            // rows past the edge: clamped, never stored
-            offA[i] = (uint32_t)(((long long)(ra_ - m0) * K + chunk * 8) * 2);
-            offB[i] = (uint32_t)(((long long)row * K + chunk * 8) * 2);
+            const int u = (wave * LPW + i) * 64 + lane;
+            if constexpr (!TNF) {                                    // 16-byte unit of the 256 x 4 tile
+                const int row = u >> 2, slot = u & 3;
+                const int chunk = slot ^ ((row >> 2) & 3);
+                int ra_ = m0 + row;
+                ra_ = ra_ < M ? ra_ : M - 1;                        // rows past the edge: clamped, never stored
+                offA[i] = (uint32_t)(((long long)(ra_ - m0) * K + chunk * 8) * 2);
+                offB[i] = (uint32_t)(((long long)row * K + chunk * 8) * 2);
+                krow[i] = 0;
+            } else {                                                // 16-byte unit of the 32 x 32 tile (512-byte rows)
+                const int row = u >> 5, pos = u & 31;
+                const int chunk = (((pos >> 2) ^ (row & 3)) << 2) | (pos & 3);
+                offA[i] = (uint32_t)(((long long)row * M + chunk * 8) * 2);
+                offB[i] = (uint32_t)(((long long)row * N + chunk * 8) * 2);
+                krow[i] = row;
+            }
         }
-        const char* pa = reinterpret_cast<const char*>(A) + (long long)m0 * K * 2;
-        const char* pb = reinterpret_cast<const char*>(B) + (long long)n0 * K * 2;
+        const char* pa = reinterpret_cast<const char*>(A) + (TNF ? (long long)m0 * 2 : (long long)m0 * K * 2);
+        const char* pb = reinterpret_cast<const char*>(B) + (TNF ? (long long)n0 * 2 : (long long)n0 * K * 2);
+        const long long tile_step_a = TNF ? (long long)NT_DK * M * 2 : NT_DK * 2;
+        const long long tile_step_b = TNF ? (long long)NT_DK * N * 2 : NT_DK * 2;
         const int frag_row = lane & 31, frag_half = lane >> 5;
         const int t_last = t_end - 1;
         auto issue = [&](int tile, int stage) {
             tile = tile < t_last ? tile : t_last;
-            const char* ga = pa + (long long)tile * (NT_DK * 2);
-            const char* gb = pb + (long long)tile * (NT_DK * 2);
+            const char* ga = pa + tile * tile_step_a;
+            const char* gb = pb + tile * tile_step_b;
             char* la = smem + stage * NT_STAGE + wave * (LPW * 1024);
             char* lb = la + NT_HALF;
+            const int k_left = TNF ? K - tile * NT_DK : NT_DK;      // valid k-rows of this tile
 #pragma unroll
             for (int i = 0; i < LPW; ++i) {
-                __builtin_amdgcn_global_load_lds((gptr_t)(ga + offA[i]), (lptr_t)(la + i * 1024), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((gptr_t)(gb + offB[i]), (lptr_t)(lb + i * 1024), 16, 0, 0);
+                const char* sa = ga + offA[i];
+                const char* sb = gb + offB[i];
+                if (TNF && k_left < NT_DK && krow[i] >= k_left) {
+                    sa = reinterpret_cast<const char*>(&g_zero16);
+                    sb = sa;
+                }
+                lds_dma16(sa, la + i * 1024);
+                lds_dma16(sb, lb + i * 1024);
             }
         };
-        // 64-byte rows: 16 consecutive rows at one chunk index must hit 16 different 16-byte units
+        // NT: 64-byte rows: 16 consecutive rows at one chunk index must hit 16 different 16-byte units
         auto off32 = [](int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4); };
+        // TN: 512-byte rows; a transpose read covers 4 consecutive k-rows x 64 bytes per 32 lanes, so the 64-byte
+        // unit index is XORed with row%4.  Lane (i = lane%16, hm = lane/16%2, g = lane/32) addresses k-row
+        // 4g + i/4 (+8 for the second read, +16 per k step) at features hm*16 + (i%4)*4 of a 32-feature unit.
+        const int tr_x = (lane >> 2) & 3;
+        const int tr_base = (4 * (lane >> 5) + ((lane & 15) >> 2)) * 512 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+        auto read_tr = [&](const char* base, int ks, int unit) {
+            typedef short s16x4_t __attribute__((ext_vector_type(4)));
+            typedef short s16x8_t __attribute__((ext_vector_type(8)));
+            typedef __attribute__((address_space(3))) s16x4_t* lds4_t;
+            const char* q = base + ks * (16 * 512) + tr_base + ((unit ^ tr_x) << 6);
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)q);
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(q + 8 * 512));
+            const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8_t, v);
+        };
         issue(t_begin, 0);
         issue(t_begin + 1, 1);
         issue(t_begin + 2, 2);
@@ -548,11 +590,15 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
             for (int ks = 0; ks < 2; ++ks) {
                 bf16x8_t fa[TM], fb[TN];
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off32(wm * (TM * 32) + i * 32 + frag_row, ks * 2 + frag_half));
+                for (int i = 0; i < TM; ++i) {
+                    if constexpr (TNF) fa[i] = read_tr(a_base, ks, wm * TM + i);
+                    else fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off32(wm * (TM * 32) + i * 32 + frag_row, ks * 2 + frag_half));
+                }
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off32(wn * (TN * 32) + j * 32 + frag_row, ks * 2 + frag_half));
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (TNF) fb[j] = read_tr(b_base, ks, wn * TN + j);
+                    else fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off32(wn * (TN * 32) + j * 32 + frag_row, ks * 2 + frag_half));
+                }
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -562,7 +608,10 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
             }
         }
-        __syncthreads();          // drains the redundant tail loads before LDS is reused by the epilogue
+        // drain the redundant tail transfers before LDS is reused by the epilogue (explicit: the compiler does not
+        // see transfers issued by lds_dma16)
+        __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0) lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
     }
 
     // ---- epilogue through LDS: per wavefront a [32][STG_LD] fp32 staging block
@@ -673,12 +722,34 @@ ds_status launch_mfma(int M, int N, int K, const void* A, const void* B, void* C
     return DS_OK;
 }
 
-template <int EPI>
+// number of K splits of a weight-gradient GEMM: the fewest that bring the work-group count closest to a whole
+// number of rounds over the compute units (time ~ rounds x split length)
+static int choose_splits(int tiles, int nt, int M, int N, size_t split_ws_floats) {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        n_cu = v;
+    }
+    int best = 1;
+    double best_cost = 1e30;
+    for (int sp = 1; sp <= 16; ++sp) {
+        if (sp > 1 && (sp > nt / 16 || (size_t)sp * M * N > split_ws_floats)) break;
+        const int per = (nt + sp - 1) / sp;
+        if ((nt + per - 1) / per != sp) continue;               // every split must own at least one K tile
+        const double rounds = (double)(((long long)tiles * sp + n_cu - 1) / n_cu);
+        const double cost = rounds * per * (1.0 + 0.01 * sp);    // slight preference for fewer partial sums
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = sp; }
+    }
+    return best;
+}
+
+template <int EPI, bool TNF>
 ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, const GemmEpi& p, float* split_ws,
                     size_t split_ws_floats, hipStream_t st) {
     static bool attr_set = false;
     constexpr int WM = NT_WM, WN = NT_WN;
-    auto kern = gemm_bf16_nt_kernel<EPI, WM, WN>;
+    auto kern = gemm_bf16_nt_kernel<EPI, WM, WN, TNF>;
     constexpr int stg = WM * WN * 32 * ((256 / WN) + 4) * 4;
     const int smem = NT_NS * NT_STAGE > stg ? NT_NS * NT_STAGE : stg;
     if (!attr_set) {
@@ -686,19 +757,9 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
         attr_set = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
-    const int nt = K / NT_DK;
+    const int nt = TNF ? (K + NT_DK - 1) / NT_DK : K / NT_DK;
     int splits = 1;
-    if (EPI == DS_EPI_ACC32 && split_ws) {
-        const int tiles = tiles_m * tiles_n;
-        if (tiles < 384) {
-            splits = (512 + tiles - 1) / tiles;
-            if (splits > 16) splits = 16;
-            if (splits > nt / 16) splits = nt / 16 > 0 ? nt / 16 : 1;
-            while (splits > 1 && (size_t)splits * M * N > split_ws_floats) --splits;
-            const int per = (nt + splits - 1) / splits;       // every split must own at least one K tile
-            splits = (nt + per - 1) / per;
-        }
-    }
+    if (EPI == DS_EPI_ACC32 && split_ws) splits = choose_splits(tiles_m * tiles_n, nt, M, N, split_ws_floats);
     const int total = tiles_m * tiles_n * splits;
     hipLaunchKernelGGL(kern, dim3(total), dim3(WM * WN * 64), smem, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C,
                        tiles_m, tiles_n, splits, split_ws, p);
@@ -723,7 +784,9 @@ ds_status dispatch_epi(int dtype, int ta, int tb, int M, int N, int K, const voi
         const bool aligned = ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && ((uintptr_t)C % 16 == 0);
         if (ok_n && ok_a && ok_b && aligned && M >= 1 && K >= 1) {
             if (!ta && !tb) return launch_mfma<0, 0, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
-            if (!ta && tb) return launch_nt<EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
+            if (!ta && tb) return launch_nt<EPI, false>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
+            if constexpr (EPI == DS_EPI_ACC32)
+                if (ta && !tb) return launch_nt<EPI, true>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
             if (ta && !tb) return launch_mfma<1, 0, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
         }
     }

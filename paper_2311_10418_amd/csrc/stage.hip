@@ -92,7 +92,6 @@ struct ds_stage {
          *dx1 = nullptr, *dx2 = nullptr, *d_o = nullptr, *dqkv = nullptr, *dqc = nullptr, *dkvc = nullptr, *de = nullptr,
          *deB = nullptr;
     float *delta = nullptr, *partial = nullptr, *split_ws = nullptr;
-    void *xt = nullptr, *dyt = nullptr;     // token-major -> feature-major copies for the weight-gradient GEMMs
     void* attn_scratch = nullptr;           // feature-major copies for the attention kernels
     size_t attn_scratch_bytes = 0;
     bool nt_mode = false;
@@ -193,11 +192,6 @@ void carve(ds_stage* s) {
         s->attn_scratch_bytes = attn_scratch_bytes(c.n_heads, hd, (int)Rm, (int)Rm, (int)S);
         s->attn_scratch = ar.take(s->attn_scratch_bytes);
     }
-    if (nt) {
-        const size_t Rp = (Rm + 63) & ~size_t(63);
-        s->xt = ar.take(std::max(d, F) * Rp * es);
-        s->dyt = ar.take(std::max(3 * d, F) * Rp * es);
-    }
     ar.take(4096);
 }
 
@@ -287,16 +281,7 @@ struct Ops {
     }
     // dW[K,N] (+)= X[rows,K]^T dY[rows,N]
     ds_status wgrad(const Stream& sm, int K, int N, const void* X, const void* dY, void* dW) {
-        if (!nt)
-            return gemm_raw(DS_PROF_GEMM_WGRAD, 1, 0, K, N, sm.R, X, dY, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr,
-                            nullptr, accumulate);
-        const int Rp = (sm.R + 63) & ~63;
-        DS_TRY(timed(s, DS_PROF_TRANSPOSE, st, [&] {
-            DS_TRY(launch_transpose_bf16(sm.R, K, Rp, X, s->xt, st));
-            s->launches += 2;
-            return launch_transpose_bf16(sm.R, N, Rp, dY, s->dyt, st);
-        }));
-        return gemm_raw(DS_PROF_GEMM_WGRAD, 0, 1, K, N, Rp, s->xt, s->dyt, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr,
+        return gemm_raw(DS_PROF_GEMM_WGRAD, 1, 0, K, N, sm.R, X, dY, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr,
                         nullptr, accumulate);
     }
     ds_status weight_t(int K, int N, const void* W, void* Wt) {      // [K][N] -> [N][K]

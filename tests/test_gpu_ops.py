@@ -78,9 +78,9 @@ def test_gemm_epilogues(dt, force):
 
 
 @pytest.mark.parametrize("dt,force", [(F32, True), (BF, False)])
-def test_gemm_weight_gradient_accumulates_in_fp32(dt, force):
+@pytest.mark.parametrize("M,N,K", [(256, 512, 3000 + 11), (768, 512, 1000 + 37), (512, 256, 31), (256, 256, 64)])
+def test_gemm_weight_gradient_accumulates_in_fp32(dt, force, M, N, K):
     rng = np.random.default_rng(3)
-    M, N, K = 256, 512, 3000 + 11
     X, dY = _rnd(rng, (K, M), dt), _rnd(rng, (K, N), dt)
     ref = X.astype(np.float64).T @ dY.astype(np.float64)
     dX, ddY = to_dev(X, dt), to_dev(dY, dt)
