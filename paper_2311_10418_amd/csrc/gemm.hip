@@ -575,38 +575,54 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
             const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             return __builtin_bit_cast(bf16x8_t, v);
         };
+        auto load_frags = [&](int stage, int ks, bf16x8_t (&fa)[TM], bf16x8_t (&fb)[TN]) {
+            const char* a_base = smem + stage * NT_STAGE;
+            const char* b_base = a_base + NT_HALF;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                if constexpr (TNF) fa[i] = read_tr(a_base, ks, wm * TM + i);
+                else fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off32(wm * (TM * 32) + i * 32 + frag_row, ks * 2 + frag_half));
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (TNF) fb[j] = read_tr(b_base, ks, wn * TN + j);
+                else fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off32(wn * (TN * 32) + j * 32 + frag_row, ks * 2 + frag_half));
+            }
+        };
+        auto mma = [&](const bf16x8_t (&fa)[TM], const bf16x8_t (&fb)[TN]) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    // operands swapped on purpose: the accumulator tile is C^T (rows = n, columns = m), so a
+                    // lane holds 4 CONSECUTIVE n per register group and the epilogue stages with 16-byte writes
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        };
+        // Software pipeline: the fragments of one 16-deep k step are read from LDS while the MFMAs of the previous
+        // step run, ACROSS the tile boundary too, so that no wavefront waits on LDS latency right after the barrier
+        // (all 8 wavefronts leave it together, so nobody would be left to cover for the others).
+        bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
         issue(t_begin, 0);
         issue(t_begin + 1, 1);
         issue(t_begin + 2, 2);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * LPW));             // tile t_begin: at most the two newest tiles outstanding
+        __builtin_amdgcn_s_barrier();
+        load_frags(0, 0, fa0, fb0);
         for (int tl = t_begin; tl < t_end; ++tl) {
             const int st_ = (tl - t_begin) & (NT_NS - 1);
-            // this wavefront's part of tile tl has landed: at most the two newest tiles (2 * 2 * LPW loads) outstanding
-            __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * LPW));
-            __builtin_amdgcn_s_barrier();                           // ... and everyone's; stage (tl-1)%4 is free again
+            // stage (tl-1)%4 is free: every wavefront finished reading it before the barrier it has just passed
             issue(tl + 3, (st_ + 3) & (NT_NS - 1));
-            const char* a_base = smem + st_ * NT_STAGE;
-            const char* b_base = a_base + NT_HALF;
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                bf16x8_t fa[TM], fb[TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    if constexpr (TNF) fa[i] = read_tr(a_base, ks, wm * TM + i);
-                    else fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off32(wm * (TM * 32) + i * 32 + frag_row, ks * 2 + frag_half));
-                }
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    if constexpr (TNF) fb[j] = read_tr(b_base, ks, wn * TN + j);
-                    else fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off32(wn * (TN * 32) + j * 32 + frag_row, ks * 2 + frag_half));
-                }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        // operands swapped on purpose: the accumulator tile is C^T (rows = n, columns = m), so a
-                        // lane holds 4 CONSECUTIVE n per register group and the epilogue stages with 16-byte writes
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-            }
+            load_frags(st_, 1, fa1, fb1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(fa0, fb0);
+            __builtin_amdgcn_sched_barrier(0);
+            // tile tl+1: this wavefront's part has landed (two newest tiles outstanding), its LDS reads are done ...
+            __builtin_amdgcn_s_waitcnt(0x0070 | (4 * LPW));         // vmcnt(4*LPW) lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();                           // ... and everyone's
+            load_frags((st_ + 1) & (NT_NS - 1), 0, fa0, fb0);       // past the last tile: a stale but valid stage, unused
+            __builtin_amdgcn_sched_barrier(0);
+            mma(fa1, fb1);
+            __builtin_amdgcn_sched_barrier(0);
         }
         // drain the redundant tail transfers before LDS is reused by the epilogue (explicit: the compiler does not
         // see transfers issued by lds_dma16)
