@@ -448,6 +448,17 @@ constexpr int NT_DK = 32, NT_NS = 4, NT_HALF = 256 * NT_DK * 2, NT_STAGE = 2 * N
 #define NT_WN 4
 #endif
 
+// tile number -> tile coordinates: groups of 8 tile rows, column-major inside a group
+__host__ __device__ __forceinline__ void nt_tile_coords(int logical, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+    const int group_sz = 8 * tiles_n;
+    const int group = logical / group_sz;
+    const int first_m = group * 8;
+    const int gs = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
+    const int in_group = logical - group * group_sz;
+    tile_m = first_m + in_group % gs;
+    tile_n = in_group / gs;
+}
+
 // 16 zero bytes: the source of every chunk past the end of a ragged contraction (TN form)
 __device__ uint4 g_zero16;
 
@@ -463,6 +474,7 @@ template <int EPI, int WM, int WN, bool TNF>
 __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
                                                                        const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
                                                                        int tiles_m, int tiles_n, int splits,
+                                                                       int n_main, int tail_splits,
                                                                        float* __restrict__ split_ws, GemmEpi p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int NW = WM * WN;                    // wavefronts
@@ -474,32 +486,41 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
     const int lane = t & 63, wave = t >> 6;
     const int wm = wave / WN, wn = wave % WN;
 
-    // ---- work-group id -> (tile_m, tile_n, split): contiguous runs per XCD, groups of 8 tile rows
-    const int total = tiles_m * tiles_n * splits;
-    int logical;
+    // ---- work-group id -> (tile, split).  Two regimes share the kernel:
+    //  * uniform split-K (weight gradients): every tile is cut into `splits` K ranges, partial sums go to split_ws
+    //    as [split][M][N];
+    //  * tail split-K (everything else): the first n_main tiles, a whole number of rounds over the compute units,
+    //    run unsplit; each of the remaining tiles is cut into tail_splits K ranges so that the last, partly filled
+    //    round costs 1/tail_splits of a round; their partial sums go to split_ws as [tail tile][split][256][256].
+    // Tiles are numbered so that each XCD works on contiguous runs, in groups of 8 tile rows (L2 reuse).
+    const int n_tiles = tiles_m * tiles_n;
+    int logical, split, nsplit;
+    bool tail = false;
     {
         const int pid = blockIdx.x;
-        const int xcd = pid & 7, local = pid >> 3;
-        const int per = total >> 3, rem = total & 7;
-        const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
-        logical = start + local;
+        const int total = splits > 1 ? n_tiles * splits : n_main;
+        if (pid < total) {
+            const int xcd = pid & 7, local = pid >> 3;
+            const int per = total >> 3, rem = total & 7;
+            const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+            logical = start + local;
+            split = logical / n_tiles;
+            logical -= split * n_tiles;
+            nsplit = splits;
+        } else {
+            const int r = pid - total;
+            logical = n_main + r / tail_splits;
+            split = r % tail_splits;
+            nsplit = tail_splits;
+            tail = true;
+        }
     }
-    const int split = logical / (tiles_m * tiles_n);
-    logical -= split * (tiles_m * tiles_n);
     int tile_m, tile_n;
-    {
-        const int group_sz = 8 * tiles_n;
-        const int group = logical / group_sz;
-        const int first_m = group * 8;
-        const int gs = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
-        const int in_group = logical - group * group_sz;
-        tile_m = first_m + in_group % gs;
-        tile_n = in_group / gs;
-    }
+    nt_tile_coords(logical, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int nt_total = TNF ? (K + NT_DK - 1) / NT_DK : K / NT_DK;
-    const int per_split = (nt_total + splits - 1) / splits;
+    const int per_split = (nt_total + nsplit - 1) / nsplit;
     const int t_begin = split * per_split;
     const int t_end = (t_begin + per_split) < nt_total ? (t_begin + per_split) : nt_total;
 
@@ -655,13 +676,39 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                 const float4 x0 = *reinterpret_cast<const float4*>(stage + row * STG_LD + rd_col);
                 const float4 x1 = *reinterpret_cast<const float4*>(stage + row * STG_LD + rd_col + 4);
                 v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
-                if (splits > 1) {
+                if (tail) {
+                    Vec8<float>::store(split_ws + ((size_t)((logical - n_main) * tail_splits + split) * BM + (m - m0)) * BN + (n - n0), v);
+                } else if (splits > 1) {
                     Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
                 } else {
                     epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
                 }
             }
         }
+    }
+}
+
+// sum the tail tiles' split-K partials ([tile][split][256][256]) and apply the epilogue; one thread per 8 columns
+template <int EPI>
+__global__ __launch_bounds__(256) void tail_finish_kernel(int M, int N, int tiles_m, int tiles_n, int n_main, int tail_splits,
+                                                          const float* __restrict__ ws, bf16_t* __restrict__ C, GemmEpi p) {
+    const int tile = blockIdx.y;
+    int tile_m, tile_n;
+    nt_tile_coords(n_main + tile, tiles_m, tiles_n, tile_m, tile_n);
+    const float* base = ws + (size_t)tile * tail_splits * (BM * BN);
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < BM * (BN / 8); i += gridDim.x * blockDim.x) {
+        const int r = i / (BN / 8), c8 = (i % (BN / 8)) * 8;
+        const int m = tile_m * BM + r, n = tile_n * BN + c8;
+        if (m >= M) continue;
+        float v[8];
+        Vec8<float>::load(base + (size_t)r * BN + c8, v);
+        for (int sp = 1; sp < tail_splits; ++sp) {
+            float w[8];
+            Vec8<float>::load(base + ((size_t)sp * BM + r) * BN + c8, w);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] += w[j];
+        }
+        epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
     }
 }
 
@@ -740,13 +787,17 @@ ds_status launch_mfma(int M, int N, int K, const void* A, const void* B, void* C
 
 // number of K splits of a weight-gradient GEMM: the fewest that bring the work-group count closest to a whole
 // number of rounds over the compute units (time ~ rounds x split length)
-static int choose_splits(int tiles, int nt, int M, int N, size_t split_ws_floats) {
+static int cu_count() {
     static int n_cu = 0;
     if (n_cu == 0) {
         int dev = 0, v = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
         n_cu = v;
     }
+    return n_cu;
+}
+static int choose_splits(int tiles, int nt, int M, int N, size_t split_ws_floats) {
+    const int n_cu = cu_count();
     int best = 1;
     double best_cost = 1e30;
     for (int sp = 1; sp <= 16; ++sp) {
@@ -774,17 +825,39 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
     const int nt = TNF ? (K + NT_DK - 1) / NT_DK : K / NT_DK;
+    const int tiles = tiles_m * tiles_n;
     int splits = 1;
-    if (EPI == DS_EPI_ACC32 && split_ws) splits = choose_splits(tiles_m * tiles_n, nt, M, N, split_ws_floats);
-    const int total = tiles_m * tiles_n * splits;
+    if (EPI == DS_EPI_ACC32 && split_ws) splits = choose_splits(tiles, nt, M, N, split_ws_floats);
+    // tail split-K: tiles beyond the last whole round over the compute units share that round
+    int n_main = tiles, tail_splits = 1;
+    if (splits == 1 && split_ws) {
+        const int n_cu = cu_count();
+        const int rem = tiles % n_cu;
+        if (tiles > n_cu && rem > 0) {
+            int ts = n_cu / rem;
+            if (ts > 32) ts = 32;
+            if (ts > nt / 8) ts = nt / 8;
+            while (ts > 1 && (size_t)rem * ts * (BM * BN) > split_ws_floats) --ts;
+            if (ts > 1) {
+                const int per = (nt + ts - 1) / ts;
+                ts = (nt + per - 1) / per;                      // every split owns at least one K tile
+            }
+            if (ts > 1) { n_main = tiles - rem; tail_splits = ts; }
+        }
+    }
+    const int total = splits > 1 ? tiles * splits : n_main + (tiles - n_main) * tail_splits;
     hipLaunchKernelGGL(kern, dim3(total), dim3(WM * WN * 64), smem, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C,
-                       tiles_m, tiles_n, splits, split_ws, p);
+                       tiles_m, tiles_n, splits, n_main, tail_splits, split_ws, p);
     DS_LAUNCH_CHECK();
     if (splits > 1) {
         long long items = (long long)M * (N / 8);
         long long g = (items + 255) / 256;
         if (g > 8192) g = 8192;
         hipLaunchKernelGGL(splitk_finish_kernel<EPI>, dim3((int)g), dim3(256), 0, st, M, N, splits, split_ws, (bf16_t*)C, p);
+        DS_LAUNCH_CHECK();
+    } else if (tail_splits > 1) {
+        hipLaunchKernelGGL(tail_finish_kernel<EPI>, dim3(8, tiles - n_main), dim3(256), 0, st, M, N, tiles_m, tiles_n, n_main,
+                           tail_splits, split_ws, (bf16_t*)C, p);
         DS_LAUNCH_CHECK();
     }
     return DS_OK;

@@ -175,7 +175,7 @@ void carve(ds_stage* s) {
     }
     const size_t partial_floats = std::max<size_t>((size_t)ds_norm_bwd_scratch_floats(1, (int)d), (size_t)2048 * 1024);
     s->partial = f32(partial_floats);
-    s->split_ws_floats = 3 * std::max(d * 3 * d, d * F);
+    s->split_ws_floats = 4 * std::max(d * 3 * d, d * F);
     s->split_ws = f32(s->split_ws_floats);
     s->main.row_valid = (int32_t*)ar.take(R * 4);
     s->main.seq_row = (int32_t*)ar.take(S * 4);
