@@ -82,6 +82,26 @@ typedef struct {
 } ds_layout_view;
 
 /*
+ * ds_cost_table_build — the profiled cost model (section "Overview", paragraph "Cost models"):
+ * execution times profiled at a grid of (micro-batch size, sequence length) points, power-of-two
+ * spaced in the paper, are bridged by linear interpolation.  Fills the table a DS_COST_TABLE cost
+ * model reads: table[(b-1)*tl + (L-1)], b = 1..tb, L = 1..tl.
+ *   b_grid HOST int32[nb], l_grid HOST int32[nl]: strictly increasing, >= 1.
+ *   t      HOST double[nb*nl], row-major [b][L]: measured time of a micro-batch of b_grid[i]
+ *          sequences padded to l_grid[j], any unit; NaN = not profiled.
+ *   Value at (b, L): linear along b at the two bracketing lengths, then linear along L between the
+ *   two results; a length below l_grid[0] costs what l_grid[0] costs; b or L beyond the grid, b
+ *   below b_grid[0], and points whose bracketing grid points (those with non-zero weight) include
+ *   an unprofiled one get inf_cost.  Entries are floor(value * scale + 0.5), at least 1.
+ *   table HOST int64[tb*tl], written by the call; nothing is retained.
+ * Errors: DS_EINVAL (null, empty or unsorted grid, tb/tl < 1, scale <= 0, inf_cost < 1, a
+ * negative time), DS_EOVERFLOW (a scaled time reaches inf_cost).
+ */
+ds_status ds_cost_table_build(const int32_t* b_grid, int32_t nb, const int32_t* l_grid, int32_t nl,
+                              const double* t, double scale, int32_t tb, int32_t tl,
+                              int64_t inf_cost, int64_t* table);
+
+/*
  * dp_plan — the paper's micro-batch construction (section "Micro-batch Construction").
  *   1. order samples ascending by length (encoder-decoder: by input length, then target
  *      length); equal keys keep their original order;

@@ -24,7 +24,7 @@ PROF_KINDS = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "n
 _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOMEM", -4: "DS_EOVERFLOW",
                  -5: "DS_EHIP", -6: "DS_ELAYOUT"}
 
-EXPORTS = ["dp_plan", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
+EXPORTS = ["dp_plan", "ds_cost_table_build", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "stage_fwd_bwd",
            "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_attention_fwd",
            "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
@@ -93,6 +93,12 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libdynastage.so is missing: run `python -m paper_2311_10418_amd.build` "
                                "(there is no fallback implementation)")
+        try:
+            # PyTorch ships its own HIP runtime; loading it first makes this library bind to that copy, so the
+            # process holds ONE runtime (with two, allocations from the second one fail)
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         _lib = C.CDLL(LIB_PATH)
         _lib.ds_version.restype = C.c_char_p
         _lib.ds_stage_workspace_bytes.restype = C.c_int64
@@ -152,6 +158,20 @@ def make_cost_model(kind=DS_COST_POLY_GPT, fixed=0, lin=2048, table=None):
         cm.table = tab.ctypes.data
         cm.tb, cm.tl = tab.shape
     return cm
+
+
+def ds_cost_table_build(b_grid, l_grid, t, tb, tl, scale=1.0, inf_cost=1 << 50):
+    """int64 table [tb, tl] for make_cost_model(kind=DS_COST_TABLE, table=...) from profiled times t[nb, nl]."""
+    bg, lg = _np_i32(b_grid), _np_i32(l_grid)
+    tt = np.ascontiguousarray(t, dtype=np.float64)
+    if tt.shape != (bg.shape[0], lg.shape[0]):
+        raise ValueError("t must have shape [len(b_grid), len(l_grid)]")
+    out = np.empty((tb, tl), dtype=np.int64)
+    rc = lib().ds_cost_table_build(_hp(bg), C.c_int32(bg.shape[0]), _hp(lg), C.c_int32(lg.shape[0]),
+                                   tt.ctypes.data_as(C.c_void_p), C.c_double(scale), C.c_int32(tb), C.c_int32(tl),
+                                   C.c_int64(inf_cost), out.ctypes.data_as(C.c_void_p))
+    _check(rc, "ds_cost_table_build")
+    return out
 
 
 class Layout:
@@ -268,6 +288,17 @@ def stage_fwd_bwd(stage, layout, weights, act_in, grad_out, act_out, grad_in, gr
         g = _layer_array(ds_t5_enc_layer, T5_ENC_KEYS, grads)
         wd = _layer_array(ds_t5_dec_layer, T5_DEC_KEYS, weights_dec)
         gd = _layer_array(ds_t5_dec_layer, T5_DEC_KEYS, grads_dec)
+    # the kernels address layout.total_rows rows of every activation tensor: refuse shorter ones here, where
+    # the shapes are still known (the C ABI sees plain pointers)
+    for name, t, rows in (("act_in", act_in, layout.total_rows), ("grad_out", grad_out, None), ("act_out", act_out, None),
+                          ("grad_in", grad_in, layout.total_rows), ("act_in_tgt", act_in_tgt, layout.total_rows_tgt),
+                          ("grad_in_tgt", grad_in_tgt, layout.total_rows_tgt)):
+        if t is None:
+            continue
+        if rows is None:
+            rows = layout.total_rows_tgt if stage.cfg.model != DS_MODEL_GPT else layout.total_rows
+        if t.dim() != 2 or t.shape[0] < rows or t.shape[1] != stage.cfg.d_model or not t.is_contiguous():
+            raise ValueError("%s must be a contiguous [>= %d, %d] tensor, got %s" % (name, rows, stage.cfg.d_model, tuple(t.shape)))
     io = ds_stage_io()
     io.act_in = act_in.data_ptr()
     io.act_in_tgt = act_in_tgt.data_ptr() if act_in_tgt is not None else None

@@ -12,6 +12,7 @@
 
 #include <algorithm>
 #include <limits>
+#include <cmath>
 #include <memory>
 #include <new>
 #include <numeric>
@@ -462,3 +463,62 @@ extern "C" ds_status ds_layout_get(const ds_layout* lo, ds_layout_view* v) {
 }
 
 extern "C" void ds_layout_free(ds_layout* lo) { delete lo; }
+
+// ------------------------------------------------------------------------------------ profiled cost table
+namespace {
+// index i with grid[i] <= x <= grid[i+1] and the weight of grid[i+1]; weight 0 when x is a grid point
+bool bracket(const int32_t* grid, int n, int x, int& i, double& w) {
+    for (int k = 0; k < n; ++k)
+        if (grid[k] == x) { i = k; w = 0.0; return true; }
+    for (int k = 0; k + 1 < n; ++k)
+        if (grid[k] < x && x < grid[k + 1]) {
+            i = k;
+            w = ((double)x - (double)grid[k]) / ((double)grid[k + 1] - (double)grid[k]);
+            return true;
+        }
+    return false;
+}
+}  // namespace
+
+extern "C" ds_status ds_cost_table_build(const int32_t* b_grid, int32_t nb, const int32_t* l_grid, int32_t nl,
+                                         const double* t, double scale, int32_t tb, int32_t tl, int64_t inf_cost,
+                                         int64_t* table) {
+    if (!b_grid || !l_grid || !t || !table || nb < 1 || nl < 1 || tb < 1 || tl < 1) return DS_EINVAL;
+    if (!(scale > 0.0) || inf_cost < 1) return DS_EINVAL;
+    for (int i = 0; i < nb; ++i)
+        if (b_grid[i] < 1 || (i > 0 && b_grid[i] <= b_grid[i - 1])) return DS_EINVAL;
+    for (int j = 0; j < nl; ++j)
+        if (l_grid[j] < 1 || (j > 0 && l_grid[j] <= l_grid[j - 1])) return DS_EINVAL;
+    for (int k = 0; k < nb * nl; ++k)
+        if (t[k] < 0.0) return DS_EINVAL;                       // NaN compares false: allowed
+    for (int b = 1; b <= tb; ++b) {
+        int i = 0;
+        double u = 0.0;
+        const bool b_in = b >= b_grid[0] && b <= b_grid[nb - 1] && bracket(b_grid, nb, b, i, u);
+        for (int L = 1; L <= tl; ++L) {
+            int64_t& out = table[(size_t)(b - 1) * tl + (L - 1)];
+            if (!b_in || L > l_grid[nl - 1]) { out = inf_cost; continue; }
+            const int Lc = L < l_grid[0] ? l_grid[0] : L;
+            int j = 0;
+            double v = 0.0;
+            if (!bracket(l_grid, nl, Lc, j, v)) { out = inf_cost; continue; }
+            auto along_b = [&](int jj) {
+                const double lo = t[(size_t)i * nl + jj];
+                if (u == 0.0) return lo;
+                const double hi = t[(size_t)(i + 1) * nl + jj];
+                return lo + u * (hi - lo);
+            };
+            const double near = along_b(j);
+            double val = near;
+            if (v != 0.0) {
+                const double far = along_b(j + 1);
+                val = near + v * (far - near);
+            }
+            if (val != val) { out = inf_cost; continue; }       // an unprofiled grid point was needed
+            const double scaled = std::floor(val * scale + 0.5);
+            if (scaled >= (double)inf_cost) return DS_EOVERFLOW;
+            out = scaled < 1.0 ? 1 : (int64_t)scaled;
+        }
+    }
+    return DS_OK;
+}

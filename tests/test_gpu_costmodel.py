@@ -1,0 +1,41 @@
+"""Profiled cost model on the GPU: profile a small grid, plan with it, check prediction against measurement."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def test_profiled_cost_model_predicts_and_improves_sequential_execution():
+    import torch
+    from paper_2311_10418_amd import binding as ds
+    from paper_2311_10418_amd import costmodel as cmod
+    from oracle import costmodel as ocm
+
+    cfg = dict(kind="gpt", dtype="bf16", n_layers=2, d_model=256, n_heads=4, d_ff=1024)
+    rng = np.random.default_rng(3)
+    lens = np.clip(np.rint(rng.lognormal(3.3, 0.7, 40)), 8, 128).astype(np.int32)
+    cap, c = 512, 4
+    b_grid = cmod.power_of_two_grid(1, min(len(lens), cap // int(lens.min())))
+    l_grid = cmod.power_of_two_grid(8, int(lens.max()))
+    # rows of ANY plan over these sequences are at most n * longest: the runner can hold every layout used below
+    runner = cmod.StageRunner(cfg, max_rows=max(len(lens) * int(lens.max()), 4 * cap), max_seqs=max(len(lens), b_grid[-1]), seed=1)
+    t_ms = cmod.profile_grid(runner, b_grid, l_grid, max_rows=4 * cap, reps=3)
+    assert np.nanmin(t_ms) > 0
+    tb, tl = min(len(lens), cap // int(lens.min())), int(lens.max())
+    table = cmod.build_table(b_grid, l_grid, t_ms, tb, tl)
+    # the library's table is the oracle's, bit for bit, on the measured grid
+    assert np.array_equal(table, ocm.build_table(b_grid, l_grid, t_ms, tb, tl, cmod.NS_PER_MS, cmod.INF_COST).reshape(tb, tl))
+    poly = ds.dp_plan(lens, ds.make_cost_model(), cap, c)
+    prof = ds.dp_plan(lens, ds.make_cost_model(kind=ds.DS_COST_TABLE, table=table), cap, c)
+    assert np.all(prof.mb_count * prof.mb_lpad <= cap)
+    m_poly = cmod.measure_plan(runner, poly, lens, table)
+    m_prof = cmod.measure_plan(runner, prof, lens, table)
+    runner.close()
+    torch.cuda.synchronize()
+    assert m_prof["unpredicted_micro_batches"] == 0
+    # a launch-bound stage: every micro-batch costs about the same, so the profiled model merges
+    assert prof.n_mb < poly.n_mb
+    assert m_prof["measured_sequential_ms"] <= 1.05 * m_poly["measured_sequential_ms"]
+    # prediction quality (the paper reports a few percent; a loose bar that a wrong table cannot meet)
+    assert m_prof["sequential_prediction_rel_error"] < 0.5
+    assert m_poly["sequential_prediction_rel_error"] < 0.5
