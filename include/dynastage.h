@@ -71,6 +71,7 @@ typedef struct {
     const int32_t* mb_count;                  /* [n_mb] sequences in micro-batch m */
     const int32_t* mb_lpad;                   /* [n_mb] padded length (packed layouts: the row length) */
     const int32_t* mb_ltgt;                   /* [n_mb] padded target length, or NULL */
+    const int64_t* mb_cost;                   /* [n_mb] t(M_m) under the cost model the layout was built with, or NULL */
     const int32_t* mb_row;                    /* [n_mb] first stream row */
     const int32_t* mb_nrows;                  /* [n_mb] stream rows the micro-batch occupies */
     const int32_t* mb_row_tgt;                /* [n_mb] or NULL */
@@ -122,6 +123,38 @@ ds_status ds_cost_table_build(const int32_t* b_grid, int32_t nb, const int32_t* 
 ds_status dp_plan(const int32_t* len, const int32_t* len_tgt, int32_t n,
                   const ds_cost_model* cm, int64_t mem_cap_tokens, int32_t num_stages,
                   ds_layout** out);
+
+/*
+ * dp_plan_replicas — micro-batch construction under hybrid data + pipeline parallelism (section
+ * "Micro-batch Construction", paragraph "Balance data parallel model replicas"): the same
+ * dynamic programme with the sum term weighted 1/n_replicas, kept exact by scaling, i.e. minimising
+ *       n_replicas * (num_stages-1) * max_m t(M_m) + sum_m t(M_m)
+ * (the layout's `objective` is this scaled value), then ds_assign_replicas on the micro-batches'
+ * times.  replica_of_mb: HOST int32, capacity n, the first n_mb entries are written;
+ * replica_time: HOST int64[n_replicas].  Other arguments and errors as dp_plan; DS_EINVAL also for
+ * n_replicas < 1, DS_EOVERFLOW when n_replicas * (num_stages-1) overflows.
+ */
+ds_status dp_plan_replicas(const int32_t* len, const int32_t* len_tgt, int32_t n,
+                           const ds_cost_model* cm, int64_t mem_cap_tokens, int32_t num_stages,
+                           int32_t n_replicas, ds_layout** out, int32_t* replica_of_mb,
+                           int64_t* replica_time);
+
+/*
+ * ds_assign_replicas — Karmarkar-Karp (largest differencing) split of n_items times into
+ * n_replicas sets with a small largest sum (same paragraph; the paper names the method only, the
+ * rules below make it reproducible).  Every item starts as a partial partition with one non-empty
+ * set; the two partial partitions of largest spread (largest set sum - smallest set sum) are merged
+ * by joining the first's sets in descending order of sum with the second's in ascending order;
+ * repeat until one is left.  Sets inside a partial partition are ordered by (sum descending,
+ * smallest member index ascending, empty sets last among equal sums), "ascending" is the exact reverse;
+ * partial partitions of equal spread are taken in order of creation (the initial ones by
+ * descending time, then ascending index).  Replica r gets the r-th set of the final order, so
+ * replica_time is non-increasing.
+ * t: HOST int64[n_items], >= 0; replica_of: HOST int32[n_items]; replica_time: HOST int64[n_replicas].
+ * Errors: DS_EINVAL (null, n_items < 0, n_replicas < 1, a negative time), DS_EOVERFLOW (sum of t).
+ */
+ds_status ds_assign_replicas(const int64_t* t, int32_t n_items, int32_t n_replicas,
+                             int32_t* replica_of, int64_t* replica_time);
 
 /*
  * ds_layout_from_cuts — layout for a given order and given cut points (the baselines the paper

@@ -24,7 +24,7 @@ PROF_KINDS = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "n
 _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOMEM", -4: "DS_EOVERFLOW",
                  -5: "DS_EHIP", -6: "DS_ELAYOUT"}
 
-EXPORTS = ["dp_plan", "ds_cost_table_build", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
+EXPORTS = ["dp_plan", "dp_plan_replicas", "ds_assign_replicas", "ds_cost_table_build", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "stage_fwd_bwd",
            "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_attention_fwd",
            "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
@@ -51,7 +51,7 @@ class ds_layout_view(C.Structure):
                 ("total_tokens", C.c_int64), ("total_tokens_tgt", C.c_int64),
                 ("objective", C.c_int64), ("t_max", C.c_int64),
                 ("perm", _I32P), ("mb_start", _I32P), ("mb_count", _I32P), ("mb_lpad", _I32P), ("mb_ltgt", _I32P),
-                ("mb_row", _I32P), ("mb_nrows", _I32P), ("mb_row_tgt", _I32P), ("mb_nrows_tgt", _I32P),
+                ("mb_cost", C.POINTER(C.c_int64)), ("mb_row", _I32P), ("mb_nrows", _I32P), ("mb_row_tgt", _I32P), ("mb_nrows_tgt", _I32P),
                 ("seq_row", _I32P), ("seq_len", _I32P), ("seq_row_tgt", _I32P), ("seq_len_tgt", _I32P)]
 
 
@@ -191,7 +191,7 @@ class Layout:
 
         for name in ("perm", "seq_row", "seq_len", "seq_row_tgt", "seq_len_tgt"):
             setattr(self, name, arr(getattr(v, name), v.n_seq))
-        for name in ("mb_start", "mb_count", "mb_lpad", "mb_ltgt", "mb_row", "mb_nrows", "mb_row_tgt", "mb_nrows_tgt"):
+        for name in ("mb_start", "mb_count", "mb_lpad", "mb_ltgt", "mb_cost", "mb_row", "mb_nrows", "mb_row_tgt", "mb_nrows_tgt"):
             setattr(self, name, arr(getattr(v, name), v.n_mb))
 
     @property
@@ -212,6 +212,32 @@ def dp_plan(lengths, cost_model, mem_cap_tokens, num_stages, lengths_tgt=None):
                        C.c_int64(mem_cap_tokens), C.c_int32(num_stages), C.byref(out))
     _check(rc, "dp_plan")
     return Layout(out)
+
+
+def dp_plan_replicas(lengths, cost_model, mem_cap_tokens, num_stages, n_replicas, lengths_tgt=None):
+    """-> (Layout, replica_of_mb int32[n_mb], replica_time int64[n_replicas])."""
+    ln, lt = _np_i32(lengths), _np_i32(lengths_tgt)
+    out = C.c_void_p()
+    n = 0 if ln is None else int(ln.shape[0])
+    rep = np.zeros(max(n, 1), dtype=np.int32)
+    sums = np.zeros(max(int(n_replicas), 1), dtype=np.int64)
+    rc = lib().dp_plan_replicas(_hp(ln), _hp(lt), C.c_int32(n), C.byref(cost_model) if cost_model is not None else None,
+                                C.c_int64(mem_cap_tokens), C.c_int32(num_stages), C.c_int32(n_replicas), C.byref(out),
+                                rep.ctypes.data_as(C.c_void_p), sums.ctypes.data_as(C.c_void_p))
+    _check(rc, "dp_plan_replicas")
+    lay = Layout(out)
+    return lay, rep[:lay.n_mb].copy(), sums
+
+
+def ds_assign_replicas(times, n_replicas):
+    """Karmarkar-Karp split of `times` into n_replicas sets -> (replica_of int32[n], replica_time int64[n_replicas])."""
+    t = np.ascontiguousarray(times, dtype=np.int64)
+    rep = np.zeros(max(t.shape[0], 1), dtype=np.int32)
+    sums = np.zeros(max(int(n_replicas), 1), dtype=np.int64)
+    rc = lib().ds_assign_replicas(t.ctypes.data_as(C.c_void_p), C.c_int32(t.shape[0]), C.c_int32(n_replicas),
+                                  rep.ctypes.data_as(C.c_void_p), sums.ctypes.data_as(C.c_void_p))
+    _check(rc, "ds_assign_replicas")
+    return rep[:t.shape[0]].copy(), sums
 
 
 def ds_layout_from_cuts(lengths, cuts, perm=None, lengths_tgt=None, pad_to=0, pad_to_tgt=0, cost_model=None, num_stages=1):

@@ -12,6 +12,7 @@
 
 #include <algorithm>
 #include <limits>
+#include <climits>
 #include <cmath>
 #include <memory>
 #include <new>
@@ -129,6 +130,7 @@ ds_status place_padded(ds_layout& lo, const int32_t* len, const int32_t* len_tgt
 // Objective of an already-built padded layout under a cost model (Eq1).
 ds_status score(ds_layout& lo, const ds_cost_model* cm, int32_t num_stages) {
     lo.objective = lo.t_max = 0;
+    lo.mb_cost.clear();
     if (!cm) return DS_OK;
     CostEval cost{cm};
     int64_t sum = 0, mx = 0;
@@ -136,6 +138,7 @@ ds_status score(ds_layout& lo, const ds_cost_model* cm, int32_t num_stages) {
         int64_t t;
         ds_status st = cost(lo.mb_count[m], lo.mb_lpad[m], lo.has_tgt ? lo.mb_ltgt[m] : 0, &t);
         if (st != DS_OK) return st;
+        lo.mb_cost.push_back(t);
         if (__builtin_add_overflow(sum, t, &sum)) return DS_EOVERFLOW;
         mx = std::max(mx, t);
     }
@@ -156,13 +159,15 @@ struct Slice {
 
 uint64_t ds_next_layout_uid() { return g_uid.fetch_add(1); }
 
-extern "C" ds_status dp_plan(const int32_t* len, const int32_t* len_tgt, int32_t n,
-                             const ds_cost_model* cm, int64_t cap, int32_t c, ds_layout** out) {
+// The dynamic programme of Eq2 over every candidate t_max, minimising  w * max_m t + sum_m t  (Eq1 with
+// w = num_stages - 1; the data-parallel variant passes w = n_replicas * (num_stages - 1)).
+static ds_status plan_impl(const int32_t* len, const int32_t* len_tgt, int32_t n, const ds_cost_model* cm, int64_t cap,
+                           int64_t w, ds_layout** out) {
     if (!out) return DS_EINVAL;
     *out = nullptr;
     ds_status st = check_lengths(len, len_tgt, n);
     if (st != DS_OK) return st;
-    if (c < 1 || cap <= 0) return DS_EINVAL;
+    if (w < 0 || cap <= 0) return DS_EINVAL;
     st = check_cost_model(cm, len_tgt != nullptr);
     if (st != DS_OK) return st;
 
@@ -242,7 +247,7 @@ extern "C" ds_status dp_plan(const int32_t* len, const int32_t* len_tgt, int32_t
             // cut-off: no t_max >= T can strictly improve on the incumbent
             if (found) {
                 int64_t lb;
-                if (__builtin_mul_overflow((int64_t)(c - 1), T, &lb) || __builtin_add_overflow(lb, f_inf, &lb))
+                if (__builtin_mul_overflow(w, T, &lb) || __builtin_add_overflow(lb, f_inf, &lb))
                     return DS_EOVERFLOW;
                 if (lb >= bestJ) break;
             }
@@ -263,7 +268,7 @@ extern "C" ds_status dp_plan(const int32_t* len, const int32_t* len_tgt, int32_t
             }
             if (f[n] == kInf) continue;
             int64_t J;
-            if (__builtin_mul_overflow((int64_t)(c - 1), T, &J) || __builtin_add_overflow(J, f[n], &J))
+            if (__builtin_mul_overflow(w, T, &J) || __builtin_add_overflow(J, f[n], &J))
                 return DS_EOVERFLOW;
             if (!found || J < bestJ) {
                 found = true;
@@ -298,6 +303,12 @@ extern "C" ds_status dp_plan(const int32_t* len, const int32_t* len_tgt, int32_t
         }
         st = place_padded(*lo, len, len_tgt);
         if (st != DS_OK) return st;
+        for (int32_t m = 0; m < lo->n_mb; ++m) {
+            int64_t t;
+            st = cost(lo->mb_count[m], lo->mb_lpad[m], lo->has_tgt ? lo->mb_ltgt[m] : 0, &t);
+            if (st != DS_OK) return st;
+            lo->mb_cost.push_back(t);
+        }
         lo->objective = bestJ;
         lo->t_max = bestT;
         *out = lo.release();
@@ -307,6 +318,115 @@ extern "C" ds_status dp_plan(const int32_t* len, const int32_t* len_tgt, int32_t
     } catch (...) {
         return DS_EINVAL;
     }
+}
+
+extern "C" ds_status dp_plan(const int32_t* len, const int32_t* len_tgt, int32_t n,
+                             const ds_cost_model* cm, int64_t cap, int32_t c, ds_layout** out) {
+    if (out) *out = nullptr;
+    if (c < 1) return DS_EINVAL;
+    return plan_impl(len, len_tgt, n, cm, cap, (int64_t)c - 1, out);
+}
+
+// ------------------------------------------------------------------------------------ replica balancing
+namespace {
+struct KkSet {
+    int64_t sum;
+    int32_t min_idx;                    // smallest member index; INT32_MAX for an empty set
+    std::vector<int32_t> items;
+};
+struct KkPart {
+    std::vector<KkSet> sets;            // canonical order: sum descending, then smallest member index ascending
+    int64_t spread;
+    int64_t seq;                        // creation number
+};
+void kk_canon(KkPart& p) {
+    std::sort(p.sets.begin(), p.sets.end(), [](const KkSet& a, const KkSet& b) {
+        if (a.sum != b.sum) return a.sum > b.sum;
+        return a.min_idx < b.min_idx;
+    });
+    p.spread = p.sets.front().sum - p.sets.back().sum;
+}
+}  // namespace
+
+extern "C" ds_status ds_assign_replicas(const int64_t* t, int32_t n_items, int32_t k, int32_t* replica_of,
+                                        int64_t* replica_time) {
+    if (n_items < 0 || k < 1 || !replica_time || (n_items > 0 && (!t || !replica_of))) return DS_EINVAL;
+    int64_t total = 0;
+    for (int32_t i = 0; i < n_items; ++i) {
+        if (t[i] < 0) return DS_EINVAL;
+        if (__builtin_add_overflow(total, t[i], &total)) return DS_EOVERFLOW;
+    }
+    for (int32_t r = 0; r < k; ++r) replica_time[r] = 0;
+    if (n_items == 0) return DS_OK;
+    try {
+        std::vector<int32_t> order(n_items);
+        std::iota(order.begin(), order.end(), 0);
+        std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return t[a] > t[b]; });
+        // largest spread first, then earliest created
+        auto later = [](const KkPart& a, const KkPart& b) {
+            if (a.spread != b.spread) return a.spread < b.spread;
+            return a.seq > b.seq;
+        };
+        std::vector<KkPart> heap;
+        heap.reserve(n_items);
+        int64_t seq = 0;
+        for (int32_t i : order) {
+            KkPart p;
+            p.sets.resize(k);
+            for (KkSet& s : p.sets) { s.sum = 0; s.min_idx = INT32_MAX; }
+            p.sets[0].sum = t[i];
+            p.sets[0].min_idx = i;
+            p.sets[0].items.push_back(i);
+            p.seq = seq++;
+            kk_canon(p);
+            heap.push_back(std::move(p));
+            std::push_heap(heap.begin(), heap.end(), later);
+        }
+        while (heap.size() > 1) {
+            std::pop_heap(heap.begin(), heap.end(), later);
+            KkPart a = std::move(heap.back());
+            heap.pop_back();
+            std::pop_heap(heap.begin(), heap.end(), later);
+            KkPart b = std::move(heap.back());
+            heap.pop_back();
+            for (int32_t p = 0; p < k; ++p) {            // a descending with b ascending
+                KkSet& dst = a.sets[p];
+                KkSet& src = b.sets[k - 1 - p];
+                dst.sum += src.sum;
+                dst.min_idx = std::min(dst.min_idx, src.min_idx);
+                dst.items.insert(dst.items.end(), src.items.begin(), src.items.end());
+            }
+            a.seq = seq++;
+            kk_canon(a);
+            heap.push_back(std::move(a));
+            std::push_heap(heap.begin(), heap.end(), later);
+        }
+        const KkPart& fin = heap.front();
+        for (int32_t r = 0; r < k; ++r) {
+            replica_time[r] = fin.sets[r].sum;
+            for (int32_t i : fin.sets[r].items) replica_of[i] = r;
+        }
+        return DS_OK;
+    } catch (const std::bad_alloc&) {
+        return DS_ENOMEM;
+    }
+}
+
+extern "C" ds_status dp_plan_replicas(const int32_t* len, const int32_t* len_tgt, int32_t n, const ds_cost_model* cm,
+                                      int64_t cap, int32_t c, int32_t n_replicas, ds_layout** out, int32_t* replica_of_mb,
+                                      int64_t* replica_time) {
+    if (out) *out = nullptr;
+    if (c < 1 || n_replicas < 1 || !replica_of_mb || !replica_time) return DS_EINVAL;
+    int64_t w;
+    if (__builtin_mul_overflow((int64_t)c - 1, (int64_t)n_replicas, &w)) return DS_EOVERFLOW;
+    ds_status st = plan_impl(len, len_tgt, n, cm, cap, w, out);
+    if (st != DS_OK) return st;
+    st = ds_assign_replicas((*out)->mb_cost.data(), (*out)->n_mb, n_replicas, replica_of_mb, replica_time);
+    if (st != DS_OK) {
+        delete *out;
+        *out = nullptr;
+    }
+    return st;
 }
 
 extern "C" ds_status ds_layout_from_cuts(const int32_t* len, const int32_t* len_tgt, int32_t n,
@@ -451,6 +571,7 @@ extern "C" ds_status ds_layout_get(const ds_layout* lo, ds_layout_view* v) {
     v->mb_count = p(lo->mb_count);
     v->mb_lpad = p(lo->mb_lpad);
     v->mb_ltgt = p(lo->mb_ltgt);
+    v->mb_cost = lo->mb_cost.empty() ? nullptr : lo->mb_cost.data();
     v->mb_row = p(lo->mb_row);
     v->mb_nrows = p(lo->mb_nrows);
     v->mb_row_tgt = p(lo->mb_row_tgt);
