@@ -23,8 +23,44 @@ namespace {
 
 // ---------------------------------------------------------------------------- epilogues
 // Applied to 8 consecutive columns n..n+7 of row m; acc holds the fp32 accumulators.
+// What an epilogue reads besides the accumulators, fetched ahead of time (8 elements of R, of R2, the row flag),
+// so that a caller can issue these loads for several rows at once instead of one dependent round trip per row.
+// Kept in storage precision (16 bytes per operand for bf16) so that a whole tile's worth fits in registers.
+template <class T> struct EpiPre {
+    T r[8], r2[8];
+    int valid;
+};
+template <class T>
+__device__ __forceinline__ void load8_raw(const T* src, T (&dst)[8]) {
+    if (sizeof(T) == 2) {
+        const uint4 v = *reinterpret_cast<const uint4*>(src);
+        __builtin_memcpy(dst, &v, 16);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dst[j] = src[j];
+    }
+}
 template <class T, int EPI>
-__device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], T* __restrict__ C, const GemmEpi& p) {
+__device__ __forceinline__ void epilogue_prefetch(int m, int n, int N, const GemmEpi& p, EpiPre<T>& q) {
+    const size_t off = (size_t)m * N + n;
+    q.valid = 1;
+    if (EPI == DS_EPI_RESID) {
+        if (p.row_valid) q.valid = p.row_valid[m] >= 0;
+        load8_raw(reinterpret_cast<const T*>(p.R) + off, q.r);
+    } else if (EPI == DS_EPI_DGELU || EPI == DS_EPI_GATE) {
+        load8_raw(reinterpret_cast<const T*>(p.R) + off, q.r);
+    } else if (EPI == DS_EPI_DGATE) {
+        load8_raw(reinterpret_cast<const T*>(p.R) + off, q.r);
+        load8_raw(reinterpret_cast<const T*>(p.R2) + off, q.r2);
+    }
+}
+template <int EPI> constexpr bool epilogue_reads() {
+    return EPI == DS_EPI_RESID || EPI == DS_EPI_DGELU || EPI == DS_EPI_GATE || EPI == DS_EPI_DGATE;
+}
+
+template <class T, int EPI>
+__device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], T* __restrict__ C, const GemmEpi& p,
+                                          const EpiPre<T>* pre = nullptr) {
     const size_t off = (size_t)m * N + n;
     if (EPI == DS_EPI_ACC32) {
         float* c = reinterpret_cast<float*>(C) + off;
@@ -53,7 +89,10 @@ __device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], 
         for (int j = 0; j < 8; ++j) { z[j] = to_f32(from_f32<T>(acc[j])); a[j] = gelu_f(z[j]); }
         Vec8<T>::store(reinterpret_cast<T*>(p.C2) + off, a);
     } else if (EPI == DS_EPI_RESID) {
-        if (p.row_valid && p.row_valid[m] < 0) {
+        if (pre) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = pre->valid ? acc[j] + to_f32(pre->r[j]) : 0.f;
+        } else if (p.row_valid && p.row_valid[m] < 0) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] = 0.f;
         } else {
@@ -65,7 +104,12 @@ __device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], 
         Vec8<T>::store(C + off, acc);
     } else if (EPI == DS_EPI_DGELU) {
         float z[8];
-        Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, z);
+        if (pre) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) z[j] = to_f32(pre->r[j]);
+        } else {
+            Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, z);
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] *= gelu_grad_f(z[j]);
         Vec8<T>::store(C + off, acc);
@@ -73,15 +117,25 @@ __device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], 
         // acc = u Wu (stored); C2 = GELU(R) * acc with R = u Wg
         float zg[8], a[8];
         Vec8<T>::store(C + off, acc);
-        Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, zg);
+        if (pre) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) zg[j] = to_f32(pre->r[j]);
+        } else {
+            Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, zg);
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) a[j] = gelu_f(zg[j]) * to_f32(from_f32<T>(acc[j]));
         Vec8<T>::store(reinterpret_cast<T*>(p.C2) + off, a);
     } else if (EPI == DS_EPI_DGATE) {
         // acc = da; R = zg, R2 = zu; C = dzg = da * zu * GELU'(zg); C2 = dzu = da * GELU(zg)
         float zg[8], zu[8], o1[8], o2[8];
-        Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, zg);
-        Vec8<T>::load(reinterpret_cast<const T*>(p.R2) + off, zu);
+        if (pre) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { zg[j] = to_f32(pre->r[j]); zu[j] = to_f32(pre->r2[j]); }
+        } else {
+            Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, zg);
+            Vec8<T>::load(reinterpret_cast<const T*>(p.R2) + off, zu);
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             o1[j] = acc[j] * zu[j] * gelu_grad_f(zg[j]);
@@ -656,8 +710,26 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
     const int col_l = lane & 31, half = lane >> 5;
     constexpr int LPR = TN * 4;                    // lanes per staged row (8 columns each)
     const int rd_row = lane / LPR, rd_col = (lane % LPR) * 8;
+    constexpr int NPSS = 32 / (64 / LPR);          // staged rows each lane finishes per pass
+    const bool direct = !tail && splits == 1;      // this work-group applies the epilogue itself
+    // what the epilogue reads from memory, for every row this lane will finish: all in flight before the first pass
+    // (one pass ahead only for the two-operand gated form, which would not fit in registers otherwise)
+    constexpr bool PRE_ALL = EPI != DS_EPI_DGATE;
+    EpiPre<bf16_t> pre[TM][NPSS];
+    auto prefetch_pass = [&](int i) {
+#pragma unroll
+        for (int pss = 0; pss < NPSS; ++pss) {
+            const int m = m0 + wm * (TM * 32) + i * 32 + pss * (64 / LPR) + rd_row;
+            if (m < M) epilogue_prefetch<bf16_t, EPI>(m, n0 + wn * (TN * 32) + rd_col, N, p, pre[i][pss]);
+        }
+    };
+    if (epilogue_reads<EPI>() && direct && PRE_ALL) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) prefetch_pass(i);
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        if (epilogue_reads<EPI>() && direct && !PRE_ALL) prefetch_pass(i);
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < TN; ++j)
@@ -667,7 +739,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                     make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
         __syncthreads();
 #pragma unroll
-        for (int pss = 0; pss < 32 / (64 / LPR); ++pss) {
+        for (int pss = 0; pss < NPSS; ++pss) {
             const int row = pss * (64 / LPR) + rd_row;
             const int m = m0 + wm * (TM * 32) + i * 32 + row;
             const int n = n0 + wn * (TN * 32) + rd_col;
@@ -680,6 +752,8 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                     Vec8<float>::store(split_ws + ((size_t)((logical - n_main) * tail_splits + split) * BM + (m - m0)) * BN + (n - n0), v);
                 } else if (splits > 1) {
                     Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
+                } else if (epilogue_reads<EPI>()) {
+                    epilogue8<bf16_t, EPI>(m, n, N, v, C, p, &pre[i][pss]);
                 } else {
                     epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
                 }
