@@ -182,6 +182,75 @@ ds_status ds_layout_get(const ds_layout* layout, ds_layout_view* view);
 void ds_layout_free(ds_layout* layout);
 
 /* ------------------------------------------------------------------------------------------
+ * Pipeline execution schedules and communication order (host only; C stages, M micro-batches).
+ * Orders are HOST int32 arrays [C][2*M]: order_mb[j*2M + k], order_kind[j*2M + k] = the k-th op
+ * of stage j (micro-batch, DS_OP_FWD / DS_OP_BWD).  Per-op data are HOST int64 [M][C]:
+ * x[i*C + j] for micro-batch i on stage j.
+ */
+enum { DS_OP_FWD = 0, DS_OP_BWD = 1 };
+enum {
+    DS_INSTR_FORWARD = 0, DS_INSTR_BACKWARD = 1,
+    DS_INSTR_SEND_ACT_START = 2, DS_INSTR_RECV_ACT_START = 3,
+    DS_INSTR_SEND_GRAD_START = 4, DS_INSTR_RECV_GRAD_START = 5,
+    DS_INSTR_WAIT_RECV_ACT = 6, DS_INSTR_WAIT_RECV_GRAD = 7
+};
+
+/*
+ * ds_schedule_adaptive — memory-aware adaptive scheduling (section "Pipeline Execution Schedule",
+ * Alg. 1).  Execution proceeds in cycles; in each cycle every stage, in stage order, takes at most
+ * one backward op and then at most one forward op from the heads of its buffers of ready ops; a
+ * forward op of micro-batch i runs on stage j only if  m_j + act[i][j] < limit[j]  (m_j = activation
+ * memory held by the stage), otherwise it stays at the head and the stage skips forward passes
+ * until backward passes have freed memory; ops unlocked during a cycle (next stage's forward, the
+ * last stage's own backward, previous stage's backward) join the buffers at the end of the cycle.
+ * All micro-batches start in the first stage's forward buffer, in index order.
+ * Errors: DS_EINVAL (null, C or M < 1, negative act), DS_EINFEASIBLE (some act[i][j] >= limit[j]:
+ * that micro-batch can never run; or a cycle in which no op could run).  n_cycles may be NULL.
+ */
+ds_status ds_schedule_adaptive(int32_t n_stages, int32_t n_mb, const int64_t* act, const int64_t* limit,
+                               int32_t* order_mb, int32_t* order_kind, int32_t* n_cycles);
+
+/*
+ * ds_schedule_1f1b — the one-forward-one-backward order the paper compares with (same section,
+ * "on the n-th device, it executes c + 1 - n forward passes, followed by regular backward-forward
+ * cycles"): stage j (0-based) runs min(C - j, M) forwards, then alternates one backward and one
+ * forward while forwards are left, then the remaining backwards; micro-batches in index order.
+ */
+ds_status ds_schedule_1f1b(int32_t n_stages, int32_t n_mb, int32_t* order_mb, int32_t* order_kind);
+
+/*
+ * ds_schedule_simulate — device timeline of given per-stage orders under given op times (what
+ * section "Communication Planning" simulates with the cost model).  A stage executes its ops in
+ * order; an op starts when the stage is free and its predecessor has ended (forward: the same
+ * micro-batch's forward on the previous stage; backward: its backward on the next stage, on the
+ * last stage its own forward).  Communication takes no time.  Outputs: *makespan; idle[C] =
+ * makespan - busy time; peak[C] = largest activation memory held (taken at a forward's start,
+ * released at the backward's end, releases first at equal times; needs act); op_start / op_end
+ * [C][2*M].  idle, peak, act, op_start, op_end may be NULL.
+ * Errors: DS_EINVAL (null, sizes, a negative time, an order that is not a permutation of all 2*M
+ * ops of a stage, or orders that deadlock), DS_EOVERFLOW.
+ */
+ds_status ds_schedule_simulate(int32_t n_stages, int32_t n_mb, const int32_t* order_mb, const int32_t* order_kind,
+                               const int64_t* t_fwd, const int64_t* t_bwd, const int64_t* act,
+                               int64_t* makespan, int64_t* idle, int64_t* peak, int64_t* op_start, int64_t* op_end);
+
+/*
+ * ds_comm_plan — order of communication between adjacent stages and the per-stage instruction
+ * stream (section "Communication Planning").  Ops of the simulated timeline are visited in
+ * ascending end time (ties: lower stage, then earlier op of that stage); a forward on stage j < C-1
+ * queues SEND_ACT_START on j and RECV_ACT_START on j+1, a backward on stage j > 0 queues
+ * SEND_GRAD_START on j and RECV_GRAD_START on j-1: both ends of a transfer are queued together, so
+ * adjacent stages see their common transfers in the same order.  The stream of a stage lists its
+ * compute ops in order; every queued start goes before the first compute op of that stage that
+ * starts at or after the start's time; the wait for a received tensor goes immediately before the
+ * op that consumes it.  stream_code / stream_mb: HOST int32 [C][8*M] (DS_INSTR_*, micro-batch),
+ * stream_len: HOST int32[C].  Errors as ds_schedule_simulate.
+ */
+ds_status ds_comm_plan(int32_t n_stages, int32_t n_mb, const int32_t* order_mb, const int32_t* order_kind,
+                       const int64_t* t_fwd, const int64_t* t_bwd,
+                       int32_t* stream_code, int32_t* stream_mb, int32_t* stream_len);
+
+/* ------------------------------------------------------------------------------------------
  * Stage: the transformer layers of one pipeline stage (what the ForwardPass / BackwardPass
  * pipeline instructions execute, section "Overview", paragraph "Execution plans").
  */

@@ -24,7 +24,8 @@ PROF_KINDS = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "n
 _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOMEM", -4: "DS_EOVERFLOW",
                  -5: "DS_EHIP", -6: "DS_ELAYOUT"}
 
-EXPORTS = ["dp_plan", "dp_plan_replicas", "ds_assign_replicas", "ds_cost_table_build", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
+EXPORTS = ["dp_plan", "dp_plan_replicas", "ds_assign_replicas", "ds_cost_table_build", "ds_schedule_adaptive",
+           "ds_schedule_1f1b", "ds_schedule_simulate", "ds_comm_plan", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "stage_fwd_bwd",
            "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_attention_fwd",
            "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
@@ -238,6 +239,64 @@ def ds_assign_replicas(times, n_replicas):
                                   rep.ctypes.data_as(C.c_void_p), sums.ctypes.data_as(C.c_void_p))
     _check(rc, "ds_assign_replicas")
     return rep[:t.shape[0]].copy(), sums
+
+
+def _i64(a, shape=None):
+    a = np.ascontiguousarray(a, dtype=np.int64)
+    if shape is not None and a.shape != shape:
+        raise ValueError("expected an int64 array of shape %s, got %s" % (shape, a.shape))
+    return a
+
+
+def _vp(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def ds_schedule_adaptive(act, limit):
+    """act [M, C], limit [C] -> (order_mb [C, 2M], order_kind [C, 2M], cycles)."""
+    act = _i64(act)
+    M, Cn = act.shape
+    limit = _i64(limit, (Cn,))
+    omb, okind = np.zeros((Cn, 2 * M), np.int32), np.zeros((Cn, 2 * M), np.int32)
+    cyc = C.c_int32(0)
+    _check(lib().ds_schedule_adaptive(C.c_int32(Cn), C.c_int32(M), _vp(act), _vp(limit), _vp(omb), _vp(okind), C.byref(cyc)),
+           "ds_schedule_adaptive")
+    return omb, okind, cyc.value
+
+
+def ds_schedule_1f1b(n_stages, n_mb):
+    omb, okind = np.zeros((n_stages, 2 * n_mb), np.int32), np.zeros((n_stages, 2 * n_mb), np.int32)
+    _check(lib().ds_schedule_1f1b(C.c_int32(n_stages), C.c_int32(n_mb), _vp(omb), _vp(okind)), "ds_schedule_1f1b")
+    return omb, okind
+
+
+def ds_schedule_simulate(order_mb, order_kind, t_fwd, t_bwd, act=None):
+    """-> dict(makespan, idle [C], peak [C] or None, start [C, 2M], end [C, 2M])."""
+    omb = np.ascontiguousarray(order_mb, dtype=np.int32)
+    okind = np.ascontiguousarray(order_kind, dtype=np.int32)
+    Cn, M2 = omb.shape
+    M = M2 // 2
+    tf, tb = _i64(t_fwd, (M, Cn)), _i64(t_bwd, (M, Cn))
+    a = None if act is None else _i64(act, (M, Cn))
+    mk = C.c_int64(0)
+    idle, peak = np.zeros(Cn, np.int64), (np.zeros(Cn, np.int64) if a is not None else None)
+    st, en = np.zeros((Cn, M2), np.int64), np.zeros((Cn, M2), np.int64)
+    _check(lib().ds_schedule_simulate(C.c_int32(Cn), C.c_int32(M), _vp(omb), _vp(okind), _vp(tf), _vp(tb), _vp(a), C.byref(mk),
+                                      _vp(idle), _vp(peak), _vp(st), _vp(en)), "ds_schedule_simulate")
+    return {"makespan": mk.value, "idle": idle, "peak": peak, "start": st, "end": en}
+
+
+def ds_comm_plan(order_mb, order_kind, t_fwd, t_bwd):
+    """-> list over stages of [(DS_INSTR_* code, micro-batch), ...]."""
+    omb = np.ascontiguousarray(order_mb, dtype=np.int32)
+    okind = np.ascontiguousarray(order_kind, dtype=np.int32)
+    Cn, M2 = omb.shape
+    M = M2 // 2
+    tf, tb = _i64(t_fwd, (M, Cn)), _i64(t_bwd, (M, Cn))
+    code, mb, ln = np.zeros((Cn, 8 * M), np.int32), np.zeros((Cn, 8 * M), np.int32), np.zeros(Cn, np.int32)
+    _check(lib().ds_comm_plan(C.c_int32(Cn), C.c_int32(M), _vp(omb), _vp(okind), _vp(tf), _vp(tb), _vp(code), _vp(mb), _vp(ln)),
+           "ds_comm_plan")
+    return [[(int(code[j, k]), int(mb[j, k])) for k in range(ln[j])] for j in range(Cn)]
 
 
 def ds_layout_from_cuts(lengths, cuts, perm=None, lengths_tgt=None, pad_to=0, pad_to_tgt=0, cost_model=None, num_stages=1):

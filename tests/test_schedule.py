@@ -1,0 +1,68 @@
+"""Schedules and communication order: the library against the oracle (host code, exact)."""
+import numpy as np
+import pytest
+
+from oracle import schedule as osch
+from paper_2311_10418_amd import binding as ds
+
+
+def _orders(O, C, M):
+    omb = np.array([[i for i, _ in O[j]] for j in range(C)], np.int32)
+    okind = np.array([[k for _, k in O[j]] for j in range(C)], np.int32)
+    return omb, okind
+
+
+def _as_list(omb, okind):
+    return [[(int(i), int(k)) for i, k in zip(omb[j], okind[j])] for j in range(omb.shape[0])]
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_adaptive_and_1f1b_orders(seed):
+    rng = np.random.default_rng(seed)
+    C, M = int(rng.integers(1, 7)), int(rng.integers(1, 14))
+    a = rng.integers(0, 40, (M, C))
+    l = a.max(axis=0) + rng.integers(1, 100, C)
+    omb, okind, cycles = ds.ds_schedule_adaptive(a, l)
+    O, ocycles = osch.adaptive(C, M, a.tolist(), l.tolist())
+    assert _as_list(omb, okind) == O and cycles == ocycles
+    omb, okind = ds.ds_schedule_1f1b(C, M)
+    assert _as_list(omb, okind) == osch.one_f_one_b(C, M)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_timeline_and_comm_plan(seed):
+    rng = np.random.default_rng(100 + seed)
+    C, M = int(rng.integers(1, 6)), int(rng.integers(1, 12))
+    a = rng.integers(1, 30, (M, C))
+    tf, tb = rng.integers(0, 50, (M, C)), rng.integers(0, 90, (M, C))
+    if seed % 2:
+        omb, okind, _ = ds.ds_schedule_adaptive(a, a.max(axis=0) + rng.integers(1, 60, C))
+    else:
+        omb, okind = ds.ds_schedule_1f1b(C, M)
+    O = _as_list(omb, okind)
+    got = ds.ds_schedule_simulate(omb, okind, tf, tb, a)
+    ref = osch.simulate(C, M, O, tf.tolist(), tb.tolist(), a.tolist())
+    assert got["makespan"] == ref["makespan"]
+    assert got["idle"].tolist() == ref["idle"] and got["peak"].tolist() == ref["peak"]
+    assert got["start"].tolist() == ref["start"] and got["end"].tolist() == ref["end"]
+    _, stream = osch.comm_plan(C, M, O, ref)
+    assert ds.ds_comm_plan(omb, okind, tf, tb) == stream
+
+
+def test_errors():
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_schedule_adaptive([[5, 5], [9, 1]], [9, 9])
+    assert e.value.code == ds.DS_EINFEASIBLE
+    omb, okind = ds.ds_schedule_1f1b(2, 1)
+    bad = okind.copy()
+    bad[0] = [1, 0]                                   # backward before its own forward: deadlock
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_schedule_simulate(omb, bad, [[1, 1]], [[1, 1]])
+    assert e.value.code == ds.DS_EINVAL
+    dup = omb.copy()
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_schedule_simulate(dup, np.zeros_like(okind), [[1, 1]], [[1, 1]])      # forward listed twice
+    assert e.value.code == ds.DS_EINVAL
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_schedule_simulate(omb, okind, [[2 ** 62, 2 ** 62]], [[2 ** 62, 2 ** 62]])
+    assert e.value.code == ds.DS_EOVERFLOW
