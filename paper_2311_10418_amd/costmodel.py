@@ -160,6 +160,17 @@ def measure_plan(runner, layout, lens, table, reps=3):
     }
 
 
+def token_based_cuts(sorted_lens, budget):
+    """Equal-token-count micro-batching (the paper's TB baseline, section "Evaluation", ablation): walk the sorted
+    list and close a micro-batch when one more sample would push count * longest over the budget."""
+    cuts, start = [0], 0
+    for k in range(1, len(sorted_lens) + 1):
+        if k == len(sorted_lens) or (k + 1 - start) * int(sorted_lens[k]) > budget:
+            cuts.append(k)
+            start = k
+    return cuts
+
+
 def report(config="gpt_2048_bf16", seed=0, reps=3, log=None):
     cfg = wl.CONFIGS[config]
     if cfg["kind"] != "gpt":
@@ -179,9 +190,15 @@ def report(config="gpt_2048_bf16", seed=0, reps=3, log=None):
     t_ms = profile_grid(runner, b_grid, l_grid, max_rows=max_rows, reps=reps, log=log)
     table = build_table(b_grid, l_grid, t_ms, tb, tl)
     prof = ds.dp_plan(lens, ds.make_cost_model(kind=ds.DS_COST_TABLE, table=table), cap, c)
-    if prof.total_rows > max_rows:                      # a plan that merges micro-batches pads: it needs more rows
+    order = np.argsort(lens, kind="stable").astype(np.int32)
+    tb_plans = {}
+    for budget in (cap // 4, cap // 2, cap):
+        cuts = token_based_cuts(lens[order], budget)
+        tb_plans["plan_token_based_%d" % budget] = ds.ds_layout_from_cuts(lens, cuts, perm=order)
+    need = max([int(prof.total_rows)] + [int(l.total_rows) for l in tb_plans.values()])
+    if need > max_rows:                                 # plans that merge micro-batches pad: they need more rows
         runner.close()
-        runner = StageRunner(cfg, max_rows=int(prof.total_rows), max_seqs=max(len(lens), b_grid[-1]), seed=seed)
+        runner = StageRunner(cfg, max_rows=need, max_seqs=max(len(lens), b_grid[-1]), seed=seed)
     out = {
         "config": config, "n_seq": int(len(lens)), "non_pad_tokens": int(lens.sum()), "cap": cap, "num_stages": c,
         "b_grid": b_grid, "l_grid": l_grid,
@@ -189,7 +206,9 @@ def report(config="gpt_2048_bf16", seed=0, reps=3, log=None):
         "plan_polynomial_cost": measure_plan(runner, poly, lens, table, reps=reps),
         "plan_profiled_cost": measure_plan(runner, prof, lens, table, reps=reps),
     }
-    for key, lay in (("plan_polynomial_cost", poly), ("plan_profiled_cost", prof)):
+    for key, lay in tb_plans.items():
+        out[key] = measure_plan(runner, lay, lens, table, reps=reps)
+    for key in ["plan_polynomial_cost", "plan_profiled_cost"] + list(tb_plans):
         m = out[key]
         m["eq1_predicted_ms"] = (c - 1) * m["predicted_max_ms"] + m["predicted_sum_ms"]
         m["eq1_measured_ms"] = (c - 1) * m["measured_max_single_call_ms"] + m["measured_sum_of_single_calls_ms"]
