@@ -902,15 +902,16 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
     const int tiles = tiles_m * tiles_n;
     int splits = 1;
     if (EPI == DS_EPI_ACC32 && split_ws) splits = choose_splits(tiles, nt, M, N, split_ws_floats);
-    // tail split-K: tiles beyond the last whole round over the compute units share that round
+    // tail split-K: the tiles beyond the last whole round over the compute units share that round; a launch with
+    // fewer tiles than compute units (small micro-batches) is all tail, so that the K loop is spread over the chip
     int n_main = tiles, tail_splits = 1;
     if (splits == 1 && split_ws) {
         const int n_cu = cu_count();
         const int rem = tiles % n_cu;
-        if (tiles > n_cu && rem > 0) {
+        if (rem > 0) {
             int ts = n_cu / rem;
             if (ts > 32) ts = 32;
-            if (ts > nt / 8) ts = nt / 8;
+            if (ts > nt / 4) ts = nt / 4;
             while (ts > 1 && (size_t)rem * ts * (BM * BN) > split_ws_floats) --ts;
             if (ts > 1) {
                 const int per = (nt + ts - 1) / ts;
