@@ -125,6 +125,19 @@ ds_status dp_plan(const int32_t* len, const int32_t* len_tgt, int32_t n,
                   ds_layout** out);
 
 /*
+ * dp_plan_sampled — dp_plan with t_max sampled at fixed intervals (section "Micro-batch
+ * Construction", end of "Dynamic programming": the paper only considers t_max values 5 us apart).
+ * Candidates are the multiples of t_max_interval (>= 1, in the cost model's unit); for each, Eq2 runs
+ * over the slices whose cost does not exceed it, and the candidate minimising
+ * (num_stages-1)*candidate + f(N; candidate) wins (ties as dp_plan).  The layout reports the
+ * objective and t_max of the partition chosen.  Its objective is at most
+ * (num_stages-1)*t_max_interval above dp_plan's; with interval 1 the two calls agree.
+ */
+ds_status dp_plan_sampled(const int32_t* len, const int32_t* len_tgt, int32_t n,
+                          const ds_cost_model* cm, int64_t mem_cap_tokens, int32_t num_stages,
+                          int64_t t_max_interval, ds_layout** out);
+
+/*
  * dp_plan_replicas — micro-batch construction under hybrid data + pipeline parallelism (section
  * "Micro-batch Construction", paragraph "Balance data parallel model replicas"): the same
  * dynamic programme with the sum term weighted 1/n_replicas, kept exact by scaling, i.e. minimising

@@ -24,7 +24,7 @@ PROF_KINDS = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "n
 _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOMEM", -4: "DS_EOVERFLOW",
                  -5: "DS_EHIP", -6: "DS_ELAYOUT"}
 
-EXPORTS = ["dp_plan", "dp_plan_replicas", "ds_assign_replicas", "ds_cost_table_build", "ds_schedule_adaptive",
+EXPORTS = ["dp_plan", "dp_plan_sampled", "dp_plan_replicas", "ds_assign_replicas", "ds_cost_table_build", "ds_schedule_adaptive",
            "ds_schedule_1f1b", "ds_schedule_simulate", "ds_comm_plan", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "stage_fwd_bwd",
            "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_attention_fwd",
@@ -212,6 +212,16 @@ def dp_plan(lengths, cost_model, mem_cap_tokens, num_stages, lengths_tgt=None):
     rc = lib().dp_plan(_hp(ln), _hp(lt), C.c_int32(n), C.byref(cost_model) if cost_model is not None else None,
                        C.c_int64(mem_cap_tokens), C.c_int32(num_stages), C.byref(out))
     _check(rc, "dp_plan")
+    return Layout(out)
+
+
+def dp_plan_sampled(lengths, cost_model, mem_cap_tokens, num_stages, t_max_interval, lengths_tgt=None):
+    ln, lt = _np_i32(lengths), _np_i32(lengths_tgt)
+    out = C.c_void_p()
+    n = 0 if ln is None else int(ln.shape[0])
+    rc = lib().dp_plan_sampled(_hp(ln), _hp(lt), C.c_int32(n), C.byref(cost_model) if cost_model is not None else None,
+                               C.c_int64(mem_cap_tokens), C.c_int32(num_stages), C.c_int64(t_max_interval), C.byref(out))
+    _check(rc, "dp_plan_sampled")
     return Layout(out)
 
 

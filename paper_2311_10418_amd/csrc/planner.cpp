@@ -161,8 +161,10 @@ uint64_t ds_next_layout_uid() { return g_uid.fetch_add(1); }
 
 // The dynamic programme of Eq2 over every candidate t_max, minimising  w * max_m t + sum_m t  (Eq1 with
 // w = num_stages - 1; the data-parallel variant passes w = n_replicas * (num_stages - 1)).
+// quantum > 0: t_max is sampled at the multiples of quantum (a slice cost t admits the slice from the candidate
+// ceil(t / quantum) * quantum on); the layout then reports the objective and t_max of the partition chosen.
 static ds_status plan_impl(const int32_t* len, const int32_t* len_tgt, int32_t n, const ds_cost_model* cm, int64_t cap,
-                           int64_t w, ds_layout** out) {
+                           int64_t w, ds_layout** out, int64_t quantum = 0) {
     if (!out) return DS_EINVAL;
     *out = nullptr;
     ds_status st = check_lengths(len, len_tgt, n);
@@ -239,8 +241,12 @@ static ds_status plan_impl(const int32_t* len, const int32_t* len_tgt, int32_t n
         bool found = false;
         size_t k = 0;
         while (k < slices.size()) {
-            const int64_t T = slices[k].t;
-            while (k < slices.size() && slices[k].t == T) {
+            int64_t T = slices[k].t;
+            if (quantum > 0) {
+                const int64_t up = T / quantum + (T % quantum != 0);
+                if (__builtin_mul_overflow(up, quantum, &T)) return DS_EOVERFLOW;
+            }
+            while (k < slices.size() && slices[k].t <= T) {
                 active[slices[k].j].push_back({slices[k].i, slices[k].t});
                 ++k;
             }
@@ -311,6 +317,16 @@ static ds_status plan_impl(const int32_t* len, const int32_t* len_tgt, int32_t n
         }
         lo->objective = bestJ;
         lo->t_max = bestT;
+        if (quantum > 0) {                                   // report the chosen partition itself, not the sampled bound
+            int64_t mx = 0, sum = 0, J;
+            for (int64_t t : lo->mb_cost) {
+                mx = std::max(mx, t);
+                if (__builtin_add_overflow(sum, t, &sum)) return DS_EOVERFLOW;
+            }
+            if (__builtin_mul_overflow(w, mx, &J) || __builtin_add_overflow(J, sum, &J)) return DS_EOVERFLOW;
+            lo->objective = J;
+            lo->t_max = mx;
+        }
         *out = lo.release();
         return DS_OK;
     } catch (const std::bad_alloc&) {
@@ -325,6 +341,13 @@ extern "C" ds_status dp_plan(const int32_t* len, const int32_t* len_tgt, int32_t
     if (out) *out = nullptr;
     if (c < 1) return DS_EINVAL;
     return plan_impl(len, len_tgt, n, cm, cap, (int64_t)c - 1, out);
+}
+
+extern "C" ds_status dp_plan_sampled(const int32_t* len, const int32_t* len_tgt, int32_t n, const ds_cost_model* cm,
+                                     int64_t cap, int32_t c, int64_t t_max_interval, ds_layout** out) {
+    if (out) *out = nullptr;
+    if (c < 1 || t_max_interval < 1) return DS_EINVAL;
+    return plan_impl(len, len_tgt, n, cm, cap, (int64_t)c - 1, out, t_max_interval);
 }
 
 // ------------------------------------------------------------------------------------ replica balancing
