@@ -533,8 +533,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int NW = WM * WN;                    // wavefronts
     constexpr int TM = 256 / WM / 32, TN = 256 / WN / 32;   // 32x32 MFMA tiles per wavefront
-    constexpr int LPW = 16 / NW;                   // direct-load instructions per operand per wavefront per K tile
-    static_assert(16 % NW == 0 && LPW >= 1, "wavefront count must divide 16");
+    static_assert(16 % NW == 0, "wavefront count must divide 16");
     constexpr int STG_LD = TN * 32 + 4;            // fp32 row stride of the epilogue staging block
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -573,7 +572,14 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
     nt_tile_coords(logical, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const int nt_total = TNF ? (K + NT_DK - 1) / NT_DK : K / NT_DK;
+    // K tiles: TN form 32 k-rows of 512 bytes, ring of 4 stages; NT form 64 k (one whole 128-byte line per row and
+    // request, which is what the L2 serves at full rate), 2 stages
+    constexpr int DK = TNF ? NT_DK : 64;
+    constexpr int NS = TNF ? NT_NS : 2;
+    constexpr int HALF = 256 * DK * 2, STAGE = 2 * HALF;
+    constexpr int LPW = HALF / 1024 / NW;          // direct-load instructions per operand per wavefront per K tile
+    static_assert(NS * STAGE == NT_NS * NT_STAGE, "both forms use the same 128 KB of LDS");
+    const int nt_total = TNF ? (K + DK - 1) / DK : K / DK;
     const int per_split = (nt_total + nsplit - 1) / nsplit;
     const int t_begin = split * per_split;
     const int t_end = (t_begin + per_split) < nt_total ? (t_begin + per_split) : nt_total;
@@ -592,9 +598,9 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int u = (wave * LPW + i) * 64 + lane;
-            if constexpr (!TNF) {                                    // 16-byte unit of the 256 x 4 tile
-                const int row = u >> 2, slot = u & 3;
-                const int chunk = slot ^ ((row >> 2) & 3);
+            if constexpr (!TNF) {                                    // 16-byte unit of the 256 x 8 tile (128-byte rows)
+                const int row = u >> 3, slot = u & 7;
+                const int chunk = slot ^ ((row >> 1) & 7);
                 int ra_ = m0 + row;
                 ra_ = ra_ < M ? ra_ : M - 1;                        // rows past the edge: clamped, never stored
                 offA[i] = (uint32_t)(((long long)(ra_ - m0) * K + chunk * 8) * 2);
@@ -610,22 +616,22 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
         }
         const char* pa = reinterpret_cast<const char*>(A) + (TNF ? (long long)m0 * 2 : (long long)m0 * K * 2);
         const char* pb = reinterpret_cast<const char*>(B) + (TNF ? (long long)n0 * 2 : (long long)n0 * K * 2);
-        const long long tile_step_a = TNF ? (long long)NT_DK * M * 2 : NT_DK * 2;
-        const long long tile_step_b = TNF ? (long long)NT_DK * N * 2 : NT_DK * 2;
+        const long long tile_step_a = TNF ? (long long)DK * M * 2 : DK * 2;
+        const long long tile_step_b = TNF ? (long long)DK * N * 2 : DK * 2;
         const int frag_row = lane & 31, frag_half = lane >> 5;
         const int t_last = t_end - 1;
         auto issue = [&](int tile, int stage) {
             tile = tile < t_last ? tile : t_last;
             const char* ga = pa + tile * tile_step_a;
             const char* gb = pb + tile * tile_step_b;
-            char* la = smem + stage * NT_STAGE + wave * (LPW * 1024);
-            char* lb = la + NT_HALF;
-            const int k_left = TNF ? K - tile * NT_DK : NT_DK;      // valid k-rows of this tile
+            char* la = smem + stage * STAGE + wave * (LPW * 1024);
+            char* lb = la + HALF;
+            const int k_left = TNF ? K - tile * DK : DK;            // valid k-rows of this tile
 #pragma unroll
             for (int i = 0; i < LPW; ++i) {
                 const char* sa = ga + offA[i];
                 const char* sb = gb + offB[i];
-                if (TNF && k_left < NT_DK && krow[i] >= k_left) {
+                if (TNF && k_left < DK && krow[i] >= k_left) {
                     sa = reinterpret_cast<const char*>(&g_zero16);
                     sb = sa;
                 }
@@ -633,8 +639,9 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                 lds_dma16(sb, lb + i * 1024);
             }
         };
-        // NT: 64-byte rows: 16 consecutive rows at one chunk index must hit 16 different 16-byte units
-        auto off32 = [](int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4); };
+        // NT: 128-byte rows: 16 consecutive rows at one chunk index must hit 16 different 16-byte units of a 256-byte
+        // window: rows 2q and 2q+1 differ by 128 bytes, the XOR with (row/2)%8 separates the 8 row pairs
+        auto off64 = [](int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); };
         // TN: 512-byte rows; a transpose read covers 4 consecutive k-rows x 64 bytes per 32 lanes, so the 64-byte
         // unit index is XORed with row%4.  Lane (i = lane%16, hm = lane/16%2, g = lane/32) addresses k-row
         // 4g + i/4 (+8 for the second read, +16 per k step) at features hm*16 + (i%4)*4 of a 32-feature unit.
@@ -651,17 +658,17 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
             return __builtin_bit_cast(bf16x8_t, v);
         };
         auto load_frags = [&](int stage, int ks, bf16x8_t (&fa)[TM], bf16x8_t (&fb)[TN]) {
-            const char* a_base = smem + stage * NT_STAGE;
-            const char* b_base = a_base + NT_HALF;
+            const char* a_base = smem + stage * STAGE;
+            const char* b_base = a_base + HALF;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 if constexpr (TNF) fa[i] = read_tr(a_base, ks, wm * TM + i);
-                else fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off32(wm * (TM * 32) + i * 32 + frag_row, ks * 2 + frag_half));
+                else fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off64(wm * (TM * 32) + i * 32 + frag_row, ks * 2 + frag_half));
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 if constexpr (TNF) fb[j] = read_tr(b_base, ks, wn * TN + j);
-                else fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off32(wn * (TN * 32) + j * 32 + frag_row, ks * 2 + frag_half));
+                else fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off64(wn * (TN * 32) + j * 32 + frag_row, ks * 2 + frag_half));
             }
         };
         auto mma = [&](const bf16x8_t (&fa)[TM], const bf16x8_t (&fb)[TN]) {
@@ -677,27 +684,58 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
         // step run, ACROSS the tile boundary too, so that no wavefront waits on LDS latency right after the barrier
         // (all 8 wavefronts leave it together, so nobody would be left to cover for the others).
         bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-        issue(t_begin, 0);
-        issue(t_begin + 1, 1);
-        issue(t_begin + 2, 2);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * LPW));             // tile t_begin: at most the two newest tiles outstanding
-        __builtin_amdgcn_s_barrier();
-        load_frags(0, 0, fa0, fb0);
-        for (int tl = t_begin; tl < t_end; ++tl) {
-            const int st_ = (tl - t_begin) & (NT_NS - 1);
-            // stage (tl-1)%4 is free: every wavefront finished reading it before the barrier it has just passed
-            issue(tl + 3, (st_ + 3) & (NT_NS - 1));
-            load_frags(st_, 1, fa1, fb1);
-            __builtin_amdgcn_sched_barrier(0);
-            mma(fa0, fb0);
-            __builtin_amdgcn_sched_barrier(0);
-            // tile tl+1: this wavefront's part has landed (two newest tiles outstanding), its LDS reads are done ...
-            __builtin_amdgcn_s_waitcnt(0x0070 | (4 * LPW));         // vmcnt(4*LPW) lgkmcnt(0)
-            __builtin_amdgcn_s_barrier();                           // ... and everyone's
-            load_frags((st_ + 1) & (NT_NS - 1), 0, fa0, fb0);       // past the last tile: a stale but valid stage, unused
-            __builtin_amdgcn_sched_barrier(0);
-            mma(fa1, fb1);
-            __builtin_amdgcn_sched_barrier(0);
+        if constexpr (TNF) {
+            issue(t_begin, 0);
+            issue(t_begin + 1, 1);
+            issue(t_begin + 2, 2);
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * LPW));         // tile t_begin: at most the two newest tiles outstanding
+            __builtin_amdgcn_s_barrier();
+            load_frags(0, 0, fa0, fb0);
+            for (int tl = t_begin; tl < t_end; ++tl) {
+                const int st_ = (tl - t_begin) & (NS - 1);
+                // stage (tl-1)%4 is free: every wavefront finished reading it before the barrier it has just passed
+                issue(tl + 3, (st_ + 3) & (NS - 1));
+                load_frags(st_, 1, fa1, fb1);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(fa0, fb0);
+                __builtin_amdgcn_sched_barrier(0);
+                // tile tl+1: this wavefront's part has landed (two newest tiles outstanding), its LDS reads are done ...
+                __builtin_amdgcn_s_waitcnt(0x0070 | (4 * LPW));     // vmcnt(4*LPW) lgkmcnt(0)
+                __builtin_amdgcn_s_barrier();                       // ... and everyone's
+                load_frags((st_ + 1) & (NS - 1), 0, fa0, fb0);      // past the last tile: a stale but valid stage, unused
+                __builtin_amdgcn_sched_barrier(0);
+                mma(fa1, fb1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+            // two 64 KB stages: tile tl+1 is in flight while the four 16-deep steps of tile tl run; one barrier per tile
+            issue(t_begin, 0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            load_frags(0, 0, fa0, fb0);
+            for (int tl = t_begin; tl < t_end; ++tl) {
+                const int st_ = (tl - t_begin) & 1;
+                // the other stage is free: every wavefront finished reading it before the barrier it has just passed
+                issue(tl + 1, st_ ^ 1);
+                load_frags(st_, 1, fa1, fb1);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(fa0, fb0);
+                __builtin_amdgcn_sched_barrier(0);
+                load_frags(st_, 2, fa0, fb0);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(fa1, fb1);
+                __builtin_amdgcn_sched_barrier(0);
+                load_frags(st_, 3, fa1, fb1);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(fa0, fb0);
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(0x0070);                 // vmcnt(0) lgkmcnt(0): tile tl+1 landed, reads of tile tl done
+                __builtin_amdgcn_s_barrier();
+                load_frags(st_ ^ 1, 0, fa0, fb0);                   // past the last tile: a reloaded copy of it, unused
+                __builtin_amdgcn_sched_barrier(0);
+                mma(fa1, fb1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         // drain the redundant tail transfers before LDS is reused by the epilogue (explicit: the compiler does not
         // see transfers issued by lds_dma16)
@@ -898,7 +936,7 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
         attr_set = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
-    const int nt = TNF ? (K + NT_DK - 1) / NT_DK : K / NT_DK;
+    const int nt = TNF ? (K + NT_DK - 1) / NT_DK : K / 64;      // K tiles as the kernel counts them
     const int tiles = tiles_m * tiles_n;
     int splits = 1;
     if (EPI == DS_EPI_ACC32 && split_ws) splits = choose_splits(tiles, nt, M, N, split_ws_floats);
