@@ -53,6 +53,17 @@ def build_layout(ds, kind, lens, cfg):
         return ds.ds_layout_from_cuts(lens, list(range(0, n, 8)) + [n], pad_to=hi), "fixed padding to %d, 8 per micro-batch" % hi
     if kind == "packed":
         return ds.ds_layout_packed(lens, hi, 8), "first-fit packing into %d-token rows, 8 rows per micro-batch" % hi
+    if kind == "packed_dense":
+        # CONTEXT ONLY (timing, not the model's result): every packed row treated as ONE causal sequence, which is
+        # the work a dense kernel with a block-diagonal mask does on packed input (section "Background", packing)
+        pk = ds.ds_layout_packed(lens, hi, 8)
+        fill = np.zeros(pk.total_rows // hi, dtype=np.int32)
+        for r, l in zip(pk.seq_row, pk.seq_len):
+            fill[r // hi] = max(fill[r // hi], r % hi + l)
+        fill = fill[fill > 0]
+        nrow = len(fill)
+        return ds.ds_layout_from_cuts(fill, list(range(0, nrow, 8)) + [nrow], pad_to=hi), \
+            "CONTEXT ONLY: packed rows attended densely (block-diagonal mask cost), %d-token rows, 8 per micro-batch" % hi
     raise SystemExit("unknown layout " + kind)
 
 
@@ -100,7 +111,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="gpt_2048_bf16")
-    ap.add_argument("--layout", default="dp", choices=["dp", "fixed", "packed"])
+    ap.add_argument("--layout", default="dp", choices=["dp", "fixed", "packed", "packed_dense"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -176,7 +187,7 @@ def main():
         weights, grads = make_layers(ds.GPT_KEYS, L)
         x, dy = rnd(R), rnd(R)
         out, dx = torch.empty_like(x), torch.empty_like(x)
-        stage = ds.Stage(ds.DS_MODEL_GPT, code, L, d, H, F, max_rows=R, max_seqs=len(lens))
+        stage = ds.Stage(ds.DS_MODEL_GPT, code, L, d, H, F, max_rows=R, max_seqs=max(len(lens), layout.n_seq))
 
         def step():
             ds.stage_fwd_bwd(stage, layout, weights, x, dy, out, dx, grads, accumulate=False)
