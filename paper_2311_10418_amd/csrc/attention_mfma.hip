@@ -57,6 +57,14 @@ template <int HD> __device__ __forceinline__ int off_rows(int row, int chunk) { 
     return row * (HD * 2) + ((chunk ^ swz<HD>(row)) << 4);
 }
 
+// max of three through v_max3_f32 directly: fmaxf() makes the compiler canonicalise every operand first (one extra
+// multiply per score), which the hardware instruction does not need
+__device__ __forceinline__ float max3f(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 // accumulator registers 8u..8u+7 of a 32x32 tile -> one bf16 B fragment
 __device__ __forceinline__ bf16x8_t frag_from_acc(const f32x16_t& a, int u) {
     bf16x8_t f;
@@ -268,11 +276,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
             }
         const bool need_mask = (kv0 + 64 > kl) || (CAUSAL && kv0 + 63 > qw0);
         if (need_mask) {
+            // the volatile statement keeps the whole mask computation inside a real branch: hoisted or if-converted,
+            // its ~130 compare / select instructions would run on every step, not just on the diagonal and the tail
+            int kbase = kv0;
+            asm volatile("" : "+s"(kbase));
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int key = kv0 + kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+                    const int key = kbase + kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
                     if (key >= kl || (CAUSAL && key > qi)) sacc[kt][e] = -INFINITY;
                 }
         }
@@ -280,9 +292,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int e = 0; e < 16; e += 2) mx = fmaxf(mx, fmaxf(sacc[kt][e], sacc[kt][e + 1]));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m, mx * c);
+            for (int e = 0; e < 16; e += 2) mx = max3f(mx, sacc[kt][e], sacc[kt][e + 1]);
+        const float m_new = max3f(m, mx * c, __shfl_xor(mx, 32, 64) * c);
         float rs = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
