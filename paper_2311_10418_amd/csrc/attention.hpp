@@ -24,6 +24,9 @@ struct AttnArgs {
     const int32_t* n_items;                           // DEVICE [2]: query-side, key-side item counts
     const int2 *items_q, *items_k;                    // DEVICE (sequence, 128-row block), longest first
     int32_t max_items_q, max_items_k;                 // host upper bounds = grid sizes
+    // DEVICE [n_heads][q_total_rows][8] bf16 each: {hi, lo, 0 x 6} splits of lse/scale and of delta, written by the
+    // dQ kernel, fetched by the dK/dV kernel straight into LDS
+    void *aug_lse, *aug_delta;
 };
 
 size_t attn_scratch_bytes(int n_heads, int head_dim, int q_total_rows, int k_total_rows, int n_seq);

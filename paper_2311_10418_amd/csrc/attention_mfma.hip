@@ -65,6 +65,13 @@ __device__ __forceinline__ float max3f(float a, float b, float c) {
     return r;
 }
 
+// {hi, lo} bf16 pair with hi + lo = v to ~2^-17 relative, packed into one dword
+__device__ __forceinline__ uint32_t split_hi_lo(float v) {
+    const bf16_t hi = (bf16_t)v;
+    const bf16_t lo = (bf16_t)(v - (float)hi);
+    return (uint32_t)__builtin_bit_cast(unsigned short, hi) | ((uint32_t)__builtin_bit_cast(unsigned short, lo) << 16);
+}
+
 // accumulator registers 8u..8u+7 of a 32x32 tile -> one bf16 B fragment
 __device__ __forceinline__ bf16x8_t frag_from_acc(const f32x16_t& a, int u) {
     bf16x8_t f;
@@ -133,6 +140,10 @@ template <int HD> struct TileLoader {
         if (r0 + 64 <= n_valid) next(); else seek(r0);
     }
 };
+
+// s_waitcnt immediate "at most n vector-memory operations outstanding" (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at their maxima, i.e. not waited for)
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
 // this wavefront's direct loads have landed, then everybody's; the stage read in the previous step is free
 __device__ __forceinline__ void wait_tiles_and_sync() {
@@ -372,8 +383,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
         for (int j = 0; j < 8; ++j) delta = __builtin_fmaf((float)of[j], (float)dof[ks][j], delta);
     }
     delta += __shfl_xor(delta, 32, 64);
-    if (g == 0 && qi < ql) a.delta[(size_t)h * a.lse_stride + qrow0 + qi] = delta;      // for the dK/dV kernel
-    const float lse2 = a.lse[(size_t)h * a.lse_stride + qrow0 + qi_c] * kLog2e;
+    const float lse_q = a.lse[(size_t)h * a.lse_stride + qrow0 + qi_c];
+    if (g == 0 && qi < ql) {
+        // for the dK/dV kernel: delta itself, and the {hi, lo} bf16 splits of lse/scale and delta that it appends
+        // to its contractions (hi + lo reproduces the value to ~2^-17 relative)
+        const size_t at = (size_t)h * a.lse_stride + qrow0 + qi;
+        a.delta[at] = delta;
+        reinterpret_cast<uint4*>(a.aug_lse)[at] = make_uint4(split_hi_lo(lse_q * (1.0f / a.scale)), 0u, 0u, 0u);
+        reinterpret_cast<uint4*>(a.aug_delta)[at] = make_uint4(split_hi_lo(delta), 0u, 0u, 0u);
+    }
+    const float lse2 = lse_q * kLog2e;
     const float c = a.scale * kLog2e;
 
     TrOffsets<HD> tro;
@@ -442,13 +461,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------ backward: dK, dV
-// LDS, two stages of: Q tile, dO tile ([64][HD]) and the two statistics tiles ([64 rows][8] bf16:
-// {hi, lo, 0 x 6} of lse/scale and of delta).
+// LDS, a ring of four stages of: Q tile, dO tile ([64][HD]) and the two statistics tiles ([64 rows][8] bf16:
+// {hi, lo, 0 x 6} of lse/scale and of delta, as the dQ kernel left them).  Three blocks are in flight while one is
+// consumed: with one wavefront per SIMD (368 registers) nothing else hides the latency of the transfers.
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TILE = 64 * HD * 2;
     constexpr int STAGE = 2 * TILE + 2048;
+    constexpr int NS = 4;                               // ring of stages: three blocks in flight while one is consumed
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, g = lane >> 5;
@@ -471,30 +492,30 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
     TileLoader<HD> ldQ, ldO;
     ldQ.setup(Q, a.ldq, ql, wave, lane);
     ldO.setup(dO, a.ldo, ql, wave, lane);
-    if (nb > 0) {
-        ldQ.seek(q_begin);
-        ldO.seek(q_begin);
-        ldQ.issue(smem);
-        ldO.issue(smem + TILE);
-    }
-    const float* lse_row = a.lse + (size_t)h * a.lse_stride + qrow0;
-    const float* delta_row = a.delta + (size_t)h * a.lse_stride + qrow0;
-    const float inv_scale = 1.0f / a.scale;
-    auto load_stats = [&](int b, float& l, float& dl) {
-        if (tid < 64) {
-            int r = q_begin + b * 64 + tid;
+    const char* aug_src = reinterpret_cast<const char*>(wave == 0 ? a.aug_lse : a.aug_delta) +
+                          ((size_t)h * a.lse_stride + qrow0) * 16;
+    // block blk -> stage blk % 4: Q tile, dO tile, and (wavefronts 0 and 1) the two statistics tiles, all by direct
+    // transfers; indices past the last block are clamped (redundant transfers into a free stage keep the count of
+    // outstanding transfers the same at every step)
+    auto issue_block = [&](int blk) {
+        char* n = smem + (blk & (NS - 1)) * STAGE;
+        const int bc = blk < nb ? blk : nb - 1;
+        const int q0 = q_begin + bc * 64;
+        ldQ.seek(q0);
+        ldO.seek(q0);
+        ldQ.issue(n);
+        ldO.issue(n + TILE);
+        if (wave < 2) {
+            int r = q0 + lane;
             r = r < ql ? r : ql - 1;
-            l = lse_row[r] * inv_scale;
-            dl = delta_row[r];
+            lds_dma16(aug_src + (size_t)r * 16, n + 2 * TILE + wave * 1024);
         }
     };
-    auto split = [](float v) {                          // {hi, lo} bf16 with hi + lo = v to ~2^-17 relative
-        const bf16_t hi = (bf16_t)v;
-        const bf16_t lo = (bf16_t)(v - (float)hi);
-        return (uint32_t)__builtin_bit_cast(unsigned short, hi) | ((uint32_t)__builtin_bit_cast(unsigned short, lo) << 16);
-    };
-    float st_l = 0.f, st_d = 0.f;
-    if (nb > 0) load_stats(0, st_l, st_d);
+    if (nb > 0) {
+        issue_block(0);
+        issue_block(1);
+        issue_block(2);
+    }
 
     bf16x8_t kf[HD / 16], vf[HD / 16];
 #pragma unroll
@@ -518,27 +539,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) { dkacc[dt][e] = 0.f; dvacc[dt][e] = 0.f; }
 
+    // the K / V fragments (ordinary loads) are complete before the loop: left to the compiler, its waits for them
+    // would sit inside the loop as "nothing outstanding", which would also drain the transfers in flight
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     for (int b = 0; b < nb; ++b) {
         const int q0 = q_begin + b * 64;
-        char* sQ = smem + (b & 1) * STAGE;
+        char* sQ = smem + (b & (NS - 1)) * STAGE;
         char* sdO = sQ + TILE;
         char* s_lse = sdO + TILE;
         char* s_delta = s_lse + 1024;
-        __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this block's tiles and statistics have landed
-        if (tid < 64) {
-            *reinterpret_cast<uint4*>(s_lse + tid * 16) = make_uint4(split(st_l), 0u, 0u, 0u);
-            *reinterpret_cast<uint4*>(s_delta + tid * 16) = make_uint4(split(st_d), 0u, 0u, 0u);
-        }
-        __builtin_amdgcn_s_waitcnt(0xC07F);             // lgkmcnt(0): the statistics are in LDS
+        // block b has landed for this wavefront (the two newest blocks may still be in flight), then for everybody;
+        // the stage read in the previous step is free
+        if (wave < 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (2 * (HD / 32) + 1)));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (2 * (HD / 32))));
         __builtin_amdgcn_s_barrier();
-        if (b + 1 < nb) {
-            char* n = smem + ((b + 1) & 1) * STAGE;
-            ldQ.advance_to(q0 + 64);
-            ldO.advance_to(q0 + 64);
-            ldQ.issue(n);
-            ldO.issue(n + TILE);
-            load_stats(b + 1, st_l, st_d);
-        }
+        issue_block(b + 3);
         if (kw0 >= kl || (CAUSAL && q0 + 63 < kw0)) continue;
         const bool need_mask = (q0 + 64 > ql) || (CAUSAL && q0 < kw0 + 31);
 #pragma unroll
@@ -585,6 +600,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
             }
         }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // no transfer may still be writing LDS when the work-group ends
     if (ki < kl) {
         store_cols<HD>(dkacc, a.scale, (bf16_t*)a.dk + (krow0 + ki) * a.ldk + h * HD, g);
         store_cols<HD>(dvacc, 1.0f, (bf16_t*)a.dv + (krow0 + ki) * a.ldv + h * HD, g);
@@ -618,7 +634,7 @@ ds_status bwd_launch(const AttnArgs& a, hipStream_t st) {
     auto kq = attn_bwd_dq_mfma_kernel<HD, CAUSAL>;
     auto kkv = attn_bwd_dkv_mfma_kernel<HD, CAUSAL>;
     const int smem_q = 4 * (64 * HD * 2);
-    const int smem_kv = 2 * (2 * (64 * HD * 2) + 2048);
+    const int smem_kv = 4 * (2 * (64 * HD * 2) + 2048);
     ds_status r = set_smem(kq, smem_q, attr_q);
     if (r != DS_OK) return r;
     r = set_smem(kkv, smem_kv, attr_kv);
@@ -634,10 +650,15 @@ int items_bound(int total_rows, int n_seq) { return total_rows / 128 + n_seq; }
 
 }  // namespace
 
-// Scratch: two work lists (query-side and key-side blocks) and their two counters.
+// Scratch: two counters, two work lists (query-side and key-side blocks), then the two statistics tensors the
+// backward kernels hand over ([n_heads][q_total_rows] entries of 16 bytes each).
+static size_t lists_bytes(int q_total_rows, int k_total_rows, int n_seq) {
+    const size_t b = 256 + sizeof(int2) * ((size_t)items_bound(q_total_rows, n_seq) + (size_t)items_bound(k_total_rows, n_seq));
+    return (b + 255) & ~(size_t)255;
+}
 size_t attn_scratch_bytes(int n_heads, int head_dim, int q_total_rows, int k_total_rows, int n_seq) {
-    (void)n_heads; (void)head_dim;
-    return 256 + sizeof(int2) * ((size_t)items_bound(q_total_rows, n_seq) + (size_t)items_bound(k_total_rows, n_seq));
+    (void)head_dim;
+    return lists_bytes(q_total_rows, k_total_rows, n_seq) + 2 * (size_t)n_heads * q_total_rows * 16;
 }
 
 bool attn_mfma_supported(const AttnArgs& a) {
@@ -663,6 +684,8 @@ ds_status attn_prepare_lists(AttnArgs& a, bool need_key_side, hipStream_t st) {
     a.max_items_k = items_bound(a.k_total_rows, a.n_seq);
     a.items_q = (const int2*)(base + 256);
     a.items_k = a.items_q + a.max_items_q;
+    a.aug_lse = base + lists_bytes(a.q_total_rows, a.k_total_rows, a.n_seq);
+    a.aug_delta = (char*)a.aug_lse + (size_t)a.n_heads * a.q_total_rows * 16;
     if (a.lists_ready) return DS_OK;
     hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(1024), 0, st, a.n_seq, a.q_len, a.k_len, a.mask, 0, a.max_items_q,
                        (int2*)a.items_q, (int32_t*)base);
