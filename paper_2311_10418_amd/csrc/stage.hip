@@ -206,7 +206,6 @@ ds_status upload_stream(ds_stage* s, Stream& sm, int32_t* host, int max_rows, in
         sr[i] = row[i];
         sl[i] = len[i];
         max_len = std::max(max_len, len[i]);
-        if (i > 0 && row[i] < row[i - 1]) return DS_ELAYOUT;        // the attention kernels need ascending rows
         for (int r = 0; r < len[i]; ++r) rv[row[i] + r] = i;
     }
     DS_HIP_CHECK(hipMemcpyAsync(sm.row_valid, rv, sizeof(int32_t) * R, hipMemcpyHostToDevice, st));
