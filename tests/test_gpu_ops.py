@@ -110,7 +110,7 @@ def _varlen_case(rng, lens, h, hd, dt, cross_lens=None):
 def test_attention_self(dt, force, hd, causal):
     rng = np.random.default_rng(4)
     h = 2
-    lens = [1, 7, 64, 65, 130, 200, 333]
+    lens = [1, 7, 64, 65, 130, 200, 333, 700]
     d, T, rows, qkv, d_o = _varlen_case(rng, lens, h, hd, dt)
     dq = to_dev(qkv, dt)
     o = torch.zeros((T, d), dtype=dt, device=DEV)
@@ -118,8 +118,10 @@ def test_attention_self(dt, force, hd, causal):
     delta = torch.zeros((h, T), dtype=F32, device=DEV)
     dqkv = torch.zeros((T, 3 * d), dtype=dt, device=DEV)
     ddo = to_dev(d_o, dt)
-    t_rows = torch.from_numpy(rows).to(DEV)
-    t_lens = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    # the sequence table is handed over in an arbitrary order: nothing may depend on ascending rows
+    order = rng.permutation(len(lens))
+    t_rows = torch.from_numpy(np.ascontiguousarray(rows[order])).to(DEV)
+    t_lens = torch.tensor([lens[i] for i in order], dtype=torch.int32, device=DEV)
     scratch = torch.zeros(ds.ds_attention_scratch_bytes(h, hd, T, T, len(lens)), dtype=torch.uint8, device=DEV)
     es = dq.element_size()
     base = dq.data_ptr()
