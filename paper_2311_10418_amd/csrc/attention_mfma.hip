@@ -141,10 +141,6 @@ template <int HD> struct TileLoader {
     }
 };
 
-// s_waitcnt immediate "at most n vector-memory operations outstanding" (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
-// expcnt 6:4 and lgkmcnt 11:8 left at their maxima, i.e. not waited for)
-constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
-
 // this wavefront's direct loads have landed, then everybody's; the stage read in the previous step is free
 __device__ __forceinline__ void wait_tiles_and_sync() {
     __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)

@@ -99,6 +99,10 @@ __device__ __forceinline__ void lds_dma16(const void* gptr, const void* lds_ptr)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_addr) : "memory", "m0");
 }
 
+// s_waitcnt immediate "at most n vector-memory operations outstanding" (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at their maxima, i.e. not waited for)
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+
 static inline size_t dtype_size(int32_t dtype) { return dtype == DS_DTYPE_BF16 ? 2 : 4; }
 
 // ---- launchers shared between translation units (all enqueue on `st`, return ds_status)

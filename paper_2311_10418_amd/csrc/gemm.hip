@@ -501,6 +501,15 @@ constexpr int NT_DK = 32, NT_NS = 4, NT_HALF = 256 * NT_DK * 2, NT_STAGE = 2 * N
 #define NT_WM 2
 #define NT_WN 4
 #endif
+// how a K tile's direct-load instructions are spread over the MFMA groups of the main loops (see the loops)
+#ifndef NT_G0
+#define NT_G0 4
+#define NT_G1 4
+#define NT_G2 0
+#endif
+#ifndef TN_PRE
+#define TN_PRE 2
+#endif
 
 // tile number -> tile coordinates: groups of 8 tile rows, column-major inside a group
 __host__ __device__ __forceinline__ void nt_tile_coords(int logical, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
@@ -584,13 +593,16 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
     const int t_begin = split * per_split;
     const int t_end = (t_begin + per_split) < nt_total ? (t_begin + per_split) : nt_total;
 
-    f32x16_t acc[TM][TN];
+    // accumulators: TM16 x TN16 blocks of 16 x 16 (v_mfma_f32_16x16x32_bf16: at the chip's power limit this shape
+    // sustains about a sixth more than 32x32x16 on random operands, at the same LDS traffic per flop)
+    constexpr int TM16 = 2 * TM, TN16 = 2 * TN, HA = TM16 / 2;
+    f32x4_t acc[TM16][TN16];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM16; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN16; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
     if (t_begin < t_end) {
         uint32_t offA[LPW], offB[LPW];
@@ -608,7 +620,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                 krow[i] = 0;
             } else {                                                // 16-byte unit of the 32 x 32 tile (512-byte rows)
                 const int row = u >> 5, pos = u & 31;
-                const int chunk = (((pos >> 2) ^ (row & 3)) << 2) | (pos & 3);
+                const int chunk = (((pos >> 1) ^ (row & 7)) << 1) | (pos & 1);
                 offA[i] = (uint32_t)(((long long)row * M + chunk * 8) * 2);
                 offB[i] = (uint32_t)(((long long)row * N + chunk * 8) * 2);
                 krow[i] = row;
@@ -618,7 +630,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
         const char* pb = reinterpret_cast<const char*>(B) + (TNF ? (long long)n0 * 2 : (long long)n0 * K * 2);
         const long long tile_step_a = TNF ? (long long)DK * M * 2 : DK * 2;
         const long long tile_step_b = TNF ? (long long)DK * N * 2 : DK * 2;
-        const int frag_row = lane & 31, frag_half = lane >> 5;
+        const int frag_row = lane & 15, frag_grp = lane >> 4;       // operand row / k group of this lane
         const int t_last = t_end - 1;
         auto issue = [&](int tile, int stage) {
             tile = tile < t_last ? tile : t_last;
@@ -639,101 +651,146 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                 lds_dma16(sb, lb + i * 1024);
             }
         };
+        // One transfer of a K tile: s = 2*i + (0: A, 1: B), i < LPW.  The texture path of a compute unit takes 16
+        // cycles per transfer, 64 of them per 64 KB, and a wavefront cannot issue anything else while its own
+        // transfers queue up there, so the main loops hand them out one at a time between the MFMAs instead of in a
+        // burst after the barrier (which left the matrix cores idle for about a quarter of every tile).
+        auto issue_one = [&](int tile, int stage, int s) {
+            tile = tile < t_last ? tile : t_last;
+            const int i = s >> 1;
+            const bool is_b = s & 1;
+            const char* g = (is_b ? pb + tile * tile_step_b + offB[i] : pa + tile * tile_step_a + offA[i]);
+            if (TNF && K - tile * DK < DK && krow[i] >= K - tile * DK) g = reinterpret_cast<const char*>(&g_zero16);
+            lds_dma16(g, smem + stage * STAGE + (is_b ? HALF : 0) + wave * (LPW * 1024) + i * 1024);
+        };
         // NT: 128-byte rows: 16 consecutive rows at one chunk index must hit 16 different 16-byte units of a 256-byte
         // window: rows 2q and 2q+1 differ by 128 bytes, the XOR with (row/2)%8 separates the 8 row pairs
         auto off64 = [](int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); };
-        // TN: 512-byte rows; a transpose read covers 4 consecutive k-rows x 64 bytes per 32 lanes, so the 64-byte
-        // unit index is XORed with row%4.  Lane (i = lane%16, hm = lane/16%2, g = lane/32) addresses k-row
-        // 4g + i/4 (+8 for the second read, +16 per k step) at features hm*16 + (i%4)*4 of a 32-feature unit.
-        const int tr_x = (lane >> 2) & 3;
-        const int tr_base = (4 * (lane >> 5) + ((lane & 15) >> 2)) * 512 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
-        auto read_tr = [&](const char* base, int ks, int unit) {
+        // TN: 512-byte rows.  One operand fragment (16 features x 32 k) is two transpose reads, each 16 k-rows x 32
+        // bytes: lane (i = lane%16, g = lane/16) addresses k-row 4g + i/4 (+16 for the second read) at features
+        // (i%4)*4 of the 16-feature unit and receives feature i at k-rows 4g..4g+3.  The 32 lanes served together
+        // touch 8 k-rows, so the 32-byte unit index is XORed with row%8.  Both operands use the same k order, so the
+        // contraction is unchanged.
+        const int tr_x = 4 * ((lane >> 4) & 1) + ((lane >> 2) & 3);
+        const int tr_base = (4 * (lane >> 4) + ((lane & 15) >> 2)) * 512 + (lane & 3) * 8;
+        auto read_tr = [&](const char* base, int unit) {
             typedef short s16x4_t __attribute__((ext_vector_type(4)));
             typedef short s16x8_t __attribute__((ext_vector_type(8)));
             typedef __attribute__((address_space(3))) s16x4_t* lds4_t;
-            const char* q = base + ks * (16 * 512) + tr_base + ((unit ^ tr_x) << 6);
+            const char* q = base + tr_base + ((unit ^ tr_x) << 5);
             const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)q);
-            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(q + 8 * 512));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(q + 16 * 512));
             const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             return __builtin_bit_cast(bf16x8_t, v);
         };
-        auto load_frags = [&](int stage, int ks, bf16x8_t (&fa)[TM], bf16x8_t (&fb)[TN]) {
+        // fragments of 32-deep k step `ks` of a stage: HA of this wavefront's TM16 row units (half h), all TN16 column units
+        auto load_a = [&](int stage, int ks, int h, bf16x8_t (&fa)[HA]) {
             const char* a_base = smem + stage * STAGE;
-            const char* b_base = a_base + HALF;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                if constexpr (TNF) fa[i] = read_tr(a_base, ks, wm * TM + i);
-                else fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off64(wm * (TM * 32) + i * 32 + frag_row, ks * 2 + frag_half));
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                if constexpr (TNF) fb[j] = read_tr(b_base, ks, wn * TN + j);
-                else fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off64(wn * (TN * 32) + j * 32 + frag_row, ks * 2 + frag_half));
+            for (int i = 0; i < HA; ++i) {
+                if constexpr (TNF) fa[i] = read_tr(a_base, wm * TM16 + h * HA + i);
+                else fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off64(wm * (TM * 32) + (h * HA + i) * 16 + frag_row, ks * 4 + frag_grp));
             }
         };
-        auto mma = [&](const bf16x8_t (&fa)[TM], const bf16x8_t (&fb)[TN]) {
+        auto load_b = [&](int stage, int ks, bf16x8_t (&fb)[TN16]) {
+            const char* b_base = smem + stage * STAGE + HALF;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    // operands swapped on purpose: the accumulator tile is C^T (rows = n, columns = m), so a
-                    // lane holds 4 CONSECUTIVE n per register group and the epilogue stages with 16-byte writes
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN16; ++j) {
+                if constexpr (TNF) fb[j] = read_tr(b_base, wn * TN16 + j);
+                else fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off64(wn * (TN * 32) + j * 16 + frag_row, ks * 4 + frag_grp));
+            }
         };
-        // Software pipeline: the fragments of one 16-deep k step are read from LDS while the MFMAs of the previous
-        // step run, ACROSS the tile boundary too, so that no wavefront waits on LDS latency right after the barrier
+        // One half step: HA x TN16 MFMAs on row units h*HA.., with transfers [s0, s0 + cnt) of K tile `tile` handed
+        // out evenly between them.  Operands swapped on purpose: the accumulator block is C^T (rows = n, columns =
+        // m), so a lane holds 4 CONSECUTIVE n per block and the epilogue stages with 16-byte writes.
+        auto mma_dma = [&](int h, const bf16x8_t (&fa)[HA], const bf16x8_t (&fb)[TN16], int tile, int stage, int s0, int cnt) {
+            int done = 0;
+#pragma unroll
+            for (int i = 0; i < HA; ++i)
+#pragma unroll
+                for (int j = 0; j < TN16; ++j) {
+                    const int q = i * TN16 + j;
+                    if (done < cnt && q == done * (HA * TN16) / cnt) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        issue_one(tile, stage, s0 + done);
+                        __builtin_amdgcn_sched_barrier(0);
+                        ++done;
+                    }
+                    acc[h * HA + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[h * HA + i][j], 0, 0, 0);
+                }
+        };
+        // Software pipeline: the fragments of the next half step are read from LDS while the MFMAs of the current
+        // one run, ACROSS the tile boundary too, so that no wavefront waits on LDS latency right after the barrier
         // (all 8 wavefronts leave it together, so nobody would be left to cover for the others).
-        bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+        bf16x8_t fax[HA], fay[HA], fbx[TN16], fby[TN16];
+        constexpr int NTR = 2 * LPW;                                // transfers per K tile and wavefront
         if constexpr (TNF) {
+            // one 32-deep k step per tile, two half steps; transfers of tile tl+3: TN_PRE before the barrier of
+            // iteration tl, the rest after it
             issue(t_begin, 0);
             issue(t_begin + 1, 1);
             issue(t_begin + 2, 2);
-            __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * LPW));         // tile t_begin: at most the two newest tiles outstanding
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * NTR));         // tile t_begin: at most the two newest tiles outstanding
             __builtin_amdgcn_s_barrier();
-            load_frags(0, 0, fa0, fb0);
-            for (int tl = t_begin; tl < t_end; ++tl) {
+            load_b(0, 0, fbx);
+            load_a(0, 0, 0, fax);
+            auto tn_iter = [&](int tl, bf16x8_t (&fb_cur)[TN16], bf16x8_t (&fb_next)[TN16]) {
                 const int st_ = (tl - t_begin) & (NS - 1);
-                // stage (tl-1)%4 is free: every wavefront finished reading it before the barrier it has just passed
-                issue(tl + 3, (st_ + 3) & (NS - 1));
-                load_frags(st_, 1, fa1, fb1);
+                // stage (tl-1)%4 is free: every wavefront finished reading it before the barrier it has passed last
+                load_a(st_, 0, 1, fay);
                 __builtin_amdgcn_sched_barrier(0);
-                mma(fa0, fb0);
+                mma_dma(0, fax, fb_cur, tl + 3, (st_ + 3) & (NS - 1), 0, TN_PRE);
                 __builtin_amdgcn_sched_barrier(0);
-                // tile tl+1: this wavefront's part has landed (two newest tiles outstanding), its LDS reads are done ...
-                __builtin_amdgcn_s_waitcnt(0x0070 | (4 * LPW));     // vmcnt(4*LPW) lgkmcnt(0)
+                // tile tl+1: this wavefront's part has landed (tile tl+2 and the new transfers outstanding), its LDS
+                // reads are done ...
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(NTR + TN_PRE) & 0xF0FF);   // vmcnt(NTR + TN_PRE) lgkmcnt(0)
                 __builtin_amdgcn_s_barrier();                       // ... and everyone's
-                load_frags((st_ + 1) & (NS - 1), 0, fa0, fb0);      // past the last tile: a stale but valid stage, unused
+                load_b((st_ + 1) & (NS - 1), 0, fb_next);           // past the last tile: a stale but valid stage, unused
+                load_a((st_ + 1) & (NS - 1), 0, 0, fax);
                 __builtin_amdgcn_sched_barrier(0);
-                mma(fa1, fb1);
+                mma_dma(1, fay, fb_cur, tl + 3, (st_ + 3) & (NS - 1), TN_PRE, NTR - TN_PRE);
                 __builtin_amdgcn_sched_barrier(0);
+            };
+            int tl = t_begin;
+            for (; tl + 1 < t_end; tl += 2) {
+                tn_iter(tl, fbx, fby);
+                tn_iter(tl + 1, fby, fbx);
             }
+            if (tl < t_end) tn_iter(tl, fbx, fby);
         } else {
-            // two 64 KB stages: tile tl+1 is in flight while the four 16-deep steps of tile tl run; one barrier per tile
+            // two 64 KB stages, two 32-deep k steps = four half steps per tile, one barrier per tile.  Transfers of
+            // tile tl+1 ride on the four half steps between two barriers: NT_G0 on the one right after the barrier
+            // (the last half step of tile tl-1), then NT_G1, NT_G2, the rest
+            static_assert(NT_G0 + NT_G1 + NT_G2 <= NTR, "more transfers scheduled than a tile has");
             issue(t_begin, 0);
             __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0)
             __builtin_amdgcn_s_barrier();
-            load_frags(0, 0, fa0, fb0);
+#pragma unroll
+            for (int s_ = 0; s_ < NT_G0; ++s_) issue_one(t_begin + 1, 1, s_);
+            load_b(0, 0, fbx);
+            load_a(0, 0, 0, fax);
             for (int tl = t_begin; tl < t_end; ++tl) {
                 const int st_ = (tl - t_begin) & 1;
-                // the other stage is free: every wavefront finished reading it before the barrier it has just passed
-                issue(tl + 1, st_ ^ 1);
-                load_frags(st_, 1, fa1, fb1);
+                load_a(st_, 0, 1, fay);
                 __builtin_amdgcn_sched_barrier(0);
-                mma(fa0, fb0);
+                mma_dma(0, fax, fbx, tl + 1, st_ ^ 1, NT_G0, NT_G1);
                 __builtin_amdgcn_sched_barrier(0);
-                load_frags(st_, 2, fa0, fb0);
+                load_b(st_, 1, fby);
+                load_a(st_, 1, 0, fax);
                 __builtin_amdgcn_sched_barrier(0);
-                mma(fa1, fb1);
+                mma_dma(1, fay, fbx, tl + 1, st_ ^ 1, NT_G0 + NT_G1, NT_G2);
                 __builtin_amdgcn_sched_barrier(0);
-                load_frags(st_, 3, fa1, fb1);
+                load_a(st_, 1, 1, fay);
                 __builtin_amdgcn_sched_barrier(0);
-                mma(fa0, fb0);
+                mma_dma(0, fax, fby, tl + 1, st_ ^ 1, NT_G0 + NT_G1 + NT_G2, NTR - NT_G0 - NT_G1 - NT_G2);
                 __builtin_amdgcn_sched_barrier(0);
                 __builtin_amdgcn_s_waitcnt(0x0070);                 // vmcnt(0) lgkmcnt(0): tile tl+1 landed, reads of tile tl done
                 __builtin_amdgcn_s_barrier();
-                load_frags(st_ ^ 1, 0, fa0, fb0);                   // past the last tile: a reloaded copy of it, unused
+                // this stage is free from here on: tile tl+2 starts to arrive in it
+                load_b(st_ ^ 1, 0, fbx);                            // past the last tile: a reloaded copy of it, unused
+                load_a(st_ ^ 1, 0, 0, fax);
                 __builtin_amdgcn_sched_barrier(0);
-                mma(fa1, fb1);
+                mma_dma(1, fay, fby, tl + 2, st_, 0, NT_G0);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -745,7 +802,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
 
     // ---- epilogue through LDS: per wavefront a [32][STG_LD] fp32 staging block
     float* stage = reinterpret_cast<float*>(smem) + wave * (32 * STG_LD);
-    const int col_l = lane & 31, half = lane >> 5;
     constexpr int LPR = TN * 4;                    // lanes per staged row (8 columns each)
     const int rd_row = lane / LPR, rd_col = (lane % LPR) * 8;
     constexpr int NPSS = 32 / (64 / LPR);          // staged rows each lane finishes per pass
@@ -770,11 +826,13 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
         if (epilogue_reads<EPI>() && direct && !PRE_ALL) prefetch_pass(i);
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)     // lane = row m (col_l); registers 4q..4q+3 = columns 8q + 4*half + 0..3
-                *reinterpret_cast<float4*>(stage + col_l * STG_LD + j * 32 + 8 * q + 4 * half) =
-                    make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            for (int j = 0; j < TN16; ++j) {    // lane = row m (lane%16 of block 2i+i2); its 4 registers = columns 4*(lane/16) + 0..3
+                const f32x4_t a4 = acc[2 * i + i2][j];
+                *reinterpret_cast<float4*>(stage + (i2 * 16 + (lane & 15)) * STG_LD + j * 16 + 4 * (lane >> 4)) =
+                    make_float4(a4[0], a4[1], a4[2], a4[3]);
+            }
         __syncthreads();
 #pragma unroll
         for (int pss = 0; pss < NPSS; ++pss) {
