@@ -42,6 +42,13 @@ template <> struct Vec8<float> {
         *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
         *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
     }
+    // streaming store: the line is not kept in L2 (outputs far larger than the cache would only evict operands
+    // that other work-groups are about to read again)
+    static __device__ __forceinline__ void store_nt(float* p, const float (&v)[8]) {
+        const f32x4_t a = {v[0], v[1], v[2], v[3]}, b = {v[4], v[5], v[6], v[7]};
+        __builtin_nontemporal_store(a, reinterpret_cast<f32x4_t*>(p));
+        __builtin_nontemporal_store(b, reinterpret_cast<f32x4_t*>(p + 4));
+    }
 };
 template <> struct Vec8<bf16_t> {
     static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
@@ -54,6 +61,12 @@ template <> struct Vec8<bf16_t> {
 #pragma unroll
         for (int i = 0; i < 8; ++i) a[i] = (bf16_t)v[i];
         *reinterpret_cast<bf16x8_t*>(p) = a;
+    }
+    static __device__ __forceinline__ void store_nt(bf16_t* p, const float (&v)[8]) {
+        bf16x8_t a;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] = (bf16_t)v[i];
+        __builtin_nontemporal_store(a, reinterpret_cast<bf16x8_t*>(p));
     }
 };
 

@@ -80,14 +80,14 @@ __device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], 
         for (int j = 0; j < 8; ++j) acc[j] += b[j];
     }
     if (EPI == DS_EPI_NONE) {
-        Vec8<T>::store(C + off, acc);
+        Vec8<T>::store_nt(C + off, acc);
     } else if (EPI == DS_EPI_GELU) {
         // round the pre-activation to storage precision first, so that forward and backward see the same z
         float z[8], a[8];
-        Vec8<T>::store(C + off, acc);
+        Vec8<T>::store_nt(C + off, acc);
 #pragma unroll
         for (int j = 0; j < 8; ++j) { z[j] = to_f32(from_f32<T>(acc[j])); a[j] = gelu_f(z[j]); }
-        Vec8<T>::store(reinterpret_cast<T*>(p.C2) + off, a);
+        Vec8<T>::store_nt(reinterpret_cast<T*>(p.C2) + off, a);
     } else if (EPI == DS_EPI_RESID) {
         if (pre) {
 #pragma unroll
@@ -101,7 +101,7 @@ __device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], 
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] += r[j];
         }
-        Vec8<T>::store(C + off, acc);
+        Vec8<T>::store_nt(C + off, acc);
     } else if (EPI == DS_EPI_DGELU) {
         float z[8];
         if (pre) {
@@ -112,11 +112,11 @@ __device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], 
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] *= gelu_grad_f(z[j]);
-        Vec8<T>::store(C + off, acc);
+        Vec8<T>::store_nt(C + off, acc);
     } else if (EPI == DS_EPI_GATE) {
         // acc = u Wu (stored); C2 = GELU(R) * acc with R = u Wg
         float zg[8], a[8];
-        Vec8<T>::store(C + off, acc);
+        Vec8<T>::store_nt(C + off, acc);
         if (pre) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) zg[j] = to_f32(pre->r[j]);
@@ -125,7 +125,7 @@ __device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], 
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) a[j] = gelu_f(zg[j]) * to_f32(from_f32<T>(acc[j]));
-        Vec8<T>::store(reinterpret_cast<T*>(p.C2) + off, a);
+        Vec8<T>::store_nt(reinterpret_cast<T*>(p.C2) + off, a);
     } else if (EPI == DS_EPI_DGATE) {
         // acc = da; R = zg, R2 = zu; C = dzg = da * zu * GELU'(zg); C2 = dzu = da * GELU(zg)
         float zg[8], zu[8], o1[8], o2[8];
@@ -141,7 +141,7 @@ __device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], 
             o1[j] = acc[j] * zu[j] * gelu_grad_f(zg[j]);
             o2[j] = acc[j] * gelu_f(zg[j]);
         }
-        Vec8<T>::store(C + off, o1);
+        Vec8<T>::store_nt(C + off, o1);
         Vec8<T>::store(reinterpret_cast<T*>(p.C2) + off, o2);
     }
 }
