@@ -112,6 +112,15 @@ __device__ __forceinline__ void lds_dma16(const void* gptr, const void* lds_ptr)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_addr) : "memory", "m0");
 }
 
+// Orders the LDS writes of a wavefront's lanes before later LDS reads by other lanes of the SAME wavefront.  LDS
+// operations of one wavefront execute in order, so no instruction is needed: this only stops the compiler from
+// moving accesses across the point.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // s_waitcnt immediate "at most n vector-memory operations outstanding" (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
 // expcnt 6:4 and lgkmcnt 11:8 left at their maxima, i.e. not waited for)
 constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }

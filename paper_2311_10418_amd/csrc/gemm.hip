@@ -511,12 +511,15 @@ constexpr int NT_DK = 32, NT_NS = 4, NT_HALF = 256 * NT_DK * 2, NT_STAGE = 2 * N
 #define TN_PRE 2
 #endif
 
-// tile number -> tile coordinates: groups of 8 tile rows, column-major inside a group
+// tile number -> tile coordinates: groups of NT_GROUP tile rows, column-major inside a group
+#ifndef NT_GROUP
+#define NT_GROUP 4
+#endif
 __host__ __device__ __forceinline__ void nt_tile_coords(int logical, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
-    const int group_sz = 8 * tiles_n;
+    const int group_sz = NT_GROUP * tiles_n;
     const int group = logical / group_sz;
-    const int first_m = group * 8;
-    const int gs = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
+    const int first_m = group * NT_GROUP;
+    const int gs = (tiles_m - first_m) < NT_GROUP ? (tiles_m - first_m) : NT_GROUP;
     const int in_group = logical - group * group_sz;
     tile_m = first_m + in_group % gs;
     tile_n = in_group / gs;
@@ -824,7 +827,8 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         if (epilogue_reads<EPI>() && direct && !PRE_ALL) prefetch_pass(i);
-        __syncthreads();
+        wave_lds_sync();            // the staging block is private to the wavefront: no work-group barrier (which would
+                                    // also wait for the global stores of the previous pass to be acknowledged)
 #pragma unroll
         for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
@@ -833,7 +837,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                 *reinterpret_cast<float4*>(stage + (i2 * 16 + (lane & 15)) * STG_LD + j * 16 + 4 * (lane >> 4)) =
                     make_float4(a4[0], a4[1], a4[2], a4[3]);
             }
-        __syncthreads();
+        wave_lds_sync();
 #pragma unroll
         for (int pss = 0; pss < NPSS; ++pss) {
             const int row = pss * (64 / LPR) + rd_row;
