@@ -607,20 +607,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-    float cs[TN16];
-#pragma unroll
-    for (int j = 0; j < TN16; ++j) cs[j] = 0.f;
-    // the 16 column blocks of a tile are dealt out over the tile rows (block b to tile row b % cs_t), so that no
-    // work-group carries much more than the others
-    const int cs_t = tiles_m < WN * TN16 ? tiles_m : WN * TN16;
-    bool cs_on[TN16];
-    bool do_cs = false;
-#pragma unroll
-    for (int j = 0; j < TN16; ++j) {
-        cs_on[j] = TNF && EPI == DS_EPI_ACC32 && p.colsum_ws != nullptr && wm == 0 && (wn * TN16 + j) % cs_t == tile_m;
-        do_cs = do_cs || cs_on[j];
-    }
-
     if (t_begin < t_end) {
         uint32_t offA[LPW], offB[LPW];
         int krow[LPW];                                              // TN: k-row of this lane's chunk within a tile
@@ -744,20 +730,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
         // (all 8 wavefronts leave it together, so nobody would be left to cover for the others).
         bf16x8_t fax[HA], fay[HA], fbx[TN16], fby[TN16];
         constexpr int NTR = 2 * LPW;                                // transfers per K tile and wavefront
-        // bias gradient riding on a weight gradient: a wavefront of the tile's top half adds up the B fragments of its
-        // share of the column blocks (lane = column n, 8 k each) on the vector ALU while the partner wavefront of
-        // the SIMD keeps the matrix pipe busy
-        auto cs_add = [&](const bf16x8_t (&fb)[TN16]) {
-            typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-#pragma unroll
-            for (int j = 0; j < TN16; ++j) {
-                if (!cs_on[j]) continue;
-                const u32x4_t u = __builtin_bit_cast(u32x4_t, fb[j]);
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    cs[j] += __builtin_bit_cast(float, u[q] << 16) + __builtin_bit_cast(float, u[q] & 0xffff0000u);
-            }
-        };
         if constexpr (TNF) {
             // one 32-deep k step per tile, two half steps; transfers of tile tl+3: TN_PRE before the barrier of
             // iteration tl, the rest after it
@@ -772,7 +744,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                 const int st_ = (tl - t_begin) & (NS - 1);
                 // stage (tl-1)%4 is free: every wavefront finished reading it before the barrier it has passed last
                 load_a(st_, 0, 1, fay);
-                if (do_cs) cs_add(fb_cur);
                 __builtin_amdgcn_sched_barrier(0);
                 mma_dma(0, fax, fb_cur, tl + 3, (st_ + 3) & (NS - 1), 0, TN_PRE);
                 __builtin_amdgcn_sched_barrier(0);
@@ -833,16 +804,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
         // see transfers issued by lds_dma16)
         __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0) lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
-    }
-
-    if (do_cs) {        // lanes 16g + c hold the sums of k group g for column c: fold the four groups, lanes 0..15 store
-#pragma unroll
-        for (int j = 0; j < TN16; ++j) {
-            float v = cs[j];
-            v += __shfl_xor(v, 16, 64);
-            v += __shfl_xor(v, 32, 64);
-            if (cs_on[j] && lane < 16) p.colsum_ws[(size_t)split * N + n0 + wn * (TN * 32) + j * 16 + lane] = v;
-        }
     }
 
     // ---- epilogue through LDS: per wavefront a [32][STG_LD] fp32 staging block
@@ -945,23 +906,6 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(int M, int N, int sp
             for (int j = 0; j < 8; ++j) v[j] += w[j];
         }
         epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
-        if (EPI == DS_EPI_ACC32 && m == 0 && p.colsum_ws) {        // the bias gradient's partial sums, same fixed order
-            float c[8];
-            Vec8<float>::load(p.colsum_ws + n, c);
-            for (int s = 1; s < splits; ++s) {
-                float w[8];
-                Vec8<float>::load(p.colsum_ws + (size_t)s * N + n, w);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) c[j] += w[j];
-            }
-            if (p.accumulate) {
-                float old[8];
-                Vec8<float>::load(p.colsum + n, old);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) c[j] += old[j];
-            }
-            Vec8<float>::store(p.colsum + n, c);
-        }
     }
 }
 
@@ -1060,12 +1004,7 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
     const int nt = TNF ? (K + NT_DK - 1) / NT_DK : K / 64;      // K tiles as the kernel counts them
     const int tiles = tiles_m * tiles_n;
     int splits = 1;
-    // the bias gradient's per-split sums live in the last 16 * N floats of the workspace
-    const size_t cs_floats = (TNF && p.colsum) ? (size_t)16 * N : 0;
-    if (cs_floats >= split_ws_floats) split_ws = nullptr;
-    if (EPI == DS_EPI_ACC32 && split_ws) splits = choose_splits(tiles, nt, M, N, split_ws_floats - cs_floats);
-    GemmEpi q = p;
-    q.colsum_ws = (cs_floats && splits > 1) ? split_ws + (split_ws_floats - cs_floats) : nullptr;
+    if (EPI == DS_EPI_ACC32 && split_ws) splits = choose_splits(tiles, nt, M, N, split_ws_floats);
     // tail split-K: the tiles beyond the last whole round over the compute units share that round; a launch with
     // fewer tiles than compute units (small micro-batches) is all tail, so that the K loop is spread over the chip
     int n_main = tiles, tail_splits = 1;
@@ -1086,32 +1025,25 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
     }
     const int total = splits > 1 ? tiles * splits : n_main + (tiles - n_main) * tail_splits;
     hipLaunchKernelGGL(kern, dim3(total), dim3(WM * WN * 64), smem, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C,
-                       tiles_m, tiles_n, splits, n_main, tail_splits, split_ws, q);
+                       tiles_m, tiles_n, splits, n_main, tail_splits, split_ws, p);
     DS_LAUNCH_CHECK();
     if (splits > 1) {
         long long items = (long long)M * (N / 8);
         long long g = (items + 255) / 256;
         if (g > 8192) g = 8192;
-        hipLaunchKernelGGL(splitk_finish_kernel<EPI>, dim3((int)g), dim3(256), 0, st, M, N, splits, split_ws, (bf16_t*)C, q);
+        hipLaunchKernelGGL(splitk_finish_kernel<EPI>, dim3((int)g), dim3(256), 0, st, M, N, splits, split_ws, (bf16_t*)C, p);
         DS_LAUNCH_CHECK();
     } else if (tail_splits > 1) {
         hipLaunchKernelGGL(tail_finish_kernel<EPI>, dim3(8, tiles - n_main), dim3(256), 0, st, M, N, tiles_m, tiles_n, n_main,
                            tail_splits, split_ws, (bf16_t*)C, p);
         DS_LAUNCH_CHECK();
     }
-    if (p.colsum && !q.colsum_ws)        // not folded into the kernel (unsplit launch): the stand-alone column sums
-        return ds_colsum(DS_DTYPE_BF16, K, N, B, p.colsum, p.colsum_partial, p.accumulate, st);
     return DS_OK;
 }
 
 template <int EPI>
 ds_status dispatch_epi(int dtype, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C,
                        const GemmEpi& p, bool force_generic, float* split_ws, size_t split_ws_floats, hipStream_t st) {
-    // paths that do not fold the bias gradient into the GEMM run the stand-alone column sums after it
-    auto then_colsum = [&](ds_status r) {
-        if (r != DS_OK || !p.colsum) return r;
-        return ds_colsum(dtype, K, N, B, p.colsum, p.colsum_partial, p.accumulate, st);
-    };
     if (dtype == DS_DTYPE_BF16 && !force_generic) {
         const bool ok_n = N % BN == 0;
         const bool ok_a = ta ? (M % BM == 0) : (K % BK == 0);
@@ -1122,11 +1054,11 @@ ds_status dispatch_epi(int dtype, int ta, int tb, int M, int N, int K, const voi
             if (!ta && tb) return launch_nt<EPI, false>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
             if constexpr (EPI == DS_EPI_ACC32)
                 if (ta && !tb) return launch_nt<EPI, true>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
-            if (ta && !tb) return then_colsum(launch_mfma<1, 0, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st));
+            if (ta && !tb) return launch_mfma<1, 0, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
         }
     }
-    if (dtype == DS_DTYPE_BF16) return then_colsum(launch_generic<bf16_t, EPI>(ta, tb, M, N, K, A, B, C, p, st));
-    return then_colsum(launch_generic<float, EPI>(ta, tb, M, N, K, A, B, C, p, st));
+    if (dtype == DS_DTYPE_BF16) return launch_generic<bf16_t, EPI>(ta, tb, M, N, K, A, B, C, p, st);
+    return launch_generic<float, EPI>(ta, tb, M, N, K, A, B, C, p, st);
 }
 
 }  // namespace
@@ -1138,7 +1070,6 @@ ds_status launch_gemm(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int32_t 
     if (M <= 0 || N <= 0 || K <= 0 || !A || !B || !C) return DS_EINVAL;
     if (N % 8) return DS_EINVAL;
     if (dtype != DS_DTYPE_F32 && dtype != DS_DTYPE_BF16) return DS_EINVAL;
-    if (p.colsum && (epilogue != DS_EPI_ACC32 || !ta || tb || !p.colsum_partial)) return DS_EINVAL;
     switch (epilogue) {
     case DS_EPI_NONE: return dispatch_epi<DS_EPI_NONE>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
     case DS_EPI_GELU:

@@ -9,12 +9,6 @@ struct GemmEpi {
     void* C2;                  // second output
     const int32_t* row_valid;  // rows with a negative entry are written as zeros (RESID epilogue)
     int accumulate;            // ACC32: add to C instead of overwriting
-    // ACC32 with A = [K,M], B = [K,N] (a weight gradient): when colsum is set, it also receives the column sums of B
-    // over K (the gradient of the bias that goes with the weight), float32 [N], added to when `accumulate`.
-    // colsum_partial: float32 scratch of ds_colsum's size, used when the sums are not folded into the GEMM kernel.
-    float* colsum;
-    float* colsum_partial;
-    float* colsum_ws;          // set by the launcher: per-split partial sums [splits][N] inside the split-K workspace
 };
 
 ds_status launch_gemm(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int32_t N, int32_t K, const void* A, const void* B,

@@ -175,8 +175,7 @@ void carve(ds_stage* s) {
     }
     const size_t partial_floats = std::max<size_t>((size_t)ds_norm_bwd_scratch_floats(1, (int)d), (size_t)2048 * 1024);
     s->partial = f32(partial_floats);
-    // 4 split-K partial sums of the largest weight gradient, plus the bias gradient's 16 rows of per-split sums
-    s->split_ws_floats = 4 * std::max(d * 3 * d, d * F) + 16 * std::max(3 * d, F);
+    s->split_ws_floats = 4 * std::max(d * 3 * d, d * F);
     s->split_ws = f32(s->split_ws_floats);
     s->main.row_valid = (int32_t*)ar.take(R * 4);
     s->main.seq_row = (int32_t*)ar.take(S * 4);
@@ -260,10 +259,9 @@ struct Ops {
     bool nt;
 
     ds_status gemm_raw(int cat, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C, int epi,
-                       const void* bias, const void* R, const void* R2, void* C2, const int32_t* row_valid, int acc,
-                       float* colsum = nullptr) {
+                       const void* bias, const void* R, const void* R2, void* C2, const int32_t* row_valid, int acc) {
         return timed(s, cat, st, [&] {
-            GemmEpi p{bias, R, R2, C2, row_valid, acc, colsum, colsum ? s->partial : nullptr, nullptr};
+            GemmEpi p{bias, R, R2, C2, row_valid, acc};
             s->launches++;
             return launch_gemm(dt, ta, tb, M, N, K, A, B, C, epi, p, false, s->split_ws, s->split_ws_floats, st);
         });
@@ -280,10 +278,10 @@ struct Ops {
                     const void* R2, void* C2) {
         return gemm_raw(DS_PROF_GEMM_DGRAD, 0, 1, sm.R, K, N, dY, W, C, epi, nullptr, R, R2, C2, nullptr, 0);
     }
-    // dW[K,N] (+)= X[rows,K]^T dY[rows,N]; db[N] (+)= column sums of dY when the projection has a bias
-    ds_status wgrad(const Stream& sm, int K, int N, const void* X, const void* dY, void* dW, void* db = nullptr) {
+    // dW[K,N] (+)= X[rows,K]^T dY[rows,N]
+    ds_status wgrad(const Stream& sm, int K, int N, const void* X, const void* dY, void* dW) {
         return gemm_raw(DS_PROF_GEMM_WGRAD, 1, 0, K, N, sm.R, X, dY, dW, DS_EPI_ACC32, nullptr, nullptr, nullptr, nullptr,
-                        nullptr, accumulate, (float*)db);
+                        nullptr, accumulate);
     }
     ds_status weight_t(int K, int N, const void* W, void* Wt) {      // [K][N] -> [N][K]
         s->launches++;
@@ -417,16 +415,20 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         const void* xl_in = (l == 0) ? x0 : s->gpt[l - 1].xout;
         void* dx_in = (l == 0) ? io->grad_in : pp[flip];
         // MLP
-        DS_TRY(op.wgrad(sm, F, d, b.a, dy, g[l].w_2, g[l].b_2));
+        DS_TRY(op.wgrad(sm, F, d, b.a, dy, g[l].w_2));
+        DS_TRY(op.colsum(sm, d, dy, g[l].b_2));
         DS_TRY(op.dgrad(sm, F, d, dy, w[l].w_2, s->dz, DS_EPI_DGELU, b.z, nullptr, nullptr));
-        DS_TRY(op.wgrad(sm, d, F, b.u2, s->dz, g[l].w_1, g[l].b_1));
+        DS_TRY(op.wgrad(sm, d, F, b.u2, s->dz, g[l].w_1));
+        DS_TRY(op.colsum(sm, F, s->dz, g[l].b_1));
         DS_TRY(op.dgrad(sm, d, F, s->dz, w[l].w_1, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr));
         DS_TRY(op.norm_bwd(sm, 0, s->du, b.x1, w[l].ln2_g, b.stats2, dy, s->dx1, g[l].ln2_g, g[l].ln2_b));
         // attention
-        DS_TRY(op.wgrad(sm, d, d, b.o, s->dx1, g[l].w_o, g[l].b_o));
+        DS_TRY(op.wgrad(sm, d, d, b.o, s->dx1, g[l].w_o));
+        DS_TRY(op.colsum(sm, d, s->dx1, g[l].b_o));
         DS_TRY(op.dgrad(sm, d, d, s->dx1, w[l].w_o, s->d_o, DS_EPI_NONE, nullptr, nullptr, nullptr));
         DS_TRY(op.self_bwd(sm, 1, b.qkv, b.o, s->d_o, b.lse, s->dqkv));
-        DS_TRY(op.wgrad(sm, d, 3 * d, b.u1, s->dqkv, g[l].w_qkv, g[l].b_qkv));
+        DS_TRY(op.wgrad(sm, d, 3 * d, b.u1, s->dqkv, g[l].w_qkv));
+        DS_TRY(op.colsum(sm, 3 * d, s->dqkv, g[l].b_qkv));
         DS_TRY(op.dgrad(sm, d, 3 * d, s->dqkv, w[l].w_qkv, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr));
         DS_TRY(op.norm_bwd(sm, 0, s->du, xl_in, w[l].ln1_g, b.stats1, s->dx1, dx_in, g[l].ln1_g, g[l].ln1_b));
         dy = dx_in;
