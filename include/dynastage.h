@@ -264,6 +264,35 @@ ds_status ds_comm_plan(int32_t n_stages, int32_t n_mb, const int32_t* order_mb, 
                        int32_t* stream_code, int32_t* stream_mb, int32_t* stream_len);
 
 /* ------------------------------------------------------------------------------------------
+ * Dynamic recomputation (section "Implementation", paragraph "Dynamic recomputation"; host only).
+ * The peak memory of an iteration varies with its micro-batches, so the recomputation scheme is
+ * chosen per iteration: micro-batch construction and scheduling are repeated once per scheme, each
+ * under that scheme's cost model, and the scheme with the least overhead that stays in memory wins.
+ */
+typedef struct {
+    ds_cost_model cm;           /* t(b, L) of a micro-batch's forward + backward on one stage, INCLUDING what the scheme recomputes */
+    int64_t act_per_row;        /* > 0: units of activation memory one padded row (main + target stream) holds on a
+                                   stage between the micro-batch's forward and its backward */
+    int64_t fwd_num, fwd_den;   /* the forward takes t * fwd_num / fwd_den (integer division), the backward the rest */
+} ds_recompute_scheme;
+
+/*
+ * ds_plan_recompute — for every scheme r: dp_plan under schemes[r].cm with the token cap
+ * (mem_limit - 1) / act_per_row (one micro-batch alone must satisfy Alg. 1's  act < limit); then
+ * ds_schedule_adaptive with act = act_per_row * padded rows of the micro-batch and the same
+ * mem_limit on each of the num_stages (alike) stages; then ds_schedule_simulate with the times
+ * above.  A scheme is feasible if all three succeed.  *chosen = the feasible scheme with the
+ * smallest makespan (equal: the one listed first; list schemes in ascending order of
+ * recomputation); *out = its layout (caller frees).  makespan / peak: HOST int64[n_schemes] or
+ * NULL, -1 for an infeasible scheme (peak = largest memory any stage holds, < mem_limit).
+ * Errors: DS_EINVAL, DS_EINFEASIBLE (no scheme fits), DS_EOVERFLOW, DS_ENOMEM.
+ */
+ds_status ds_plan_recompute(const int32_t* len, const int32_t* len_tgt, int32_t n,
+                            const ds_recompute_scheme* schemes, int32_t n_schemes, int64_t mem_limit,
+                            int32_t num_stages, int32_t* chosen, ds_layout** out, int64_t* makespan,
+                            int64_t* peak);
+
+/* ------------------------------------------------------------------------------------------
  * Stage: the transformer layers of one pipeline stage (what the ForwardPass / BackwardPass
  * pipeline instructions execute, section "Overview", paragraph "Execution plans").
  */

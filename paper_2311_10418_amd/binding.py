@@ -24,7 +24,7 @@ PROF_KINDS = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "n
 _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOMEM", -4: "DS_EOVERFLOW",
                  -5: "DS_EHIP", -6: "DS_ELAYOUT"}
 
-EXPORTS = ["dp_plan", "dp_plan_sampled", "dp_plan_replicas", "ds_assign_replicas", "ds_cost_table_build", "ds_schedule_adaptive",
+EXPORTS = ["dp_plan", "dp_plan_sampled", "dp_plan_replicas", "ds_plan_recompute", "ds_assign_replicas", "ds_cost_table_build", "ds_schedule_adaptive",
            "ds_schedule_1f1b", "ds_schedule_simulate", "ds_comm_plan", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "stage_fwd_bwd",
            "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_attention_fwd",
@@ -41,6 +41,10 @@ class DsError(RuntimeError):
 class ds_cost_model(C.Structure):
     _fields_ = [("kind", C.c_int32), ("fixed", C.c_int64), ("lin", C.c_int64),
                 ("table", C.c_void_p), ("tb", C.c_int32), ("tl", C.c_int32)]
+
+
+class ds_recompute_scheme(C.Structure):
+    _fields_ = [("cm", ds_cost_model), ("act_per_row", C.c_int64), ("fwd_num", C.c_int64), ("fwd_den", C.c_int64)]
 
 
 _I32P = C.POINTER(C.c_int32)
@@ -213,6 +217,30 @@ def dp_plan(lengths, cost_model, mem_cap_tokens, num_stages, lengths_tgt=None):
                        C.c_int64(mem_cap_tokens), C.c_int32(num_stages), C.byref(out))
     _check(rc, "dp_plan")
     return Layout(out)
+
+
+def ds_plan_recompute(lengths, schemes, mem_limit, num_stages, lengths_tgt=None):
+    """schemes: list of (cost_model, act_per_row, fwd_num, fwd_den).
+    -> (chosen index, Layout of the chosen scheme, makespan int64[n_schemes], peak int64[n_schemes]); -1 marks an
+    infeasible scheme."""
+    ln, lt = _np_i32(lengths), _np_i32(lengths_tgt)
+    n = 0 if ln is None else int(ln.shape[0])
+    k = len(schemes)
+    arr = (ds_recompute_scheme * max(k, 1))()
+    keep = []
+    for r, (cm, a, fn, fd) in enumerate(schemes):
+        arr[r].cm.kind, arr[r].cm.fixed, arr[r].cm.lin = cm.kind, cm.fixed, cm.lin
+        arr[r].cm.table, arr[r].cm.tb, arr[r].cm.tl = cm.table, cm.tb, cm.tl
+        keep.append(cm)                                     # the table memory stays alive through the call
+        arr[r].act_per_row, arr[r].fwd_num, arr[r].fwd_den = int(a), int(fn), int(fd)
+    out = C.c_void_p()
+    chosen = C.c_int32(-1)
+    ms = np.zeros(max(k, 1), dtype=np.int64)
+    pk = np.zeros(max(k, 1), dtype=np.int64)
+    rc = lib().ds_plan_recompute(_hp(ln), _hp(lt), C.c_int32(n), arr if k else None, C.c_int32(k), C.c_int64(mem_limit),
+                                 C.c_int32(num_stages), C.byref(chosen), C.byref(out), _hp(ms), _hp(pk))
+    _check(rc, "ds_plan_recompute")
+    return int(chosen.value), Layout(out), ms[:k], pk[:k]
 
 
 def dp_plan_sampled(lengths, cost_model, mem_cap_tokens, num_stages, t_max_interval, lengths_tgt=None):

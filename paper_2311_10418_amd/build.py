@@ -14,7 +14,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdynastage.so")
 
 HIP_SOURCES = ["elementwise.hip", "gemm.hip", "attention_generic.hip", "attention_mfma.hip", "attention_api.hip", "stage.hip"]
-CPP_SOURCES = ["planner.cpp", "schedule.cpp"]
+CPP_SOURCES = ["planner.cpp", "schedule.cpp", "recompute.cpp"]
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
