@@ -308,7 +308,16 @@ typedef struct {
     int32_t max_rows;       /* workspace capacity: padded rows of the main stream */
     int32_t max_rows_tgt;   /* ... of the target stream (0 for GPT) */
     int32_t max_seqs;
+    int32_t recompute;      /* DS_RECOMPUTE_*: what the backward pass recomputes instead of keeping */
 } ds_stage_config;
+
+/* Recomputation (activation checkpointing; section "Implementation", paragraph "Dynamic recomputation").
+ * NONE: every layer keeps what its backward reads (the attention kernels recompute the probabilities from the saved
+ *       log-sum-exp in any case, which is what "selective" recomputation saves elsewhere).
+ * FULL: only each layer's input is kept; the layer's forward is run again right before its backward (except for the
+ *       layer whose forward ran last).  Results are bit-identical to NONE; the workspace holds one layer's
+ *       activations instead of all layers'. */
+enum { DS_RECOMPUTE_NONE = 0, DS_RECOMPUTE_FULL = 1 };
 
 /* Per-layer tensors, DEVICE pointers.  The same structs carry weights (element type = the
  * stage dtype) and weight gradients (always float32).  Matrices are row-major
@@ -354,6 +363,10 @@ ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out);
 void ds_stage_destroy(ds_stage* stage);
 /* Bytes of device workspace the stage holds. */
 int64_t ds_stage_workspace_bytes(const ds_stage* stage);
+/* Bytes of device workspace ds_stage_create would allocate for cfg, without allocating (host only):
+ * what a caller compares with its memory limit when it chooses a recomputation scheme.  -1 for an
+ * invalid configuration. */
+int64_t ds_stage_workspace_need(const ds_stage_config* cfg);
 
 /*
  * stage_fwd_bwd — run forward then backward of every layer of the stage over every

@@ -26,7 +26,7 @@ _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOM
 
 EXPORTS = ["dp_plan", "dp_plan_sampled", "dp_plan_replicas", "ds_plan_recompute", "ds_assign_replicas", "ds_cost_table_build", "ds_schedule_adaptive",
            "ds_schedule_1f1b", "ds_schedule_simulate", "ds_comm_plan", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
-           "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "stage_fwd_bwd",
+           "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "ds_stage_workspace_need", "stage_fwd_bwd",
            "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_attention_fwd",
            "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
            "ds_version"]
@@ -63,7 +63,10 @@ class ds_layout_view(C.Structure):
 class ds_stage_config(C.Structure):
     _fields_ = [("model", C.c_int32), ("dtype", C.c_int32), ("n_layers", C.c_int32), ("n_dec_layers", C.c_int32),
                 ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
-                ("max_rows", C.c_int32), ("max_rows_tgt", C.c_int32), ("max_seqs", C.c_int32)]
+                ("max_rows", C.c_int32), ("max_rows_tgt", C.c_int32), ("max_seqs", C.c_int32), ("recompute", C.c_int32)]
+
+
+DS_RECOMPUTE_NONE, DS_RECOMPUTE_FULL = 0, 1
 
 
 GPT_KEYS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
@@ -107,6 +110,7 @@ def lib():
         _lib = C.CDLL(LIB_PATH)
         _lib.ds_version.restype = C.c_char_p
         _lib.ds_stage_workspace_bytes.restype = C.c_int64
+        _lib.ds_stage_workspace_need.restype = C.c_int64
         _lib.ds_norm_bwd_scratch_floats.restype = C.c_int64
         _lib.ds_attention_scratch_bytes.restype = C.c_int64
         _lib.ds_layout_free.restype = None
@@ -364,11 +368,23 @@ def _layer_array(struct, keys, layers):
     return arr
 
 
+def ds_stage_workspace_need(model, dtype, n_layers, d_model, n_heads, d_ff, max_rows, max_seqs, n_dec_layers=0, max_rows_tgt=0,
+                            recompute=DS_RECOMPUTE_NONE):
+    """Bytes of device workspace a Stage with this configuration allocates (host only; no GPU needed)."""
+    cfg = ds_stage_config(model, dtype, n_layers, n_dec_layers, d_model, n_heads, d_ff, max_rows, max_rows_tgt, max_seqs, recompute)
+    need = lib().ds_stage_workspace_need(C.byref(cfg))
+    if need < 0:
+        raise DsError(-1, "ds_stage_workspace_need")
+    return int(need)
+
+
 class Stage:
     """Owns a ds_stage* (device workspace)."""
 
-    def __init__(self, model, dtype, n_layers, d_model, n_heads, d_ff, max_rows, max_seqs, n_dec_layers=0, max_rows_tgt=0):
-        cfg = ds_stage_config(model, dtype, n_layers, n_dec_layers, d_model, n_heads, d_ff, max_rows, max_rows_tgt, max_seqs)
+    def __init__(self, model, dtype, n_layers, d_model, n_heads, d_ff, max_rows, max_seqs, n_dec_layers=0, max_rows_tgt=0,
+                 recompute=DS_RECOMPUTE_NONE):
+        cfg = ds_stage_config(model, dtype, n_layers, n_dec_layers, d_model, n_heads, d_ff, max_rows, max_rows_tgt, max_seqs,
+                              recompute)
         self.cfg = cfg
         h = C.c_void_p()
         _check(lib().ds_stage_create(C.byref(cfg), C.byref(h)), "ds_stage_create")

@@ -122,13 +122,23 @@ void carve(ds_stage* s) {
     const size_t S = c.max_seqs;
     const bool nt = s->nt_mode;
     auto f32 = [&](size_t n) { return (float*)ar.take(n * 4); };
+    // Full recomputation: only a layer's output (the next layer's input) is kept per layer; what a layer saves for its
+    // backward lives in ONE set of buffers per kind of layer, refilled by re-running the layer's forward right before
+    // its backward.
+    const bool share = c.recompute == DS_RECOMPUTE_FULL;
     if (c.model == DS_MODEL_GPT) {
         s->gpt.resize(c.n_layers);
-        for (GptBufs& b : s->gpt) {
-            b.u1 = ar.take(R * d * es); b.qkv = ar.take(R * 3 * d * es); b.o = ar.take(R * d * es);
-            b.x1 = ar.take(R * d * es); b.u2 = ar.take(R * d * es); b.z = ar.take(R * F * es);
-            b.a = ar.take(R * F * es); b.xout = ar.take(R * d * es);
-            b.stats1 = f32(2 * R); b.stats2 = f32(2 * R); b.lse = f32(R * h);
+        for (size_t li = 0; li < s->gpt.size(); ++li) {
+            GptBufs& b = s->gpt[li];
+            if (share && li > 0) {
+                b = s->gpt[0];
+            } else {
+                b.u1 = ar.take(R * d * es); b.qkv = ar.take(R * 3 * d * es); b.o = ar.take(R * d * es);
+                b.x1 = ar.take(R * d * es); b.u2 = ar.take(R * d * es); b.z = ar.take(R * F * es);
+                b.a = ar.take(R * F * es);
+                b.stats1 = f32(2 * R); b.stats2 = f32(2 * R); b.lse = f32(R * h);
+            }
+            b.xout = ar.take(R * d * es);
             b.wqkv_t = b.wo_t = b.w1_t = b.w2_t = nullptr;
             if (nt) {
                 b.wqkv_t = ar.take(3 * d * d * es); b.wo_t = ar.take(d * d * es);
@@ -136,18 +146,23 @@ void carve(ds_stage* s) {
             }
         }
     } else {
-        auto layer = [&](T5Bufs& b, size_t rows, bool is_dec) {
-            b.u1 = ar.take(rows * d * es); b.qkv = ar.take(rows * 3 * d * es); b.o = ar.take(rows * d * es);
-            b.x1 = ar.take(rows * d * es); b.u2 = ar.take(rows * d * es); b.zg = ar.take(rows * F * es);
-            b.zu = ar.take(rows * F * es); b.a = ar.take(rows * F * es); b.xout = ar.take(rows * d * es);
-            b.stats1 = f32(2 * rows); b.stats2 = f32(2 * rows); b.lse = f32(rows * h);
-            b.uc = b.qc = b.kvc = b.oc = b.x2 = nullptr;
-            b.statsc = b.lsec = nullptr;
-            if (is_dec) {
-                b.uc = ar.take(rows * d * es); b.qc = ar.take(rows * d * es); b.kvc = ar.take(R * 2 * d * es);
-                b.oc = ar.take(rows * d * es); b.x2 = ar.take(rows * d * es);
-                b.statsc = f32(2 * rows); b.lsec = f32(rows * h);
+        auto layer = [&](T5Bufs& b, const T5Bufs* shared, size_t rows, bool is_dec) {
+            if (shared) {
+                b = *shared;
+            } else {
+                b.u1 = ar.take(rows * d * es); b.qkv = ar.take(rows * 3 * d * es); b.o = ar.take(rows * d * es);
+                b.x1 = ar.take(rows * d * es); b.u2 = ar.take(rows * d * es); b.zg = ar.take(rows * F * es);
+                b.zu = ar.take(rows * F * es); b.a = ar.take(rows * F * es);
+                b.stats1 = f32(2 * rows); b.stats2 = f32(2 * rows); b.lse = f32(rows * h);
+                b.uc = b.qc = b.kvc = b.oc = b.x2 = nullptr;
+                b.statsc = b.lsec = nullptr;
+                if (is_dec) {
+                    b.uc = ar.take(rows * d * es); b.qc = ar.take(rows * d * es); b.kvc = ar.take(R * 2 * d * es);
+                    b.oc = ar.take(rows * d * es); b.x2 = ar.take(rows * d * es);
+                    b.statsc = f32(2 * rows); b.lsec = f32(rows * h);
+                }
             }
+            b.xout = ar.take(rows * d * es);
             b.wqkv_t = b.wo_t = b.wg_t = b.wu_t = b.w2_t = b.wcq_t = b.wckv_t = b.wco_t = nullptr;
             if (nt) {
                 b.wqkv_t = ar.take(3 * d * d * es); b.wo_t = ar.take(d * d * es);
@@ -159,8 +174,8 @@ void carve(ds_stage* s) {
         };
         s->enc.resize(c.n_layers);
         s->dec.resize(c.n_dec_layers);
-        for (T5Bufs& b : s->enc) layer(b, R, false);
-        for (T5Bufs& b : s->dec) layer(b, Rt, true);
+        for (size_t li = 0; li < s->enc.size(); ++li) layer(s->enc[li], share && li > 0 ? &s->enc[0] : nullptr, R, false);
+        for (size_t li = 0; li < s->dec.size(); ++li) layer(s->dec[li], share && li > 0 ? &s->dec[0] : nullptr, Rt, true);
     }
     s->x0 = ar.take(R * d * es);
     s->dyA = ar.take(Rm * d * es); s->dyB = ar.take(Rm * d * es);
@@ -389,18 +404,24 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         x_in = s->x0;
     }
     const void* x0 = x_in;
-    for (int l = 0; l < L; ++l) {
+    // forward of layer l from its input; x_out = NULL: only what the layer's backward reads (recomputation)
+    auto layer_fwd = [&](int l, const void* xl, void* x_out) -> ds_status {
         GptBufs& b = s->gpt[l];
-        void* x_out = (l == L - 1) ? io->act_out : b.xout;
-        DS_TRY(op.norm_fwd(sm, 0, x_in, w[l].ln1_g, w[l].ln1_b, b.u1, b.stats1));
+        DS_TRY(op.norm_fwd(sm, 0, xl, w[l].ln1_g, w[l].ln1_b, b.u1, b.stats1));
         DS_TRY(op.fwd(sm, 3 * d, d, b.u1, w[l].w_qkv, b.wqkv_t, b.qkv, DS_EPI_NONE, w[l].b_qkv, nullptr, nullptr, false));
         DS_TRY(op.self_fwd(sm, 1, b.qkv, b.o, b.lse));
-        DS_TRY(op.fwd(sm, d, d, b.o, w[l].w_o, b.wo_t, b.x1, DS_EPI_RESID, w[l].b_o, x_in, nullptr, true));
+        DS_TRY(op.fwd(sm, d, d, b.o, w[l].w_o, b.wo_t, b.x1, DS_EPI_RESID, w[l].b_o, xl, nullptr, true));
         DS_TRY(op.norm_fwd(sm, 0, b.x1, w[l].ln2_g, w[l].ln2_b, b.u2, b.stats2));
         DS_TRY(op.fwd(sm, F, d, b.u2, w[l].w_1, b.w1_t, b.z, DS_EPI_GELU, w[l].b_1, nullptr, b.a, false));
-        DS_TRY(op.fwd(sm, d, F, b.a, w[l].w_2, b.w2_t, x_out, DS_EPI_RESID, w[l].b_2, b.x1, nullptr, true));
+        if (!x_out) return DS_OK;
+        return op.fwd(sm, d, F, b.a, w[l].w_2, b.w2_t, x_out, DS_EPI_RESID, w[l].b_2, b.x1, nullptr, true);
+    };
+    for (int l = 0; l < L; ++l) {
+        void* x_out = (l == L - 1) ? io->act_out : s->gpt[l].xout;
+        DS_TRY(layer_fwd(l, x_in, x_out));
         x_in = x_out;
     }
+    const bool recompute = s->cfg.recompute == DS_RECOMPUTE_FULL;
 
     // ---------------- backward (BackwardPass of every micro-batch; weight gradients summed over all of them)
     const void* dy = io->grad_out;
@@ -414,6 +435,8 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         GptBufs& b = s->gpt[l];
         const void* xl_in = (l == 0) ? x0 : s->gpt[l - 1].xout;
         void* dx_in = (l == 0) ? io->grad_in : pp[flip];
+        // the shared buffers still hold the last layer's forward; every other layer's is run again
+        if (recompute && l != L - 1) DS_TRY(layer_fwd(l, xl_in, nullptr));
         // MLP
         DS_TRY(op.wgrad(sm, F, d, b.a, dy, g[l].w_2));
         DS_TRY(op.colsum(sm, d, dy, g[l].b_2));
@@ -448,12 +471,14 @@ ds_status t5_self_fwd(Ops& op, const Stream& sm, int mask, const void* x, T5Bufs
     return op.fwd(sm, d, d, b.o, w_o, b.wo_t, b.x1, DS_EPI_RESID, nullptr, x, nullptr, true);
 }
 // Gated-GELU MLP forward: out = xin + (GELU(u Wg) * (u Wu)) W2,  u = RMS2(xin)
+// (out = NULL: only what the backward reads, for recomputation)
 ds_status t5_mlp_fwd(Ops& op, const Stream& sm, const void* xin, void* out, T5Bufs& b, const void* ln2_g, const void* w_g,
                      const void* w_u, const void* w_2) {
     const int d = op.d, F = op.F;
     DS_TRY(op.norm_fwd(sm, 1, xin, ln2_g, nullptr, b.u2, b.stats2));
     DS_TRY(op.fwd(sm, F, d, b.u2, w_g, b.wg_t, b.zg, DS_EPI_NONE, nullptr, nullptr, nullptr, false));
     DS_TRY(op.fwd(sm, F, d, b.u2, w_u, b.wu_t, b.zu, DS_EPI_GATE, nullptr, b.zg, b.a, false));
+    if (!out) return DS_OK;
     return op.fwd(sm, d, F, b.a, w_2, b.w2_t, out, DS_EPI_RESID, nullptr, xin, nullptr, true);
 }
 // MLP backward: dy = gradient of the MLP output; writes dy + RMS2-backward(...) (the gradient of xin) into dxin
@@ -520,11 +545,16 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
         x_in = s->x0;
     }
     const void* x0 = x_in;
-    for (int l = 0; l < Le; ++l) {
+    const bool recompute = s->cfg.recompute == DS_RECOMPUTE_FULL;
+    // forward of encoder layer l from its input; with_out = false: only what its backward reads (recomputation)
+    auto enc_layer_fwd = [&](int l, const void* xl, bool with_out) -> ds_status {
         T5Bufs& b = s->enc[l];
-        DS_TRY(t5_self_fwd(op, E, 0, x_in, b, we[l].ln1_g, we[l].w_qkv, we[l].w_o));
-        DS_TRY(t5_mlp_fwd(op, E, b.x1, b.xout, b, we[l].ln2_g, we[l].w_g, we[l].w_u, we[l].w_2));
-        x_in = b.xout;
+        DS_TRY(t5_self_fwd(op, E, 0, xl, b, we[l].ln1_g, we[l].w_qkv, we[l].w_o));
+        return t5_mlp_fwd(op, E, b.x1, with_out ? b.xout : nullptr, b, we[l].ln2_g, we[l].w_g, we[l].w_u, we[l].w_2);
+    };
+    for (int l = 0; l < Le; ++l) {
+        DS_TRY(enc_layer_fwd(l, x_in, true));
+        x_in = s->enc[l].xout;
     }
     const void* enc_out = x_in;
 
@@ -535,10 +565,10 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
         y_in = s->y0;
     }
     const void* y0 = y_in;
-    for (int l = 0; l < Ld; ++l) {
+    // forward of decoder layer l from its input; y_out = NULL: only what its backward reads (recomputation)
+    auto dec_layer_fwd = [&](int l, const void* yl, void* y_out) -> ds_status {
         T5Bufs& b = s->dec[l];
-        void* y_out = (l == Ld - 1) ? io->act_out : b.xout;
-        DS_TRY(t5_self_fwd(op, D, 1, y_in, b, wd[l].ln1_g, wd[l].w_qkv, wd[l].w_o));
+        DS_TRY(t5_self_fwd(op, D, 1, yl, b, wd[l].ln1_g, wd[l].w_qkv, wd[l].w_o));
         // cross-attention: queries from the decoder stream, keys / values from the encoder output
         DS_TRY(op.norm_fwd(D, 1, b.x1, wd[l].lnc_g, nullptr, b.uc, b.statsc));
         DS_TRY(op.fwd(D, d, d, b.uc, wd[l].w_cq, b.wcq_t, b.qc, DS_EPI_NONE, nullptr, nullptr, nullptr, false));
@@ -553,7 +583,11 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
             DS_TRY(op.zero_pad(D, b.oc, d));
         }
         DS_TRY(op.fwd(D, d, d, b.oc, wd[l].w_co, b.wco_t, b.x2, DS_EPI_RESID, nullptr, b.x1, nullptr, true));
-        DS_TRY(t5_mlp_fwd(op, D, b.x2, y_out, b, wd[l].ln2_g, wd[l].w_g, wd[l].w_u, wd[l].w_2));
+        return t5_mlp_fwd(op, D, b.x2, y_out, b, wd[l].ln2_g, wd[l].w_g, wd[l].w_u, wd[l].w_2);
+    };
+    for (int l = 0; l < Ld; ++l) {
+        void* y_out = (l == Ld - 1) ? io->act_out : s->dec[l].xout;
+        DS_TRY(dec_layer_fwd(l, y_in, y_out));
         y_in = y_out;
     }
 
@@ -572,6 +606,7 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
         T5Bufs& b = s->dec[l];
         const void* yl_in = (l == 0) ? y0 : s->dec[l - 1].xout;
         void* dy_in = (l == 0) ? io->grad_in_tgt : pp[flip];
+        if (recompute && l != Ld - 1) DS_TRY(dec_layer_fwd(l, yl_in, nullptr));
         // MLP: gradient of x2 into dx2
         DS_TRY(t5_mlp_bwd(op, D, dy, b.x2, s->dx2, b, wd[l].ln2_g, wd[l].w_g, wd[l].w_u, wd[l].w_2, gd[l].ln2_g, gd[l].w_g,
                           gd[l].w_u, gd[l].w_2));
@@ -614,6 +649,7 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
         T5Bufs& b = s->enc[l];
         const void* xl_in = (l == 0) ? x0 : s->enc[l - 1].xout;
         void* dx_in = (l == 0) ? io->grad_in : pp[flip];
+        if (recompute && l != Le - 1) DS_TRY(enc_layer_fwd(l, xl_in, false));
         DS_TRY(t5_mlp_bwd(op, E, dx, b.x1, s->dx1, b, we[l].ln2_g, we[l].w_g, we[l].w_u, we[l].w_2, ge[l].ln2_g, ge[l].w_g,
                           ge[l].w_u, ge[l].w_2));
         DS_TRY(t5_self_bwd(op, E, 0, s->dx1, xl_in, dx_in, b, we[l].ln1_g, we[l].w_qkv, we[l].w_o, ge[l].ln1_g, ge[l].w_qkv,
@@ -626,9 +662,8 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
 
 }  // namespace
 
-extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out) {
-    if (!cfg || !out) return DS_EINVAL;
-    *out = nullptr;
+namespace {
+ds_status check_config(const ds_stage_config* cfg) {
     if (cfg->model != DS_MODEL_GPT && cfg->model != DS_MODEL_T5) return DS_EINVAL;
     if (cfg->dtype != DS_DTYPE_F32 && cfg->dtype != DS_DTYPE_BF16) return DS_EINVAL;
     if (cfg->n_layers <= 0 || cfg->d_model <= 0 || cfg->n_heads <= 0 || cfg->d_ff <= 0) return DS_EINVAL;
@@ -638,7 +673,11 @@ extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out)
     if (cfg->max_rows <= 0 || cfg->max_seqs <= 0) return DS_EINVAL;
     if (cfg->model == DS_MODEL_GPT && (cfg->n_dec_layers != 0 || cfg->max_rows_tgt != 0)) return DS_EINVAL;
     if (cfg->model == DS_MODEL_T5 && (cfg->n_dec_layers <= 0 || cfg->max_rows_tgt <= 0)) return DS_EINVAL;
-
+    if (cfg->recompute != DS_RECOMPUTE_NONE && cfg->recompute != DS_RECOMPUTE_FULL) return DS_EINVAL;
+    return DS_OK;
+}
+// a stage object with its workspace measured (arena.used) but not allocated
+ds_status measure(const ds_stage_config* cfg, ds_stage** out) {
     ds_stage* s = new (std::nothrow) ds_stage();
     if (!s) return DS_ENOMEM;
     s->cfg = *cfg;
@@ -650,6 +689,25 @@ extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out)
         delete s;
         return DS_ENOMEM;
     }
+    *out = s;
+    return DS_OK;
+}
+}  // namespace
+
+extern "C" int64_t ds_stage_workspace_need(const ds_stage_config* cfg) {
+    ds_stage* s = nullptr;
+    if (!cfg || check_config(cfg) != DS_OK || measure(cfg, &s) != DS_OK) return -1;
+    const int64_t need = (int64_t)s->arena.used;
+    delete s;
+    return need;
+}
+
+extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out) {
+    if (!cfg || !out) return DS_EINVAL;
+    *out = nullptr;
+    DS_TRY(check_config(cfg));
+    ds_stage* s = nullptr;
+    DS_TRY(measure(cfg, &s));
     const size_t need = s->arena.used;
     if (hipMalloc(&s->ws, need) != hipSuccess) {
         (void)hipGetLastError();

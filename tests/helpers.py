@@ -62,14 +62,15 @@ def zero_grads_like(params_dev):
     return [{k: torch.zeros(v.shape, dtype=torch.float32, device=DEV) for k, v in layer.items()} for layer in params_dev]
 
 
-def run_gpt_stage(layout, cfg, params, xs, dys, dtype_code, stage=None, fill=float("nan"), accumulate=False, grads=None):
+def run_gpt_stage(layout, cfg, params, xs, dys, dtype_code, stage=None, fill=float("nan"), accumulate=False, grads=None,
+                  recompute=0):
     """Run stage_fwd_bwd on a layout.  Returns (outs, dxs, grads_np, pad_out_rows, pad_dx_rows)."""
     dt = tdtype(dtype_code)
     d = cfg["d_model"]
     own = stage is None
     if own:
         stage = ds.Stage(ds.DS_MODEL_GPT, dtype_code, cfg["n_layers"], d, cfg["n_heads"], cfg["d_ff"],
-                         max_rows=layout.total_rows, max_seqs=layout.n_seq)
+                         max_rows=layout.total_rows, max_seqs=layout.n_seq, recompute=recompute)
     w = params_to_dev(params, dt)
     if grads is None:
         grads = zero_grads_like(w)
@@ -91,14 +92,14 @@ def cat(seqs):
     return np.concatenate([np.asarray(s, dtype=np.float64) for s in seqs], axis=0)
 
 
-def run_t5_stage(layout, cfg, enc_params, dec_params, enc_xs, dec_xs, ddec, dtype_code, fill=float("nan")):
+def run_t5_stage(layout, cfg, enc_params, dec_params, enc_xs, dec_xs, ddec, dtype_code, fill=float("nan"), recompute=0):
     """Encoder-decoder stage on a two-stream layout.  Returns dict of per-sequence outputs / gradients,
     weight gradients (numpy) and the padding rows of every output stream."""
     dt = tdtype(dtype_code)
     d = cfg["d_model"]
     stage = ds.Stage(ds.DS_MODEL_T5, dtype_code, cfg["n_layers"], d, cfg["n_heads"], cfg["d_ff"],
                      max_rows=layout.total_rows, max_seqs=layout.n_seq, n_dec_layers=cfg["n_dec_layers"],
-                     max_rows_tgt=layout.total_rows_tgt)
+                     max_rows_tgt=layout.total_rows_tgt, recompute=recompute)
     we, wd = params_to_dev(enc_params, dt), params_to_dev(dec_params, dt)
     ge, gd = zero_grads_like(we), zero_grads_like(wd)
     x = stream_from_seqs(enc_xs, layout, d, dt, fill, which=0)

@@ -89,3 +89,23 @@ def test_errors():
     with pytest.raises(ds.DsError) as e:
         ds.ds_plan_recompute(lens, [ok], 9, 2)        # cap 8 < 9
     assert e.value.code == -2
+
+
+def test_workspace_need_of_recomputation_modes():
+    """Host-side workspace sizes: one layer's saved activations are shared under full recomputation."""
+    def need(L, mode, model=ds.DS_MODEL_GPT, **kw):
+        return ds.ds_stage_workspace_need(model, ds.DS_DTYPE_BF16, L, 512, 4, 2048, max_rows=5000, max_seqs=64, recompute=mode, **kw)
+    keep = [need(L, ds.DS_RECOMPUTE_NONE) for L in (1, 2, 3, 4)]
+    redo = [need(L, ds.DS_RECOMPUTE_FULL) for L in (1, 2, 3, 4)]
+    assert keep[0] == redo[0]                                # a single layer has nothing to share
+    per_keep, per_redo = keep[1] - keep[0], redo[1] - redo[0]
+    assert keep[3] - keep[2] == per_keep and redo[3] - redo[2] == per_redo      # linear in the layer count
+    # what full recomputation no longer keeps per extra layer: u1, qkv, o, x1, u2 (7 d per row), z, a (2 F), bf16,
+    # plus the fp32 statistics (2 + 2 + heads per row); allocations are rounded up to 256 bytes
+    rows, d, F, h = 5000, 512, 2048, 4
+    saved = rows * ((7 * d + 2 * F) * 2 + (4 + h) * 4)
+    assert 0 <= (per_keep - per_redo) - saved < 16 * 256
+    t5 = dict(model=ds.DS_MODEL_T5, n_dec_layers=2, max_rows_tgt=1000)
+    assert need(2, ds.DS_RECOMPUTE_FULL, **t5) < need(2, ds.DS_RECOMPUTE_NONE, **t5)
+    with pytest.raises(ds.DsError):
+        need(2, 7)
