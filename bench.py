@@ -113,6 +113,9 @@ def main():
     ap.add_argument("--config", default="gpt_2048_bf16")
     ap.add_argument("--layout", default="dp", choices=["dp", "fixed", "packed", "packed_dense"])
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--recompute", default="none", choices=["none", "full"],
+                    help="full: keep only layer inputs and re-run each layer's forward before its backward (context; "
+                         "the headline keeps every activation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -128,6 +131,7 @@ def main():
         sys.exit(3)
     cfg = wl.CONFIGS[args.config]
     t5 = cfg["kind"] == "t5"
+    recompute = ds.DS_RECOMPUTE_FULL if args.recompute == "full" else ds.DS_RECOMPUTE_NONE
     dev = "cuda:0"
     torch.cuda.set_device(0)
     lens, tgts = wl.draw_lengths(cfg["lengths"], seed=args.seed)
@@ -178,7 +182,7 @@ def main():
         x, y, dy = rnd(R), rnd(Rt), rnd(Rt)
         out, dx, dyin = torch.empty_like(y), torch.empty_like(x), torch.empty_like(y)
         stage = ds.Stage(ds.DS_MODEL_T5, code, L, d, H, F, max_rows=R, max_seqs=len(lens),
-                         n_dec_layers=cfg["n_dec_layers"], max_rows_tgt=Rt)
+                         n_dec_layers=cfg["n_dec_layers"], max_rows_tgt=Rt, recompute=recompute)
 
         def step():
             ds.stage_fwd_bwd(stage, layout, weights, x, dy, out, dx, grads, accumulate=False, weights_dec=weights_d,
@@ -187,11 +191,13 @@ def main():
         weights, grads = make_layers(ds.GPT_KEYS, L)
         x, dy = rnd(R), rnd(R)
         out, dx = torch.empty_like(x), torch.empty_like(x)
-        stage = ds.Stage(ds.DS_MODEL_GPT, code, L, d, H, F, max_rows=R, max_seqs=max(len(lens), layout.n_seq))
+        stage = ds.Stage(ds.DS_MODEL_GPT, code, L, d, H, F, max_rows=R, max_seqs=max(len(lens), layout.n_seq),
+                         recompute=recompute)
 
         def step():
             ds.stage_fwd_bwd(stage, layout, weights, x, dy, out, dx, grads, accumulate=False)
-    log("workspace %.2f GB" % (stage.workspace_bytes() / 2 ** 30))
+    workspace_gb = stage.workspace_bytes() / 2 ** 30
+    log("workspace %.2f GB" % workspace_gb)
 
     for _ in range(args.warmup):
         step()
@@ -236,7 +242,8 @@ def main():
         "config": {"workload": args.config, "model": "%d layers d_model %d heads %d d_ff %d causal" % (L, d, H, F),
                    "layout": layout_desc, "n_seq": int(len(lens)), "non_pad_tokens": tokens, "rows": int(all_rows),
                    "n_micro_batches": int(layout.n_mb), "padding_efficiency": tokens / all_rows,
-                   "dp_plan_ms": plan_ms, "useful_mfma_utilisation": useful_util,
+                   "dp_plan_ms": plan_ms, "recompute": args.recompute, "workspace_gb": round(workspace_gb, 3),
+                   "useful_mfma_utilisation": useful_util,
                    "ms_per_step_by_group": breakdown},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt_kernel (all projections: forward, dgrad, wgrad)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -43,7 +43,7 @@ def power_of_two_grid(lo, hi):
 class StageRunner:
     """A GPT stage with seeded random weights and row buffers; runs any layout on a row range."""
 
-    def __init__(self, cfg, max_rows, max_seqs, seed=0, device="cuda:0"):
+    def __init__(self, cfg, max_rows, max_seqs, seed=0, device="cuda:0", recompute=0):
         import torch
         self.torch = torch
         d, F, L, H = cfg["d_model"], cfg["d_ff"], cfg["n_layers"], cfg["n_heads"]
@@ -69,7 +69,7 @@ class StageRunner:
         self.out = torch.empty_like(self.x)
         self.dx = torch.empty_like(self.x)
         self.stage = ds.Stage(ds.DS_MODEL_GPT, ds.DS_DTYPE_BF16 if bf16 else ds.DS_DTYPE_F32, L, d, H, F,
-                              max_rows=max_rows, max_seqs=max_seqs)
+                              max_rows=max_rows, max_seqs=max_seqs, recompute=recompute)
 
     def run(self, layout, row0=0, accumulate=False):
         r1 = row0 + layout.total_rows
