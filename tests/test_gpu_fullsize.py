@@ -119,3 +119,57 @@ def test_full_size_configuration(name, sample_tokens, long_len):
             assert e <= 2e-3, (li, k, e)
     print("  additivity of weight gradients over halves, worst %.2e" % worst)
     stage.close()
+
+
+@pytest.mark.timeout(900)
+def test_full_size_encoder_decoder_configuration():
+    """t5_1024_bf16 at its full size (DP plan of the whole seeded batch, 2 + 2 layers, d = 1024, head dimension 64):
+    decoder outputs and both input gradients of SAMPLED samples against the oracle (samples are independent of each
+    other), weight gradients on the sampled sub-batch."""
+    from helpers import run_t5_stage
+    name = "t5_1024_bf16"
+    cfg = wl.CONFIGS[name]
+    d, F, H = cfg["d_model"], cfg["d_ff"], cfg["n_heads"]
+    lens, tgts = wl.draw_lengths(cfg["lengths"], seed=0)
+    cm = ds.make_cost_model(kind=ds.DS_COST_POLY_T5)
+    layout = ds.dp_plan(lens, cm, cfg["cap"], cfg["num_stages"], lengths_tgt=tgts)
+    ep = wl.draw_params(wl.T5_ENC_KEYS, cfg["n_layers"], d, F, seed=0, tag=6, bf16=True)
+    dp = wl.draw_params(wl.T5_DEC_KEYS, cfg["n_dec_layers"], d, F, seed=0, tag=7, bf16=True)
+    ex = wl.draw_rows(lens, d, seed=0, tag=3, bf16=True)
+    dx = wl.draw_rows(tgts, d, seed=0, tag=8, bf16=True)
+    ddy = wl.draw_rows(tgts, d, seed=0, tag=5, bf16=True)
+    # sampled samples: shortest and longest input, longest target, and median ones up to a token budget
+    order = np.argsort(lens, kind="stable")
+    pick = {int(order[0]), int(np.argmin(np.abs(lens.astype(np.int64) - 700))), int(np.argmax(tgts))}
+    tok = int(sum(lens[i] for i in pick))
+    for i in order[len(order) // 2:]:
+        if tok + int(lens[i]) > 1800:
+            break
+        if int(i) not in pick:
+            pick.add(int(i))
+            tok += int(lens[i])
+    pick = sorted(pick)
+    print(name, "sampled", pick, "input lengths", [int(lens[i]) for i in pick], "target lengths", [int(tgts[i]) for i in pick])
+
+    got = run_t5_stage(layout, cfg, ep, dp, ex, dx, ddy, ds.DS_DTYPE_BF16)
+    sub = lambda seqs: [seqs[i] for i in pick]
+    r_outs, r_denc, r_ddec, r_eg, r_dg = ost.t5_stage_fwd_bwd(sub(ex), sub(dx), sub(ddy), ep, dp, H)
+    for j, i in enumerate(pick):
+        e = (rel_err(got["outs"][i], r_outs[j]), rel_err(got["d_enc"][i], r_denc[j]), rel_err(got["d_dec"][i], r_ddec[j]))
+        print("  sample", i, "dec_out %.2e d_enc_in %.2e d_dec_in %.2e" % e)
+        assert max(e) <= 2e-2, (i, e)
+    for p in got["pads"]:
+        assert p.size == 0 or np.all(p == 0)
+
+    # the sampled sub-batch through the full-size model: weight gradients against the oracle
+    sl, st_ = lens[pick], tgts[pick]
+    lo_sub = ds.dp_plan(sl, cm, cfg["cap"], cfg["num_stages"], lengths_tgt=st_)
+    got_sub = run_t5_stage(lo_sub, cfg, ep, dp, sub(ex), sub(dx), sub(ddy), ds.DS_DTYPE_BF16)
+    worst = 0.0
+    for tag, gg, rr in (("enc", got_sub["eg"], r_eg), ("dec", got_sub["dg"], r_dg)):
+        for li, layer in enumerate(rr):
+            for k, v in layer.items():
+                e = rel_err(gg[li][k], v)
+                worst = max(worst, e)
+                assert e <= 2e-2, (tag, li, k, e)
+    print("  sub-batch weight gradients, worst %.2e" % worst)
