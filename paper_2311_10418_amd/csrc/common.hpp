@@ -125,6 +125,20 @@ __device__ __forceinline__ void wave_lds_sync() {
 // expcnt 6:4 and lgkmcnt 11:8 left at their maxima, i.e. not waited for)
 constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
+// The same transfer addressed as a wavefront-uniform base (scalar registers) plus a 32-bit byte offset per lane:
+// the per-lane part can then stay fixed over a whole K loop, and stepping to the next tile is scalar arithmetic.
+__device__ __forceinline__ void lds_dma16_s(const void* base, uint32_t lane_off, const void* lds_ptr) {
+    const uint32_t lds_addr =
+        __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds_ptr);
+    const uint64_t b = (uint64_t)(uintptr_t)base;
+    // (the builtin returns a signed int: without the casts the low half would be sign-extended over the high half)
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    const uint64_t sb = ((uint64_t)hi << 32) | (uint64_t)lo;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 : : "v"(lane_off), "s"(sb), "s"(lds_addr) : "memory", "m0");
+}
+
 static inline size_t dtype_size(int32_t dtype) { return dtype == DS_DTYPE_BF16 ? 2 : 4; }
 
 // ---- launchers shared between translation units (all enqueue on `st`, return ds_status)
