@@ -106,3 +106,49 @@ def test_layout_too_large_for_workspace_is_rejected():
         run_gpt_stage(lo, dict(cfg, n_layers=1), params[:1], xs, dys, ds.DS_DTYPE_BF16, stage=stage)
     assert e.value.code == ds.DS_ELAYOUT
     stage.close()
+
+
+def test_stage_call_can_be_captured_in_a_graph_and_replays_identically():
+    """With its layout already bound (one eager call), stage_fwd_bwd only enqueues kernels: it can be captured in a
+    HIP graph; every replay, with eager work and synchronisation in between, reproduces the eager result bit for bit."""
+    cfg, lens, params, xs, dys = _small_case(True, n_seq=12)
+    lo = ds.dp_plan(lens, ds.make_cost_model(fixed=2_000_000), cfg["cap"], cfg["num_stages"])
+    from helpers import params_to_dev, stream_from_seqs, zero_grads_like
+    d = cfg["d_model"]
+    stage = ds.Stage(ds.DS_MODEL_GPT, ds.DS_DTYPE_BF16, cfg["n_layers"], d, cfg["n_heads"], cfg["d_ff"],
+                     max_rows=lo.total_rows, max_seqs=lo.n_seq)
+    w = params_to_dev(params, torch.bfloat16)
+    grads = zero_grads_like(w)
+    x = stream_from_seqs(xs, lo, d, torch.bfloat16, 0.0)
+    dy = stream_from_seqs(dys, lo, d, torch.bfloat16, 0.0)
+    out, dx = torch.empty_like(x), torch.empty_like(x)
+
+    def call():
+        ds.stage_fwd_bwd(stage, lo, w, x, dy, out, dx, grads, accumulate=False)
+
+    def snapshot():
+        return [out.clone(), dx.clone()] + [g[k].clone() for g in grads for k in g]
+
+    for _ in range(2):
+        call()
+    torch.cuda.synchronize()
+    ref = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        out.fill_(3.0)
+        dx.fill_(3.0)
+        for g in grads:
+            for v in g.values():
+                v.fill_(3.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(ref, snapshot()):
+            assert torch.equal(a, b)
+        call()                                   # eager work between replays
+        torch.cuda.synchronize()
+    del graph
+    stage.close()
