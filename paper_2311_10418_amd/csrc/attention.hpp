@@ -21,6 +21,7 @@ struct AttnArgs {
     size_t scratch_bytes;
     int32_t q_total_rows, k_total_rows;               // rows of the query-side / key-side streams
     int32_t lists_ready;                              // the scratch already holds this call's work lists
+    int32_t lists_want_both;                          // build the key-side list too even if this call only needs the query side
     const int32_t* n_items;                           // DEVICE [2]: query-side, key-side item counts
     const int2 *items_q, *items_k;                    // DEVICE (sequence, 128-row block), longest first
     int32_t max_items_q, max_items_k;                 // host upper bounds = grid sizes

@@ -686,7 +686,7 @@ ds_status attn_prepare_lists(AttnArgs& a, bool need_key_side, hipStream_t st) {
     hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(1024), 0, st, a.n_seq, a.q_len, a.k_len, a.mask, 0, a.max_items_q,
                        (int2*)a.items_q, (int32_t*)base);
     DS_LAUNCH_CHECK();
-    if (need_key_side) {
+    if (need_key_side || a.lists_want_both) {
         hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(1024), 0, st, a.n_seq, a.k_len, a.q_len, a.mask, 1, a.max_items_k,
                            (int2*)a.items_k, (int32_t*)base + 1);
         DS_LAUNCH_CHECK();

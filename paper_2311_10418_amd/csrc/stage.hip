@@ -95,6 +95,10 @@ struct ds_stage {
     void* attn_scratch = nullptr;           // feature-major copies for the attention kernels
     size_t attn_scratch_bytes = 0;
     bool nt_mode = false;
+    // the attention work lists in the scratch depend only on the layout and on which streams / mask they were built
+    // for: they are kept across layers and calls while both stay the same
+    uint64_t lists_uid = 0;
+    int lists_kind = -1;
     size_t split_ws_floats = 0;
     int32_t launches = 0;
     // optional per-kernel-group timing
@@ -272,6 +276,7 @@ struct Ops {
     int accumulate;
     int dt, d, F;
     bool nt;
+    int cur_kind = -1;          // of the attention arguments built last
 
     ds_status gemm_raw(int cat, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C, int epi,
                        const void* bias, const void* R, const void* R2, void* C2, const int32_t* row_valid, int acc) {
@@ -351,7 +356,17 @@ struct Ops {
         a.scratch_bytes = s->attn_scratch_bytes;
         a.q_total_rows = q.R;
         a.k_total_rows = k.R;
+        cur_kind = (&q == &s->tgt ? 1 : 0) | (&k == &s->tgt ? 2 : 0) | (mask ? 4 : 0);
+        a.lists_want_both = 1;
+        a.lists_ready = (s->lists_uid != 0 && s->lists_uid == s->bound_uid && s->lists_kind == cur_kind) ? 1 : 0;
         return a;
+    }
+    // after a launch that went through the matrix-core kernels: the scratch now holds both lists of this kind
+    void lists_built(const AttnArgs& a) {
+        if (attn_mfma_supported(a)) {
+            s->lists_uid = s->bound_uid;
+            s->lists_kind = cur_kind;
+        }
     }
     // self-attention over a packed [rows, 3d] tensor
     ds_status self_fwd(const Stream& sm, int mask, const void* qkv, void* o, float* lse) {
@@ -360,8 +375,9 @@ struct Ops {
         a.q = base; a.k = base + (size_t)d * s->es; a.v = base + (size_t)2 * d * s->es;
         a.ldq = a.ldk = a.ldv = 3 * d;
         a.o = o; a.lse = lse;
-        s->launches += 2;
+        s->launches += a.lists_ready ? 1 : 3;
         DS_TRY(timed(s, DS_PROF_ATTN_FWD, st, [&] { return launch_attention_fwd(a, false, st); }));
+        lists_built(a);
         return zero_pad(sm, o, d);
     }
     ds_status self_bwd(const Stream& sm, int mask, const void* qkv, const void* o, const void* d_o, const float* lse, void* dqkv) {
@@ -372,8 +388,9 @@ struct Ops {
         a.o = const_cast<void*>(o); a.d_o = d_o; a.lse = const_cast<float*>(lse); a.delta = s->delta;
         char* g = (char*)dqkv;
         a.dq = g; a.dk = g + (size_t)d * s->es; a.dv = g + (size_t)2 * d * s->es;
-        s->launches += 4;
+        s->launches += a.lists_ready ? 2 : 4;
         DS_TRY(timed(s, DS_PROF_ATTN_BWD, st, [&] { return launch_attention_bwd(a, false, st); }));
+        lists_built(a);
         return zero_pad(sm, dqkv, 3 * d);
     }
 };
@@ -580,6 +597,7 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
             a.o = b.oc; a.lse = b.lsec;
             s->launches += 2;
             DS_TRY(timed(s, DS_PROF_ATTN_FWD, st, [&] { return launch_attention_fwd(a, false, st); }));
+            op.lists_built(a);
             DS_TRY(op.zero_pad(D, b.oc, d));
         }
         DS_TRY(op.fwd(D, d, d, b.oc, wd[l].w_co, b.wco_t, b.x2, DS_EPI_RESID, nullptr, b.x1, nullptr, true));
@@ -621,6 +639,7 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
             a.dq = s->dqc; a.dk = s->dkvc; a.dv = (char*)s->dkvc + (size_t)d * s->es;
             s->launches += 4;
             DS_TRY(timed(s, DS_PROF_ATTN_BWD, st, [&] { return launch_attention_bwd(a, false, st); }));
+            op.lists_built(a);
             DS_TRY(op.zero_pad(D, s->dqc, d));
             DS_TRY(op.zero_pad(E, s->dkvc, 2 * d));
         }
