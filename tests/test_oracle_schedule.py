@@ -115,3 +115,53 @@ def test_comm_plan_invariants(seed):
             if j + 1 < C:
                 assert idx[(osch.RECV_GRAD, i)] < idx[(osch.WAIT_GRAD, i)] == idx[(osch.BWD, i)] - 1
                 assert idx[(osch.FWD, i)] < idx[(osch.SEND_ACT, i)]
+
+
+def _golden(name):
+    import os
+    out = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", name)) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, *v = line.split()
+                out[k] = [int(x) for x in v]
+    return out
+
+
+def test_paper_example_of_safety_stocks():
+    """The figures the paper states for its 7-micro-batch example (tests/golden/safety_stock_example.txt), with
+    equal micro-batches (the text gives no sizes): how many micro-batches the first stage takes in before its first
+    backward under 1F1B and under the adaptive schedule, the activations held, and which micro-batches a limit of
+    three activations holds back."""
+    g = _golden("safety_stock_example.txt")
+    C, M = g["stages"][0], g["micro_batches"][0]
+    a = [[1] * C for _ in range(M)]
+
+    def leading_forwards(order):
+        n = 0
+        for _, kind in order:
+            if kind != osch.F:
+                break
+            n += 1
+        return n
+
+    assert leading_forwards(osch.one_f_one_b(C, M)[0]) == g["injected_at_start_1f1b"][0]
+    O, _ = osch.adaptive(C, M, a, [10 ** 6] * C)
+    assert leading_forwards(O[0]) == g["injected_at_start_adaptive"][0]
+    tf, tb = [[1] * C for _ in range(M)], [[2] * C for _ in range(M)]
+    assert max(osch.simulate(C, M, O, tf, tb, a)["peak"]) == g["peak_adaptive_unlimited"][0]
+    # a limit of three activations (Alg. 1's test is strict: m + a < l, so l = 3 + 1)
+    lim = g["peak_adaptive_limited"][0]
+    O, _ = osch.adaptive(C, M, a, [lim + 1] * C)
+    sim = osch.simulate(C, M, O, tf, tb, a)
+    assert max(sim["peak"]) == lim
+    # held back = forwards on the first stage that start after the stage sat idle (since its previous forward)
+    held, idle = [], False
+    for k, (i, kind) in enumerate(O[0]):
+        if k and sim["start"][0][k] > sim["end"][0][k - 1]:
+            idle = True
+        if kind == osch.F:
+            if idle:
+                held.append(i)
+            idle = False
+    assert held == g["held_back"]
