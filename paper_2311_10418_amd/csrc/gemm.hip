@@ -834,6 +834,46 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
 #pragma unroll
         for (int i = 0; i < TM; ++i) prefetch_pass(i);
     }
+    if constexpr (EPI == DS_EPI_NONE) {
+        // Plain output (+ bias): nothing is computed after the transposition, so the bias is added and the value
+        // rounded to bf16 BEFORE staging: half the LDS traffic of the fp32 staging below, which bounds the epilogue.
+        if (direct) {
+            bf16_t* stage_h = reinterpret_cast<bf16_t*>(stage);
+            constexpr int LD_H = TN * 32 + 8;                       // bf16 row stride (144 bytes: 8-byte writes of 16 rows spread over the banks)
+            float bias4[TN16][4];
+#pragma unroll
+            for (int j = 0; j < TN16; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    bias4[j][e] = p.bias ? (float)reinterpret_cast<const bf16_t*>(p.bias)[n0 + wn * (TN * 32) + j * 16 + 4 * (lane >> 4) + e] : 0.f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                wave_lds_sync();
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                    for (int j = 0; j < TN16; ++j) {
+                        typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+                        const f32x4_t a4 = acc[2 * i + i2][j];
+                        const bf16x4_t h4 = {(bf16_t)(a4[0] + bias4[j][0]), (bf16_t)(a4[1] + bias4[j][1]),
+                                             (bf16_t)(a4[2] + bias4[j][2]), (bf16_t)(a4[3] + bias4[j][3])};
+                        *reinterpret_cast<bf16x4_t*>(stage_h + (i2 * 16 + (lane & 15)) * LD_H + j * 16 + 4 * (lane >> 4)) = h4;
+                    }
+                wave_lds_sync();
+#pragma unroll
+                for (int pss = 0; pss < NPSS; ++pss) {
+                    const int row = pss * (64 / LPR) + rd_row;
+                    const int m = m0 + wm * (TM * 32) + i * 32 + row;
+                    const int n = n0 + wn * (TN * 32) + rd_col;
+                    if (m < M) {
+                        const bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(stage_h + row * LD_H + rd_col);
+                        __builtin_nontemporal_store(v, reinterpret_cast<bf16x8_t*>(C + (size_t)m * N + n));
+                    }
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         if (epilogue_reads<EPI>() && direct && !PRE_ALL) prefetch_pass(i);
