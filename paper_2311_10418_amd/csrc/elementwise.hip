@@ -236,6 +236,88 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(int rows, int d, const T*
     }
 }
 
+// Wide rows (d > 2048): one row per PAIR of wavefronts (a 128-thread work-group), each owning half of the columns, so
+// that the per-lane state (gain, dgamma / dbeta sums, dy * g, xhat: 5 x 8 x NI floats) still fits two wavefronts per
+// SIMD; with one wavefront per row it needs more than 256 registers and the kernel runs at half the memory rate.
+// The two row sums are exchanged through LDS (double-buffered by row parity: one barrier per row).
+// partial[pair][0][:] / [1][:] as above; a pair writes both halves of its partial row.
+template <class T, bool RMS, int NI>
+__global__ __launch_bounds__(128) void norm_bwd_pair_kernel(int rows, int d, const T* __restrict__ dy, const T* __restrict__ x,
+                                                            const T* __restrict__ g, const float* __restrict__ stats,
+                                                            const T* __restrict__ resid, T* __restrict__ dx,
+                                                            float* __restrict__ partial) {
+    __shared__ float red[2][2][2];
+    const int half = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int hd = d / 2, c0 = half * hd;
+    float gg[NI][8], dg[NI][8], db[NI][8];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int col = (lane + 64 * i) * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { dg[i][j] = 0.f; db[i][j] = 0.f; gg[i][j] = 0.f; }
+        if (col < hd) Vec8<T>::load(g + c0 + col, gg[i]);
+    }
+    const float inv_d = 1.0f / (float)d;
+    int par = 0;
+    for (int row = blockIdx.x; row < rows; row += gridDim.x, par ^= 1) {      // both wavefronts: the same rows
+        const float mean = RMS ? 0.f : stats[row];
+        const float rstd = stats[rows + row];
+        const T* dyr = dy + (size_t)row * d + c0;
+        const T* xr = x + (size_t)row * d + c0;
+        float a[NI][8], xh[NI][8];
+        float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int col = (lane + 64 * i) * 8;
+            if (col < hd) {
+                Vec8<T>::load(dyr + col, a[i]);
+                Vec8<T>::load(xr + col, xh[i]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    xh[i][j] = (xh[i][j] - mean) * rstd;
+                    dg[i][j] += a[i][j] * xh[i][j];
+                    db[i][j] += a[i][j];
+                    a[i][j] *= gg[i][j];
+                    c1 += a[i][j];
+                    c2 += a[i][j] * xh[i][j];
+                }
+            }
+        }
+        c1 = wave_sum(c1);
+        c2 = wave_sum(c2);
+        if (lane == 0) { red[par][half][0] = c1; red[par][half][1] = c2; }
+        __syncthreads();
+        c1 = RMS ? 0.f : (red[par][0][0] + red[par][1][0]) * inv_d;
+        c2 = (red[par][0][1] + red[par][1][1]) * inv_d;
+        T* dxr = dx + (size_t)row * d + c0;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int col = (lane + 64 * i) * 8;
+            if (col < hd) {
+                float o[8];
+                if (resid) {
+                    Vec8<T>::load(resid + (size_t)row * d + c0 + col, o);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) o[j] = 0.f;
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) o[j] += rstd * (a[i][j] - c1 - xh[i][j] * c2);
+                Vec8<T>::store(dxr + col, o);
+            }
+        }
+    }
+    float* p0 = partial + (size_t)blockIdx.x * 2 * d + c0;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int col = (lane + 64 * i) * 8;
+        if (col < hd) {
+            Vec8<float>::store(p0 + col, dg[i]);
+            if (!RMS) Vec8<float>::store(p0 + d + col, db[i]);
+        }
+    }
+}
+
 // out[c] = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c];  block = 32 columns x 8 row lanes
 __global__ __launch_bounds__(256) void reduce_partials_kernel(int n_partial, int n, size_t stride,
                                                               const float* __restrict__ partial,
@@ -309,6 +391,16 @@ template <class T, bool RMS>
 ds_status norm_bwd_dispatch(int rows, int d, const T* dy, const T* x, const T* g, const float* stats, const T* resid,
                             T* dx, float* dg, float* db, float* partial, int accumulate, hipStream_t st) {
     const int ni = (d + 511) / 512;
+    if (ni > 4 && d % 16 == 0) {                 // wide rows: a pair of wavefronts per row (see norm_bwd_pair_kernel)
+        const int np = rows < kPartialRows ? rows : kPartialRows;
+        hipLaunchKernelGGL((norm_bwd_pair_kernel<T, RMS, 4>), dim3(np), dim3(128), 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
+        DS_LAUNCH_CHECK();
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32), dim3(256), 0, st, np, d, (size_t)2 * d, partial, dg, accumulate);
+        if (!RMS)
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32), dim3(256), 0, st, np, d, (size_t)2 * d, partial + d, db, accumulate);
+        DS_LAUNCH_CHECK();
+        return DS_OK;
+    }
     int nblk = (rows + 3) / 4;
     if (nblk > kPartialRows / 4) nblk = kPartialRows / 4;
     dim3 grid(nblk), block(256);

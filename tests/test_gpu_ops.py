@@ -198,8 +198,17 @@ def test_attention_cross(dt, force):
 @pytest.mark.parametrize("rms", [False, True])
 @pytest.mark.parametrize("d", [256, 1024, 2048, 4096])
 def test_norm_forward_backward(dt, rms, d):
+    _norm_case(dt, rms, d, 1000 + 3)
+
+
+@pytest.mark.parametrize("dt,rms", [(BF, False), (F32, True)])
+def test_norm_wide_rows_more_rows_than_work_groups(dt, rms):
+    """d = 4096 runs a pair of wavefronts per row; with more rows than work-groups each pair walks several rows."""
+    _norm_case(dt, rms, 4096, 4500)
+
+
+def _norm_case(dt, rms, d, rows):
     rng = np.random.default_rng(6)
-    rows = 1000 + 3
     x = _rnd(rng, (rows, d), dt, 2.0) + (0 if rms else 0.5)
     if dt == BF:
         x = wl.to_bf16_grid(x)
