@@ -381,6 +381,10 @@ int64_t ds_stage_workspace_need(const ds_stage_config* cfg);
  * returns; it allocates nothing.  The first call with a new layout uploads the layout's tables
  * (a few KB) and may wait for the stream to drain; later calls with the same layout do not.
  * Calls on the same stage must not overlap in time (they share the workspace).
+ * A call with the layout of the previous call only enqueues kernels (no copies, no memsets) and may
+ * be captured into a HIP graph; the tables and the attention work lists it relies on stay in the
+ * workspace, so a captured call is valid for replay only as long as no call with another layout
+ * has been made on the stage in between.
  * Errors: DS_EINVAL, DS_ELAYOUT (layout rows / sequences exceed the workspace, or stream kinds
  * do not match the model), DS_EHIP.
  */
