@@ -2,20 +2,19 @@
 // the contraction running over every token of every micro-batch, which is the gradient
 // accumulation across micro-batches).
 //
-// Two kernels:
-//   * gemm_bf16_mfma_kernel — bf16 in, fp32 accumulate on the CDNA4 matrix cores
-//     (v_mfma_f32_32x32x16_bf16).  256x256x64 macro tile, 4 wavefronts of 64 lanes in a 2x2
-//     arrangement, each owning a 128x128 accumulator block (16 MFMA tiles, 256 accumulator
-//     registers per lane).  Operands are staged global -> registers -> LDS (double buffered,
-//     128 KB of the 160 KB LDS) in a [row][k] layout with a 16-byte XOR swizzle so that both
-//     the 16-byte LDS writes and the MFMA fragment reads are bank-conflict free.  Operands
-//     whose contraction index is not contiguous in memory are transposed in registers (8x8
-//     bf16 blocks, v_perm_b32) on their way to LDS, so one kernel body serves NN, NT and TN.
-//     The epilogue goes back through LDS so that global stores (and the residual / activation
-//     reads) are 16-byte per lane and row-contiguous.  Work-group ids are remapped so that each
-//     XCD (own L2) gets a contiguous run of tiles, ordered in groups of 8 tile-rows.
-//   * gemm_generic_kernel — any dtype / shape / stride, plain FMA; the fp32 path and the
-//     fallback for shapes the MFMA kernel does not take.
+// Three kernels:
+//   * gemm_bf16_nt_kernel — the one the stage runs on: bf16 in, fp32 accumulate on the CDNA4 matrix cores
+//     (v_mfma_f32_16x16x32_bf16), operands straight from global memory into LDS, NT form (forward with [N][K]
+//     weight copies, input gradients) and TN form (weight gradients); described where it is defined.
+//   * gemm_bf16_mfma_kernel — the earlier register-staged kernel (v_mfma_f32_32x32x16_bf16, 256x256x64 macro
+//     tile, 4 wavefronts of 128x128): operands go global -> registers -> LDS (double buffered) in a [row][k] layout
+//     with a 16-byte XOR swizzle; operands whose contraction index is not contiguous in memory are transposed in
+//     registers (8x8 bf16 blocks, v_perm_b32) on their way to LDS, so one body serves NN, NT and TN.  Kept for the
+//     operand forms the first kernel does not take (NN; TN with an epilogue other than fp32 accumulation).
+//   * gemm_generic_kernel — any dtype / shape / stride, plain FMA; the fp32 path and the fallback for shapes the
+//     matrix-core kernels do not take.
+// Epilogues go back through LDS so that global stores (and the residual / activation reads) are 16 bytes per lane
+// and row-contiguous.  Work-group ids are remapped so that each XCD (own L2) gets a contiguous run of tiles.
 #include "gemm.hpp"
 
 
@@ -480,22 +479,23 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_mfma_kernel(int M, int N, in
     }
 }
 
-// ---------------------------------------------------------------------------- NT kernel, direct to LDS
-// C[M,N] = A[M,K] * B[N,K]^T, both operands k-contiguous (K % 32 == 0, N % 256 == 0).
+// ---------------------------------------------------------------------------- NT / TN kernel, direct to LDS
+// NT form: C[M,N] = A[M,K] * B[N,K]^T, both operands k-contiguous (K % 64 == 0, N % 256 == 0).
+// TN form: C[M,N] = A[K,M]^T * B[K,N], both operands with the contraction index as the row (weight gradients).
 //
-// 256x256 macro tile, 8 wavefronts (2 per SIMD) in a 2x4 arrangement, each owning a 128x64
-// accumulator block (8 MFMA tiles of 32x32, 128 accumulator registers).  Operands go global -> LDS
-// directly (global_load_lds_dwordx4): no staging registers, no LDS write instructions.  A wavefront
-// instruction deposits 64 x 16 bytes at consecutive LDS addresses, i.e. 16 tile rows of 4 chunks;
-// the XOR swizzle that makes the fragment reads conflict-free is obtained by choosing WHICH global
-// chunk each lane fetches.  K advances in 32-element tiles through a ring of 4 LDS stages (32 KB
-// each): three tiles are in flight while one is consumed.  One barrier per tile; the only
-// vector-memory wait is "at most the two newest tiles outstanding".  Tile indices past the end are
-// clamped (a few redundant loads into a free stage) so that this count is the same at every step.
+// 256x256 macro tile, 8 wavefronts (2 per SIMD) in a 2x4 arrangement, each owning a 128x64 accumulator block:
+// 8 x 4 blocks of v_mfma_f32_16x16x32_bf16, 128 accumulator registers.  Operands go global -> LDS directly
+// (global_load_lds_dwordx4): no staging registers, no LDS write instructions.  A wavefront instruction deposits
+// 64 x 16 bytes at consecutive LDS addresses; the XOR swizzle that makes the fragment reads conflict-free is
+// obtained by choosing WHICH global chunk each lane fetches.  NT: 64-deep K tiles (whole 128-byte lines per row),
+// two 64 KB stages, one barrier per tile.  TN: 32 k-rows of 512 bytes per tile, ring of 4 stages of 32 KB, three
+// tiles in flight while one is consumed, fragments through the LDS transpose read.  Tile indices past the end
+// are clamped (a few redundant loads into a free stage) so that the wait counts are the same at every step.
 //
-// Why 8 wavefronts: measured on MI355X, one 4-wavefront work-group cannot pull more than about
-// 40-50 GB/s from L2 however many loads it keeps in flight, which is what a 256x256x(bf16) tile
-// needs at full MFMA rate; the rate scales with the number of wavefronts on the CU.
+// Why 8 wavefronts: measured on MI355X, one 4-wavefront work-group cannot pull more than about 40-50 GB/s from
+// L2 however many loads it keeps in flight, which is what a 256x256x(bf16) tile needs at full MFMA rate; the rate
+// scales with the number of wavefronts on the CU; and a single wavefront per SIMD cannot keep the matrix pipe
+// busy with the 16x16x32 shape (it needs two issuing).
 constexpr int NT_DK = 32, NT_NS = 4, NT_HALF = 256 * NT_DK * 2, NT_STAGE = 2 * NT_HALF;
 #ifndef NT_WM
 #define NT_WM 2
@@ -621,7 +621,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                 offA[i] = (uint32_t)(((long long)(ra_ - m0) * K + chunk * 8) * 2);
                 offB[i] = (uint32_t)(((long long)row * K + chunk * 8) * 2);
                 krow[i] = 0;
-            } else {                                                // 16-byte unit of the 32 x 32 tile (512-byte rows)
+            } else {                                                // 16-byte unit of the 32 k-row tile (512-byte rows)
                 const int row = u >> 5, pos = u & 31;
                 const int chunk = (((pos >> 1) ^ (row & 7)) << 1) | (pos & 1);
                 offA[i] = (uint32_t)(((long long)row * M + chunk * 8) * 2);
