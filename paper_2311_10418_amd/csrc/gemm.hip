@@ -508,7 +508,7 @@ constexpr int NT_DK = 32, NT_NS = 4, NT_HALF = 256 * NT_DK * 2, NT_STAGE = 2 * N
 #define NT_G2 0
 #endif
 #ifndef TN_PRE
-#define TN_PRE 2
+#define TN_PRE 4
 #endif
 
 // tile number -> tile coordinates: groups of NT_GROUP tile rows, column-major inside a group
