@@ -443,6 +443,16 @@ ds_status ds_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, in
                   const void* A, const void* B, void* C, int32_t epilogue, const void* bias,
                   const void* R, const void* R2, void* C2, const int32_t* row_valid, int32_t accumulate,
                   int32_t force_generic, void* hip_stream);
+/* ds_gemm with a DEVICE float32 workspace of workspace_floats entries (16-byte aligned), which lets the bf16
+ * matrix-core kernels split the contraction the way the stage does: weight-gradient launches (ACC32,
+ * trans_a = 1, trans_b = 0) into K ranges whose partial sums a second kernel adds up in a fixed order, all other
+ * launches for the tiles of their last, partly filled round over the compute units.  The result differs from
+ * ds_gemm's only in the order of fp32 additions; a workspace too small for a split is simply not used.
+ * Calls sharing a workspace must not overlap. */
+ds_status ds_gemm_ws(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
+                     const void* A, const void* B, void* C, int32_t epilogue, const void* bias,
+                     const void* R, const void* R2, void* C2, const int32_t* row_valid, int32_t accumulate,
+                     int32_t force_generic, float* workspace, int64_t workspace_floats, void* hip_stream);
 
 /* Bytes of DEVICE scratch the bf16 matrix-core attention kernels need: the work lists of the call
  * (sequence, 128-row block) in descending order of trip count, and the per-(head, query row)

@@ -27,7 +27,7 @@ _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOM
 EXPORTS = ["dp_plan", "dp_plan_sampled", "dp_plan_replicas", "ds_plan_recompute", "ds_assign_replicas", "ds_cost_table_build", "ds_schedule_adaptive",
            "ds_schedule_1f1b", "ds_schedule_simulate", "ds_comm_plan", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "ds_stage_workspace_need", "stage_fwd_bwd",
-           "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_attention_fwd",
+           "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_gemm_ws", "ds_attention_fwd",
            "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
            "ds_version"]
 
@@ -463,12 +463,18 @@ def ds_unpack(layout, stream_rows, canonical, which=0, stream=None):
 
 
 def ds_gemm(A, B, Cout, M, N, K, trans_a=False, trans_b=False, epilogue=DS_EPI_NONE, bias=None, R=None, R2=None, C2=None,
-            row_valid=None, accumulate=False, force_generic=False, stream=None):
-    rc = lib().ds_gemm(C.c_int32(_dtype_code(A)), C.c_int32(int(trans_a)), C.c_int32(int(trans_b)),
-                       C.c_int32(M), C.c_int32(N), C.c_int32(K), _dp(A), _dp(B), _dp(Cout), C.c_int32(epilogue),
-                       _dp(bias), _dp(R), _dp(R2), _dp(C2), _dp(row_valid), C.c_int32(int(accumulate)),
-                       C.c_int32(int(force_generic)), _stream(stream))
-    _check(rc, "ds_gemm")
+            row_valid=None, accumulate=False, force_generic=False, stream=None, workspace=None):
+    """workspace: optional float32 device tensor that lets the matrix-core kernels split the contraction (ds_gemm_ws)."""
+    args = [C.c_int32(_dtype_code(A)), C.c_int32(int(trans_a)), C.c_int32(int(trans_b)),
+            C.c_int32(M), C.c_int32(N), C.c_int32(K), _dp(A), _dp(B), _dp(Cout), C.c_int32(epilogue),
+            _dp(bias), _dp(R), _dp(R2), _dp(C2), _dp(row_valid), C.c_int32(int(accumulate)),
+            C.c_int32(int(force_generic))]
+    if workspace is None:
+        rc = lib().ds_gemm(*args, _stream(stream))
+        _check(rc, "ds_gemm")
+    else:
+        rc = lib().ds_gemm_ws(*args, _dp(workspace), C.c_int64(workspace.numel()), _stream(stream))
+        _check(rc, "ds_gemm_ws")
 
 
 def ds_attention_fwd(q, k, v, o, lse, q_row, q_len, k_row, k_len, n_heads, head_dim, causal, max_q_len, max_k_len,

@@ -1147,3 +1147,13 @@ extern "C" ds_status ds_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, in
     return launch_gemm(dtype, trans_a, trans_b, M, N, K, A, B, C, epilogue, p, force_generic != 0, nullptr, 0,
                        (hipStream_t)hip_stream);
 }
+
+extern "C" ds_status ds_gemm_ws(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
+                                const void* A, const void* B, void* C, int32_t epilogue, const void* bias, const void* R,
+                                const void* R2, void* C2, const int32_t* row_valid, int32_t accumulate,
+                                int32_t force_generic, float* workspace, int64_t workspace_floats, void* hip_stream) {
+    if (workspace_floats < 0 || (workspace_floats > 0 && (!workspace || ((uintptr_t)workspace & 15)))) return DS_EINVAL;
+    GemmEpi p{bias, R, R2, C2, row_valid, accumulate};
+    return launch_gemm(dtype, trans_a, trans_b, M, N, K, A, B, C, epilogue, p, force_generic != 0,
+                       workspace_floats > 0 ? workspace : nullptr, (size_t)workspace_floats, (hipStream_t)hip_stream);
+}

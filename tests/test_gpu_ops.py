@@ -277,3 +277,71 @@ def test_pack_unpack_roundtrip():
     back = torch.zeros_like(canon)
     ds.ds_unpack(lo, stream, back)
     assert torch.equal(back, canon)
+
+
+# ---- the direct-to-LDS matrix-core kernel (NT / TN forms) at operator level, with and without the split-K workspace
+
+def _ws(floats):
+    return torch.zeros(floats, dtype=F32, device=DEV)
+
+
+@pytest.mark.parametrize("use_ws", [False, True])
+@pytest.mark.parametrize("M,N,K", [(700, 256, 128), (1037, 512, 1024), (5157, 3328, 1024)])
+def test_gemm_nt_epilogues(use_ws, M, N, K):
+    """C = A B^T with B given as [N, K] (forward with transposed weights, input gradients): every epilogue, ragged M,
+    launches with fewer tiles than compute units (all tiles split over K when a workspace is given) and with more
+    (whole rounds unsplit, the remaining tiles split)."""
+    rng = np.random.default_rng(12)
+    A, B = _rnd(rng, (M, K), BF), _rnd(rng, (N, K), BF, 0.1)
+    bias, R, R2 = _rnd(rng, (N,), BF), _rnd(rng, (M, N), BF), _rnd(rng, (M, N), BF)
+    valid = np.where(rng.random(M) < 0.8, 1, -1).astype(np.int32)
+    acc = A.astype(np.float64) @ B.astype(np.float64).T
+    dA, dB, db, dR, dR2 = (to_dev(x, BF) for x in (A, B, bias, R, R2))
+    dvalid = torch.from_numpy(valid).to(DEV)
+    ws = _ws(40 * 256 * 256) if use_ws else None
+    tol = 6e-3
+
+    def run(epi, **kw):
+        c = torch.zeros((M, N), dtype=BF, device=DEV)
+        c2 = torch.zeros((M, N), dtype=BF, device=DEV)
+        ds.ds_gemm(dA, dB, c, M, N, K, trans_b=True, epilogue=epi, C2=c2, workspace=ws, **kw)
+        torch.cuda.synchronize()
+        return to_np(c), to_np(c2)
+
+    c, _ = run(ds.DS_EPI_NONE)
+    assert rel_err(c, acc) <= tol
+    c, _ = run(ds.DS_EPI_NONE, bias=db)
+    assert rel_err(c, acc + bias) <= tol
+    z, a = run(ds.DS_EPI_GELU, bias=db)
+    assert rel_err(z, acc + bias) <= tol and rel_err(a, ost.gelu(acc + bias)) <= tol
+    c, _ = run(ds.DS_EPI_RESID, bias=db, R=dR, row_valid=dvalid)
+    assert rel_err(c, (acc + bias + R) * (valid[:, None] >= 0)) <= tol and np.all(c[valid < 0] == 0)
+    c, _ = run(ds.DS_EPI_DGELU, R=dR)
+    assert rel_err(c, acc * ost.gelu_grad(R.astype(np.float64))) <= tol
+    zu, h = run(ds.DS_EPI_GATE, R=dR)
+    assert rel_err(zu, acc) <= tol and rel_err(h, ost.gelu(R.astype(np.float64)) * acc) <= tol
+    g1, g2 = run(ds.DS_EPI_DGATE, R=dR, R2=dR2)
+    assert rel_err(g1, acc * R2 * ost.gelu_grad(R.astype(np.float64))) <= tol
+    assert rel_err(g2, acc * ost.gelu(R.astype(np.float64))) <= tol
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 768, 2085), (256, 256, 4100), (2048, 2048, 1031)])
+def test_gemm_weight_gradient_split_over_the_contraction(M, N, K):
+    """dW = X^T dY with a workspace: the contraction is cut into ranges (ragged last tile), partial sums added by the
+    second kernel; overwrite and accumulate; same result as the unsplit launch up to summation order."""
+    rng = np.random.default_rng(13)
+    X, dY = _rnd(rng, (K, M), BF), _rnd(rng, (K, N), BF)
+    ref = X.astype(np.float64).T @ dY.astype(np.float64)
+    dX, ddY = to_dev(X, BF), to_dev(dY, BF)
+    ws = _ws(4 * M * N + 4096)
+    Cd = torch.full((M, N), 3.0, dtype=F32, device=DEV)
+    ds.ds_gemm(dX, ddY, Cd, M, N, K, trans_a=True, epilogue=ds.DS_EPI_ACC32, accumulate=False, workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(Cd), ref) <= 1e-5
+    ds.ds_gemm(dX, ddY, Cd, M, N, K, trans_a=True, epilogue=ds.DS_EPI_ACC32, accumulate=True, workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(Cd), 2 * ref) <= 1e-5
+    plain = torch.zeros((M, N), dtype=F32, device=DEV)
+    ds.ds_gemm(dX, ddY, plain, M, N, K, trans_a=True, epilogue=ds.DS_EPI_ACC32, accumulate=False)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(plain), ref) <= 1e-5
