@@ -319,10 +319,17 @@ __global__ __launch_bounds__(128) void norm_bwd_pair_kernel(int rows, int d, con
 }
 
 // out[c] = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c];  block = 32 columns x 8 row lanes
+// blockIdx.y = 1 (when launched with two rows of blocks) reduces a second set of partials into out2.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(int n_partial, int n, size_t stride,
                                                               const float* __restrict__ partial,
-                                                              float* __restrict__ out, int accumulate) {
+                                                              float* __restrict__ out, int accumulate,
+                                                              const float* __restrict__ partial2 = nullptr,
+                                                              float* __restrict__ out2 = nullptr) {
     __shared__ float red[8][33];
+    if (blockIdx.y == 1) {
+        partial = partial2;
+        out = out2;
+    }
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int col = blockIdx.x * 32 + tx;
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
@@ -395,9 +402,9 @@ ds_status norm_bwd_dispatch(int rows, int d, const T* dy, const T* x, const T* g
         const int np = rows < kPartialRows ? rows : kPartialRows;
         hipLaunchKernelGGL((norm_bwd_pair_kernel<T, RMS, 4>), dim3(np), dim3(128), 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
         DS_LAUNCH_CHECK();
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32), dim3(256), 0, st, np, d, (size_t)2 * d, partial, dg, accumulate);
-        if (!RMS)
-            hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32), dim3(256), 0, st, np, d, (size_t)2 * d, partial + d, db, accumulate);
+        // dgamma and, for LayerNorm, dbeta in one launch
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32, RMS ? 1 : 2), dim3(256), 0, st, np, d, (size_t)2 * d, partial, dg,
+                           accumulate, (const float*)(partial + d), db);
         DS_LAUNCH_CHECK();
         return DS_OK;
     }
@@ -410,9 +417,8 @@ ds_status norm_bwd_dispatch(int rows, int d, const T* dy, const T* x, const T* g
     else hipLaunchKernelGGL((norm_bwd_kernel<T, RMS, 8>), grid, block, 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
     DS_LAUNCH_CHECK();
     const int np = nblk * 4;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32), dim3(256), 0, st, np, d, (size_t)2 * d, partial, dg, accumulate);
-    if (!RMS)
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32), dim3(256), 0, st, np, d, (size_t)2 * d, partial + d, db, accumulate);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32, RMS ? 1 : 2), dim3(256), 0, st, np, d, (size_t)2 * d, partial, dg,
+                       accumulate, (const float*)(partial + d), db);
     DS_LAUNCH_CHECK();
     return DS_OK;
 }
@@ -520,7 +526,8 @@ extern "C" ds_status ds_colsum(int32_t dtype, int32_t rows, int32_t n, const voi
     else
         hipLaunchKernelGGL(colsum_kernel<float>, dim3(gx, gy), dim3(256), 0, st, rows, n, (const float*)x, partial);
     DS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((n + 31) / 32), dim3(256), 0, st, gy, n, (size_t)n, partial, out, accumulate);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((n + 31) / 32), dim3(256), 0, st, gy, n, (size_t)n, partial, out, accumulate,
+                       (const float*)nullptr, (float*)nullptr);
     DS_LAUNCH_CHECK();
     return DS_OK;
 }

@@ -317,7 +317,7 @@ struct Ops {
     }
     ds_status norm_bwd(const Stream& sm, int rms, const void* dy, const void* x, const void* g, const float* stats,
                        const void* resid, void* dx, void* dg, void* db) {
-        s->launches += 3;
+        s->launches += 2;
         return timed(s, DS_PROF_NORM, st, [&] {
             return ds_norm_bwd(dt, rms, sm.R, d, dy, x, g, stats, resid, dx, (float*)dg, (float*)db, s->partial, accumulate, st);
         });
