@@ -22,9 +22,10 @@
 // XOR swizzle (applied by choosing which global chunk each lane fetches) that keeps both access
 // patterns free of bank conflicts on the 64-bank LDS.
 //
-// Scheduling.  A small kernel lists the (sequence, 128-row block) work items of a call in descending
-// order of their trip count; the attention grids walk that list, heads fastest, so that long items
-// start first, equal items spread over the XCDs, and no work-group is launched for nothing.
+// Scheduling.  A small kernel lists the (sequence, 128-row block) work items of a call, long sequences
+// first and the blocks of one sequence together; the attention grids walk that list, heads fastest, so
+// that the work-groups sharing a sequence's tiles run on one XCD at the same time (one fetch from HBM per
+// tile instead of one per block) and no work-group is launched for nothing.
 //
 // VALU economy (the matrix pipe is only as fast as the scalar work between its instructions): the
 // softmax scale rides in one FMA with the running max, the accumulator is rescaled only when some
@@ -36,6 +37,7 @@
 // owner: no atomics, results are bit-reproducible.  Sequences are addressed through (row, length)
 // tables, so padding rows cost nothing and packed layouts need no mask.
 #include "attention.hpp"
+#include <type_traits>
 
 namespace {
 
@@ -103,41 +105,44 @@ __device__ __forceinline__ bf16x8_t read_tr(const char* tile, const TrOffsets<HD
     return __builtin_bit_cast(bf16x8_t, v);
 }
 
-// Direct-to-LDS loader of 64-row tiles of one row-major tensor: each wavefront issues HD/32
-// instructions of 64 x 16 bytes per tile; the per-lane source pointers step by 64 rows.
+// Direct-to-LDS loader of 64-row tiles of one row-major tensor: each wavefront issues HD/32 transfers of
+// 64 x 16 bytes per tile.  A transfer is addressed as a wavefront-uniform base (tensor + first row of the tile,
+// scalar arithmetic) plus a 32-bit byte offset per lane; the offsets of a tile whose 64 rows all exist are fixed
+// for the whole kernel, so stepping along the sequence costs no vector instruction.  Only the ragged last tile
+// recomputes them (rows past the end are clamped to the last valid row; the consumers mask the duplicates).
 template <int HD> struct TileLoader {
     static constexpr int PW = HD / 32;
-    const char* p[PW];
-    const bf16_t* base;
-    long long ld;
+    const char* base;
+    long long ld2;                                      // row stride in bytes (64 rows of it fit in 31 bits)
     int n_valid, wave, lane;
-    __device__ __forceinline__ void setup(const bf16_t* base_, long long ld_, int n_valid_, int wave_, int lane_) {
-        base = base_; ld = ld_; n_valid = n_valid_; wave = wave_; lane = lane_;
+    uint32_t off_full[PW];
+    __device__ __forceinline__ static int row_of(int u) { return HD == 128 ? (u >> 4) : (u >> 3); }
+    __device__ __forceinline__ static int chunk_of(int u) {
+        return (HD == 128 ? (u & 15) : (u & 7)) ^ swz<HD>(row_of(u));
     }
-    // rows r0 .. r0+63, clamped to the last valid row (the duplicates are masked by the consumers)
-    __device__ __forceinline__ void seek(int r0) {
+    __device__ __forceinline__ void setup(const bf16_t* base_, long long ld_, int n_valid_, int wave_, int lane_) {
+        base = (const char*)base_; ld2 = ld_ * 2; n_valid = n_valid_; wave = wave_; lane = lane_;
 #pragma unroll
         for (int i = 0; i < PW; ++i) {
             const int u = (wave * PW + i) * 64 + lane;
-            const int row = HD == 128 ? (u >> 4) : (u >> 3);
-            const int chunk = (HD == 128 ? (u & 15) : (u & 7)) ^ swz<HD>(row);
-            int r = r0 + row;
-            r = r < n_valid ? r : n_valid - 1;
-            p[i] = (const char*)(base + (long long)r * ld + chunk * 8);
+            off_full[i] = (uint32_t)(row_of(u) * (int)ld2 + chunk_of(u) * 16);
         }
     }
-    __device__ __forceinline__ void next() {            // only when the next 64 rows are all valid
-        const long long step = 64 * ld * 2;
+    // rows r0 .. r0+63 -> the tile at `lds`; 0 <= r0 < n_valid
+    __device__ __forceinline__ void issue(char* lds, int r0) const {
+        const char* b = base + (long long)r0 * ld2;
+        if (r0 + 64 <= n_valid) {
 #pragma unroll
-        for (int i = 0; i < PW; ++i) p[i] += step;
-    }
-    __device__ __forceinline__ void issue(char* lds) const {
+            for (int i = 0; i < PW; ++i) lds_dma16_s(b, off_full[i], lds + (wave * PW + i) * 1024);
+        } else {
+            const int last = n_valid - 1 - r0;
 #pragma unroll
-        for (int i = 0; i < PW; ++i)
-            lds_dma16(p[i], lds + (wave * PW + i) * 1024);
-    }
-    __device__ __forceinline__ void advance_to(int r0) {
-        if (r0 + 64 <= n_valid) next(); else seek(r0);
+            for (int i = 0; i < PW; ++i) {
+                const int u = (wave * PW + i) * 64 + lane;
+                const int rr = min(row_of(u), last);
+                lds_dma16_s(b, (uint32_t)(rr * (int)ld2 + chunk_of(u) * 16), lds + (wave * PW + i) * 1024);
+            }
+        }
     }
 };
 
@@ -162,8 +167,14 @@ __device__ __forceinline__ void store_cols(const f32x16_t (&acc)[HD / 32], float
 }
 
 // ------------------------------------------------------------------------------------ work lists
-// items[0 .. n): (sequence, block) pairs of `block` rows each, in descending order of the number of
-// 64-row steps the block's work-group will take; n is written to *n_items.  One work-group.
+// items[0 .. n): the (sequence, block) pairs of `block` rows each; n is written to *n_items.  One work-group.
+// Order: sequences by descending trip count of their longest block (a block's trip count = the number of
+// 64-row steps its work-group takes), the blocks of one sequence next to each other, longest first.  The
+// grids walk the list with heads fastest and the hardware deals consecutive work-groups round-robin to the
+// XCDs, so with a head count that is a multiple of the XCD count every block of one (sequence, head) runs on
+// the same XCD at about the same time and streams the same K / V (or Q / dO) tiles: all but the first fetch
+// of a tile hit in that XCD's L2.  Long sequences still start first and the list ends with the shortest, so
+// the grid's tail stays fine-grained.
 __global__ __launch_bounds__(1024) void attn_worklist_kernel(int n_seq, const int32_t* __restrict__ own_len,
                                                              const int32_t* __restrict__ other_len, int causal,
                                                              int key_side, int max_items, int2* __restrict__ items,
@@ -172,23 +183,19 @@ __global__ __launch_bounds__(1024) void attn_worklist_kernel(int n_seq, const in
     __shared__ int hist[NB];
     __shared__ int start[NB];
     const int tid = threadIdx.x;
-    auto steps_of = [&](int own, int other, int blk) {
+    // trip count of the longest block of a sequence: the last query block (it sees every key up to its own
+    // end), the first key block (every query from its own start on), any block when nothing is masked
+    auto longest = [&](int own, int other) {
         int n;
-        if (!key_side) {                               // query block: key steps it visits
-            const int end = causal ? min(other, (blk + 1) * 128) : other;
-            n = (end + 63) >> 6;
-        } else {                                       // key block: query steps it visits
-            const int begin = causal ? blk * 128 : 0;
-            n = (other - begin + 63) >> 6;
-        }
-        (void)own;
+        if (!key_side) n = ((causal ? min(other, ((own + 127) >> 7) * 128) : other) + 63) >> 6;
+        else n = (other + 63) >> 6;
         return min(max(n, 0), NB - 1);
     };
     hist[tid] = 0;
     __syncthreads();
     for (int s = tid; s < n_seq; s += NB) {
-        const int own = own_len[s], other = other_len[s];
-        for (int blk = 0; blk * 128 < own; ++blk) atomicAdd(&hist[steps_of(own, other, blk)], 1);
+        const int own = own_len[s];
+        if (own > 0) atomicAdd(&hist[longest(own, other_len[s])], (own + 127) >> 7);
     }
     __syncthreads();
     if (tid == 0) {
@@ -198,11 +205,12 @@ __global__ __launch_bounds__(1024) void attn_worklist_kernel(int n_seq, const in
     }
     __syncthreads();
     for (int s = tid; s < n_seq; s += NB) {
-        const int own = own_len[s], other = other_len[s];
-        for (int blk = 0; blk * 128 < own; ++blk) {
-            const int pos = atomicAdd(&start[steps_of(own, other, blk)], 1);
-            if (pos < max_items) items[pos] = make_int2(s, blk);
-        }
+        const int own = own_len[s];
+        if (own <= 0) continue;
+        const int nblk = (own + 127) >> 7;
+        const int base = atomicAdd(&start[longest(own, other_len[s])], nblk);
+        for (int j = 0; j < nblk; ++j)
+            if (base + j < max_items) items[base + j] = make_int2(s, (!key_side && causal) ? nblk - 1 - j : j);
     }
 }
 
@@ -251,10 +259,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
     const int kv_end = CAUSAL ? min(kl, q0 + 128) : kl;
     const int wave_last = CAUSAL ? min(kl - 1, qw0 + 31) : kl - 1;     // last key this wavefront can see
     const int nb = (kv_end + 63) / 64;
-    ldK.seek(0);
-    ldV.seek(0);
-    ldK.issue(smem);
-    ldV.issue(smem + TILE);
+    if (nb > 0) {                                       // (a sequence without keys: zero output, nothing to fetch)
+        ldK.issue(smem, 0);
+        ldV.issue(smem + TILE, 0);
+    }
     for (int b = 0; b < nb; ++b) {
         const int kv0 = b * 64;
         char* sK = smem + (b & 1) * (2 * TILE);
@@ -262,10 +270,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
         wait_tiles_and_sync();                          // block b has landed; the other stage is free
         if (b + 1 < nb) {
             char* nK = smem + ((b + 1) & 1) * (2 * TILE);
-            ldK.advance_to(kv0 + 64);
-            ldV.advance_to(kv0 + 64);
-            ldK.issue(nK);
-            ldV.issue(nK + TILE);
+            ldK.issue(nK, kv0 + 64);
+            ldV.issue(nK + TILE, kv0 + 64);
         }
         if (kv0 > wave_last || qw0 >= ql) continue;
 
@@ -363,10 +369,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
     TileLoader<HD> ldK, ldV;
     ldK.setup(K, a.ldk, kl, wave, lane);
     ldV.setup(V, a.ldv, kl, wave, lane);
-    ldK.seek(0);
-    ldV.seek(0);
-    ldK.issue(smem);
-    ldV.issue(smem + TILE);
+    if (kl > 0) {
+        ldK.issue(smem, 0);
+        ldV.issue(smem + TILE, 0);
+    }
 
     bf16x8_t qf[HD / 16], dof[HD / 16];
     float delta = 0.f;                                  // rowsum(dO * O) of this lane's query, this head
@@ -412,10 +418,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
         wait_tiles_and_sync();
         if (b + 1 < nb) {
             char* n = smem + ((b + 1) & 1) * (2 * TILE);
-            ldK.advance_to(kv0 + 64);
-            ldV.advance_to(kv0 + 64);
-            ldK.issue(n);
-            ldV.issue(n + TILE);
+            ldK.issue(n, kv0 + 64);
+            ldV.issue(n + TILE, kv0 + 64);
         }
         if (kv0 > wave_last || qw0 >= ql) continue;
         const bool need_mask = (kv0 + 64 > kl) || (CAUSAL && kv0 + 63 > qw0);
@@ -434,14 +438,20 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
                 pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], pacc, 0, 0, 0);
             }
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[e], c, -lse2));
-                if (need_mask) {
-                    const int key = kv0 + kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                    if (key >= kl || (CAUSAL && key > qi)) p = 0.f;
+            for (int e = 0; e < 16; ++e) sacc[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[e], c, -lse2));   // P^T
+            if (need_mask) {
+                // one real branch around the whole mask (see the forward kernel): tested per element, it would cut
+                // the chain of exponentials into sixteen basic blocks
+                int kbase = kv0 + kt * 32;
+                asm volatile("" : "+s"(kbase));
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int key = kbase + 8 * (e >> 2) + 4 * g + (e & 3);
+                    if (key >= kl || (CAUSAL && key > qi)) sacc[e] = 0.f;
                 }
-                sacc[e] = p * (pacc[e] - delta);                          // dS^T
             }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sacc[e] *= pacc[e] - delta;          // dS^T
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const bf16x8_t dsf = frag_from_acc(sacc, u);
@@ -461,7 +471,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
 // {hi, lo, 0 x 6} of lse/scale and of delta, as the dQ kernel left them).  Three blocks are in flight while one is
 // consumed: with one wavefront per SIMD (368 registers) nothing else hides the latency of the transfers.
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TILE = 64 * HD * 2;
     constexpr int STAGE = 2 * TILE + 2048;
@@ -497,10 +507,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
         char* n = smem + (blk & (NS - 1)) * STAGE;
         const int bc = blk < nb ? blk : nb - 1;
         const int q0 = q_begin + bc * 64;
-        ldQ.seek(q0);
-        ldO.seek(q0);
-        ldQ.issue(n);
-        ldO.issue(n + TILE);
+        ldQ.issue(n, q0);
+        ldO.issue(n + TILE, q0);
         if (wave < 2) {
             int r = q0 + lane;
             r = r < ql ? r : ql - 1;
@@ -538,7 +546,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
     // the K / V fragments (ordinary loads) are complete before the loop: left to the compiler, its waits for them
     // would sit inside the loop as "nothing outstanding", which would also drain the transfers in flight
     __builtin_amdgcn_s_waitcnt(0x0F70);
-    for (int b = 0; b < nb; ++b) {
+    // One step = one 64-query block.  The step exists in two versions, with and without the mask, and the loop is
+    // cut into three: the (at most two) blocks on the diagonal, the blocks in the middle, the ragged last block.  The
+    // middle loop, where the time goes, is then straight code: a mask test inside it, even one that is never taken,
+    // splits the live ranges of the 128 accumulator registers and costs hundreds of register copies per step.
+    const bool wave_has_keys = kw0 < kl;
+    auto step = [&](int b, auto masked_t) {
+        constexpr bool MASKED = decltype(masked_t)::value;
         const int q0 = q_begin + b * 64;
         char* sQ = smem + (b & (NS - 1)) * STAGE;
         char* sdO = sQ + TILE;
@@ -550,11 +564,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
         else __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (2 * (HD / 32))));
         __builtin_amdgcn_s_barrier();
         issue_block(b + 3);
-        if (kw0 >= kl || (CAUSAL && q0 + 63 < kw0)) continue;
-        const bool need_mask = (q0 + 64 > ql) || (CAUSAL && q0 < kw0 + 31);
+        if (!wave_has_keys) return;
+        if (MASKED && CAUSAL && q0 + 63 < kw0) return;
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
-            if (q0 + qt * 32 >= ql || (CAUSAL && q0 + qt * 32 + 31 < kw0)) continue;   // a half with no visible query
+            if (MASKED && (q0 + qt * 32 >= ql || (CAUSAL && q0 + qt * 32 + 31 < kw0))) continue;   // no visible query
             f32x16_t sacc, pacc;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
@@ -575,7 +589,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 float p = __builtin_amdgcn_exp2f(sacc[e] * c);
-                if (need_mask) {
+                if (MASKED) {
                     const int q = q0 + qt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
                     if (q >= ql || (CAUSAL && q < ki)) p = 0.f;
                 }
@@ -595,7 +609,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
                 }
             }
         }
-    }
+    };
+    const int n_diag = CAUSAL ? min(2, nb) : 0;         // causal: queries k0 .. k0+127 meet this block's own keys
+    const int n_full = (ql - q_begin) / 64;             // blocks b < n_full have all their 64 rows
+    int b = 0;
+    for (; b < n_diag; ++b) step(b, std::true_type{});
+    for (; b < n_full; ++b) step(b, std::false_type{});
+    for (; b < nb; ++b) step(b, std::true_type{});
     __builtin_amdgcn_s_waitcnt(0x0F70);                 // no transfer may still be writing LDS when the work-group ends
     if (ki < kl) {
         store_cols<HD>(dkacc, a.scale, (bf16_t*)a.dk + (krow0 + ki) * a.ldk + h * HD, g);
@@ -666,6 +686,8 @@ bool attn_mfma_supported(const AttnArgs& a) {
     if (a.d_o && (!al(a.d_o) || !al(a.dq) || !al(a.dk) || !al(a.dv))) return false;
     if (!a.scratch || !al(a.scratch)) return false;
     if (a.q_total_rows <= 0 || a.k_total_rows <= 0) return false;
+    const long long ld_max = 1LL << 23;                // 64 rows of a tile stay within a 31-bit byte offset
+    if (a.ldq >= ld_max || a.ldk >= ld_max || a.ldv >= ld_max || a.ldo >= ld_max) return false;
     if (a.scratch_bytes < attn_scratch_bytes(a.n_heads, a.head_dim, a.q_total_rows, a.k_total_rows, a.n_seq)) return false;
     if ((long long)items_bound(a.q_total_rows, a.n_seq) * a.n_heads > 0x7fffffffLL) return false;
     if ((long long)items_bound(a.k_total_rows, a.n_seq) * a.n_heads > 0x7fffffffLL) return false;
