@@ -43,6 +43,8 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+// sched_barrier mask: vector ALU, scalar ALU and transcendental instructions may cross, LDS accesses and MFMAs may not
+constexpr int kFence = 0x2 | 0x4 | 0x400;
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
@@ -572,19 +574,32 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
             f32x16_t sacc, pacc;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
+            // S^T and dP^T: NA = HD/16 + 1 contraction slices (the last one is the appended statistics), two MFMAs each.
+            // The fragment reads run AHEAD slices in front of the MFMAs that use them (left alone, the compiler puts
+            // every read right before its MFMA, in the same four registers, and each MFMA waits a full LDS round
+            // trip); the fences keep LDS reads and MFMAs in this order, other instructions may move across.
+            constexpr int NA = HD / 16 + 1, AHEAD = 3;
+            bf16x8_t fq[NA], fo[NA];
+            auto read_a = [&](int i) {
+                if (i < HD / 16) {
+                    const int o = qt * (32 * HD * 2) + rbase + (((i * 2 + g) ^ rsw) << 4);
+                    fq[i] = *reinterpret_cast<const bf16x8_t*>(sQ + o);
+                    fo[i] = *reinterpret_cast<const bf16x8_t*>(sdO + o);
+                } else {
+                    fq[i] = *reinterpret_cast<const bf16x8_t*>(s_lse + (qt * 32 + col) * 16);
+                    fo[i] = *reinterpret_cast<const bf16x8_t*>(s_delta + (qt * 32 + col) * 16);
+                }
+            };
 #pragma unroll
-            for (int ks = 0; ks < HD / 16; ++ks) {
-                const int o = qt * (32 * HD * 2) + rbase + (((ks * 2 + g) ^ rsw) << 4);
-                const bf16x8_t qf = *reinterpret_cast<const bf16x8_t*>(sQ + o);
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ks], sacc, 0, 0, 0);
-                const bf16x8_t dof = *reinterpret_cast<const bf16x8_t*>(sdO + o);
-                pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dof, vf[ks], pacc, 0, 0, 0);
-            }
-            {
-                const bf16x8_t la = *reinterpret_cast<const bf16x8_t*>(s_lse + (qt * 32 + col) * 16);
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(la, neg_ones, sacc, 0, 0, 0);       // score - lse/scale
-                const bf16x8_t da = *reinterpret_cast<const bf16x8_t*>(s_delta + (qt * 32 + col) * 16);
-                pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, neg_ones, pacc, 0, 0, 0);       // dP - delta
+            for (int i = 0; i < AHEAD; ++i) read_a(i);
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                if (i + AHEAD < NA) read_a(i + AHEAD);
+                __builtin_amdgcn_sched_barrier(kFence);
+                // (last slice: score - lse/scale and dP - delta through the constant [-1, -1] operand)
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[i], i < HD / 16 ? kf[i < HD / 16 ? i : 0] : neg_ones, sacc, 0, 0, 0);
+                pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[i], i < HD / 16 ? vf[i < HD / 16 ? i : 0] : neg_ones, pacc, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(kFence);
             }
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
@@ -596,17 +611,25 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
                 sacc[e] = p;                                           // P
                 pacc[e] = p * pacc[e];                                 // dS
             }
+            // dV += dO^T P^T and dK += Q^T dS^T: ND = 2 * HD/32 pairs of MFMAs, transpose reads AHEAD_D pairs in front
+            constexpr int ND = 2 * (HD / 32), AHEAD_D = 2;
+            bf16x8_t td[ND], tq[ND];
+            auto read_d = [&](int j) {
+                td[j] = read_tr<HD>(sdO, tro, 2 * qt + j / (HD / 32), j % (HD / 32));
+                tq[j] = read_tr<HD>(sQ, tro, 2 * qt + j / (HD / 32), j % (HD / 32));
+            };
+            bf16x8_t pf[2], dsf[2];
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const bf16x8_t pf = frag_from_acc(sacc, u);
-                const bf16x8_t dsf = frag_from_acc(pacc, u);
+            for (int u = 0; u < 2; ++u) { pf[u] = frag_from_acc(sacc, u); dsf[u] = frag_from_acc(pacc, u); }
 #pragma unroll
-                for (int dt = 0; dt < HD / 32; ++dt) {
-                    const bf16x8_t dot_f = read_tr<HD>(sdO, tro, 2 * qt + u, dt);
-                    dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot_f, pf, dvacc[dt], 0, 0, 0);
-                    const bf16x8_t qt_f = read_tr<HD>(sQ, tro, 2 * qt + u, dt);
-                    dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt_f, dsf, dkacc[dt], 0, 0, 0);
-                }
+            for (int j = 0; j < AHEAD_D; ++j) read_d(j);
+#pragma unroll
+            for (int j = 0; j < ND; ++j) {
+                if (j + AHEAD_D < ND) read_d(j + AHEAD_D);
+                __builtin_amdgcn_sched_barrier(kFence);
+                dvacc[j % (HD / 32)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td[j], pf[j / (HD / 32)], dvacc[j % (HD / 32)], 0, 0, 0);
+                dkacc[j % (HD / 32)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[j], dsf[j / (HD / 32)], dkacc[j % (HD / 32)], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(kFence);
             }
         }
     };
