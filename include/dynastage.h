@@ -455,7 +455,7 @@ ds_status ds_gemm_ws(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M,
                      int32_t force_generic, float* workspace, int64_t workspace_floats, void* hip_stream);
 
 /* Bytes of DEVICE scratch the bf16 matrix-core attention kernels need: the work lists of the call
- * (sequence, 128-row block) in descending order of trip count, and the per-(head, query row)
+ * (sequence, 128-row block), long sequences first and the blocks of one sequence together, and the per-(head, query row)
  * statistics the dQ kernel hands to the dK/dV kernel.  q_total_rows / k_total_rows: rows of the
  * tensors holding the queries / the keys.  Calls that share one scratch buffer must not overlap. */
 int64_t ds_attention_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t q_total_rows, int32_t k_total_rows,
@@ -467,7 +467,8 @@ int64_t ds_attention_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t q_
  * keys rows k_row[s] .. +k_len[s]-1 of k/v.  mask: 0 = none (bidirectional / cross), 1 = causal.
  * o: [rows, n_heads*head_dim] with row stride ldo; lse: float32 [n_heads, lse_stride].
  * Rows not covered by any sequence are not touched.  q_row etc. are DEVICE int32 arrays; the
- * sequences must not overlap.  scratch (DEVICE, 16-byte aligned, at least
+ * sequences must not overlap; a sequence with q_len[s] = 0 is skipped, one with k_len[s] = 0
+ * gets zero outputs / gradients.  scratch (DEVICE, 16-byte aligned, at least
  * ds_attention_scratch_bytes) enables the bf16 matrix-core kernels; with scratch = NULL, or a
  * shape they do not take, the generic kernels run.  k_total_rows: rows of the k / v tensors (the
  * q / o tensors have lse_stride rows). */
