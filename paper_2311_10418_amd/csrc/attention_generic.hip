@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(AttnArgs a) {
         }
         m = m_new;
     }
-    const float inv = 1.0f / l;
+    const float inv = l > 0.f ? 1.0f / l : 0.f;         // (no keys: zero output)
     T* o = (T*)a.o;
     if (lane < hd) o[qr * a.ldo + h * hd + lane] = from_f32<T>(o0 * inv);
     if (lane + 64 < hd) o[qr * a.ldo + h * hd + lane + 64] = from_f32<T>(o1 * inv);

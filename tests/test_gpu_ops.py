@@ -194,6 +194,59 @@ def test_attention_cross(dt, force):
         assert rel_err(to_np(dkv)[kr[i]:kr[i] + kl[i], d:], rv) <= tol
 
 
+@pytest.mark.parametrize("dt,force", [(F32, True), (BF, True), (BF, False)])
+def test_attention_empty_sequences(dt, force):
+    """q_len = 0: the sequence is skipped.  k_len = 0: its outputs and query gradients are zero, and nothing is
+    fetched for it (its key rows are given as row 0 of the tensor, where a fetch of the row before would fall
+    outside the allocation)."""
+    rng = np.random.default_rng(15)
+    h, hd = 2, 64
+    d = h * hd
+    ql, kl = [0, 37, 130], [50, 0, 140]
+    qr = np.array([0, 4, 60], np.int32)
+    kr = np.array([10, 0, 70], np.int32)
+    Tq, Tk = 200, 220
+    q = _rnd(rng, (Tq, d), dt)
+    kv = _rnd(rng, (Tk, 2 * d), dt)
+    d_o = _rnd(rng, (Tq, d), dt)
+    tq, tkv, tdo = to_dev(q, dt), to_dev(kv, dt), to_dev(d_o, dt)
+    o = torch.full((Tq, d), 7.0, dtype=dt, device=DEV)
+    lse = torch.zeros((h, Tq), dtype=F32, device=DEV)
+    delta = torch.zeros((h, Tq), dtype=F32, device=DEV)
+    dq = torch.full((Tq, d), 7.0, dtype=dt, device=DEV)
+    dkv = torch.zeros((Tk, 2 * d), dtype=dt, device=DEV)
+    es = tq.element_size()
+    i32 = lambda a: torch.tensor(np.asarray(a), dtype=torch.int32, device=DEV)
+    t_qr, t_ql, t_kr, t_kl = i32(qr), i32(ql), i32(kr), i32(kl)
+    kb = tkv.data_ptr()
+    scratch = torch.zeros(ds.ds_attention_scratch_bytes(h, hd, Tq, Tk, 3), dtype=torch.uint8, device=DEV)
+    ds.ds_attention_fwd(tq, kb, kb + d * es, o, lse, t_qr, t_ql, t_kr, t_kl, h, hd, False, max(ql), max(kl),
+                        d, 2 * d, 2 * d, d, Tq, k_total_rows=Tk, scratch=scratch, force_generic=force)
+    gb = dkv.data_ptr()
+    ds.ds_attention_bwd(tq, kb, kb + d * es, o, tdo, lse, delta, dq, gb, gb + d * es, t_qr, t_ql, t_kr, t_kl, h, hd, False,
+                        max(ql), max(kl), d, 2 * d, 2 * d, d, Tq, k_total_rows=Tk, scratch=scratch, force_generic=force)
+    torch.cuda.synchronize()
+    o_np, dq_np, dkv_np = to_np(o), to_np(dq), to_np(dkv)
+    tol = TOL[dt]
+    # the sequence without keys: zeros; rows of no sequence (and of the one without queries): untouched
+    assert np.all(o_np[4:4 + 37] == 0) and np.all(dq_np[4:4 + 37] == 0)
+    untouched = np.ones(Tq, dtype=bool)
+    untouched[4:4 + 37] = False
+    untouched[60:60 + 130] = False
+    assert np.all(o_np[untouched] == 7.0) and np.all(dq_np[untouched] == 7.0)
+    assert np.all(dkv_np[:70] == 0) and np.all(dkv_np[70 + 140:] == 0)       # keys of the query-less sequence get nothing
+    # the ordinary sequence beside them is unaffected
+    qq = q[60:190].astype(np.float64)
+    kk = kv[70:210, :d].astype(np.float64)
+    vv = kv[70:210, d:].astype(np.float64)
+    ref_o, cache = ost.attention_fwd(qq, kk, vv, h, False)
+    rq, rk, rv = ost.attention_bwd(d_o[60:190].astype(np.float64), cache)
+    assert rel_err(o_np[60:190], ref_o) <= tol
+    assert rel_err(dq_np[60:190], rq) <= tol
+    assert rel_err(dkv_np[70:210, :d], rk) <= tol
+    assert rel_err(dkv_np[70:210, d:], rv) <= tol
+
+
 @pytest.mark.parametrize("dt", [F32, BF])
 @pytest.mark.parametrize("rms", [False, True])
 @pytest.mark.parametrize("d", [256, 1024, 2048, 4096])
