@@ -398,9 +398,10 @@ template <class T, bool RMS>
 ds_status norm_bwd_dispatch(int rows, int d, const T* dy, const T* x, const T* g, const float* stats, const T* resid,
                             T* dx, float* dg, float* db, float* partial, int accumulate, hipStream_t st) {
     const int ni = (d + 511) / 512;
-    if (ni > 4 && d % 16 == 0) {                 // wide rows: a pair of wavefronts per row (see norm_bwd_pair_kernel)
+    if (ni > 2 && d % 16 == 0) {                 // wide rows: a pair of wavefronts per row (see norm_bwd_pair_kernel)
         const int np = rows < kPartialRows ? rows : kPartialRows;
-        hipLaunchKernelGGL((norm_bwd_pair_kernel<T, RMS, 4>), dim3(np), dim3(128), 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
+        if (ni > 4) hipLaunchKernelGGL((norm_bwd_pair_kernel<T, RMS, 4>), dim3(np), dim3(128), 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
+        else hipLaunchKernelGGL((norm_bwd_pair_kernel<T, RMS, 2>), dim3(np), dim3(128), 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
         DS_LAUNCH_CHECK();
         // dgamma and, for LayerNorm, dbeta in one launch
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32, RMS ? 1 : 2), dim3(256), 0, st, np, d, (size_t)2 * d, partial, dg,
