@@ -236,7 +236,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(int rows, int d, const T*
     }
 }
 
-// Wide rows (d > 2048): one row per PAIR of wavefronts (a 128-thread work-group), each owning half of the columns, so
+// Wide rows (d > 1024): one row per PAIR of wavefronts (a 128-thread work-group), each owning half of the columns, so
 // that the per-lane state (gain, dgamma / dbeta sums, dy * g, xhat: 5 x 8 x NI floats) still fits two wavefronts per
 // SIMD; with one wavefront per row it needs more than 256 registers and the kernel runs at half the memory rate.
 // The two row sums are exchanged through LDS (double-buffered by row parity: one barrier per row).
