@@ -92,13 +92,15 @@ struct ds_stage {
          *dx1 = nullptr, *dx2 = nullptr, *d_o = nullptr, *dqkv = nullptr, *dqc = nullptr, *dkvc = nullptr, *de = nullptr,
          *deB = nullptr;
     float *delta = nullptr, *partial = nullptr, *split_ws = nullptr;
-    void* attn_scratch = nullptr;           // feature-major copies for the attention kernels
+    // scratch of the matrix-core attention kernels (work lists, backward statistics): one per kind of attention the
+    // model runs (decoder-only: causal self-attention; encoder-decoder: encoder self-, decoder self-, cross-attention)
+    void* attn_scratch[3] = {nullptr, nullptr, nullptr};
     size_t attn_scratch_bytes = 0;
     bool nt_mode = false;
-    // the attention work lists in the scratch depend only on the layout and on which streams / mask they were built
+    // the attention work lists in a scratch depend only on the layout and on which streams / mask they were built
     // for: they are kept across layers and calls while both stay the same
-    uint64_t lists_uid = 0;
-    int lists_kind = -1;
+    uint64_t lists_uid[3] = {0, 0, 0};
+    int lists_kind[3] = {-1, -1, -1};
     size_t split_ws_floats = 0;
     int32_t launches = 0;
     // optional per-kernel-group timing
@@ -205,11 +207,11 @@ void carve(ds_stage* s) {
         s->tgt.seq_len = (int32_t*)ar.take(S * 4);
     }
     const int hd = c.d_model / c.n_heads;
-    s->attn_scratch = nullptr;
     s->attn_scratch_bytes = 0;
+    for (int k = 0; k < 3; ++k) s->attn_scratch[k] = nullptr;
     if (c.dtype == DS_DTYPE_BF16 && (hd == 64 || hd == 128)) {
         s->attn_scratch_bytes = attn_scratch_bytes(c.n_heads, hd, (int)Rm, (int)Rm, (int)S);
-        s->attn_scratch = ar.take(s->attn_scratch_bytes);
+        for (int k = 0; k < (c.model == DS_MODEL_T5 ? 3 : 1); ++k) s->attn_scratch[k] = ar.take(s->attn_scratch_bytes);
     }
     ar.take(4096);
 }
@@ -276,7 +278,7 @@ struct Ops {
     int accumulate;
     int dt, d, F;
     bool nt;
-    int cur_kind = -1;          // of the attention arguments built last
+    int cur_kind = -1, cur_slot = 0;    // of the attention arguments built last
 
     ds_status gemm_raw(int cat, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C, int epi,
                        const void* bias, const void* R, const void* R2, void* C2, const int32_t* row_valid, int acc) {
@@ -352,20 +354,23 @@ struct Ops {
         a.ldo = d;
         a.lse_stride = q.R;
         a.scale = 1.0f / std::sqrt((float)hd);
-        a.scratch = s->attn_scratch;
-        a.scratch_bytes = s->attn_scratch_bytes;
         a.q_total_rows = q.R;
         a.k_total_rows = k.R;
         cur_kind = (&q == &s->tgt ? 1 : 0) | (&k == &s->tgt ? 2 : 0) | (mask ? 4 : 0);
+        // scratch 0: self-attention over the main stream, 1: self-attention over the target stream, 2: cross-attention
+        cur_slot = s->cfg.model != DS_MODEL_T5 ? 0 : (&q != &s->tgt ? 0 : (&k == &s->tgt ? 1 : 2));
+        a.scratch = s->attn_scratch[cur_slot];
+        a.scratch_bytes = s->attn_scratch_bytes;
         a.lists_want_both = 1;
-        a.lists_ready = (s->lists_uid != 0 && s->lists_uid == s->bound_uid && s->lists_kind == cur_kind) ? 1 : 0;
+        a.lists_ready = (s->lists_uid[cur_slot] != 0 && s->lists_uid[cur_slot] == s->bound_uid &&
+                         s->lists_kind[cur_slot] == cur_kind) ? 1 : 0;
         return a;
     }
     // after a launch that went through the matrix-core kernels: the scratch now holds both lists of this kind
     void lists_built(const AttnArgs& a) {
         if (attn_mfma_supported(a)) {
-            s->lists_uid = s->bound_uid;
-            s->lists_kind = cur_kind;
+            s->lists_uid[cur_slot] = s->bound_uid;
+            s->lists_kind[cur_slot] = cur_kind;
         }
     }
     // self-attention over a packed [rows, 3d] tensor
