@@ -236,19 +236,19 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(int rows, int d, const T*
     }
 }
 
-// Wide rows (d > 1024): one row per PAIR of wavefronts (a 128-thread work-group), each owning half of the columns, so
-// that the per-lane state (gain, dgamma / dbeta sums, dy * g, xhat: 5 x 8 x NI floats) still fits two wavefronts per
-// SIMD; with one wavefront per row it needs more than 256 registers and the kernel runs at half the memory rate.
-// The two row sums are exchanged through LDS (double-buffered by row parity: one barrier per row).
-// partial[pair][0][:] / [1][:] as above; a pair writes both halves of its partial row.
-template <class T, bool RMS, int NI>
-__global__ __launch_bounds__(128) void norm_bwd_pair_kernel(int rows, int d, const T* __restrict__ dy, const T* __restrict__ x,
-                                                            const T* __restrict__ g, const float* __restrict__ stats,
-                                                            const T* __restrict__ resid, T* __restrict__ dx,
-                                                            float* __restrict__ partial) {
-    __shared__ float red[2][2][2];
-    const int half = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int hd = d / 2, c0 = half * hd;
+// Wide rows (d > 1024): one row per group of NW = 2 or 4 wavefronts (one work-group), each owning d / NW of the
+// columns, so that the per-lane state (gain, dgamma / dbeta sums, dy * g, xhat: 5 x 8 x NI floats) leaves room for
+// four wavefronts per SIMD; with one wavefront per row of 4096 columns it needs more than 256 registers and the
+// kernel runs at half the memory rate.  The partial row sums are exchanged through LDS (double-buffered by row
+// parity: one barrier per row).  partial[group][0][:] / [1][:] as above; a group writes all slices of its partial row.
+template <class T, bool RMS, int NI, int NW>
+__global__ __launch_bounds__(64 * NW) void norm_bwd_multi_kernel(int rows, int d, const T* __restrict__ dy, const T* __restrict__ x,
+                                                                 const T* __restrict__ g, const float* __restrict__ stats,
+                                                                 const T* __restrict__ resid, T* __restrict__ dx,
+                                                                 float* __restrict__ partial) {
+    __shared__ float red[2][NW][2];
+    const int part = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int hd = d / NW, c0 = part * hd;
     float gg[NI][8], dg[NI][8], db[NI][8];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(128) void norm_bwd_pair_kernel(int rows, int d, con
     }
     const float inv_d = 1.0f / (float)d;
     int par = 0;
-    for (int row = blockIdx.x; row < rows; row += gridDim.x, par ^= 1) {      // both wavefronts: the same rows
+    for (int row = blockIdx.x; row < rows; row += gridDim.x, par ^= 1) {      // all wavefronts: the same rows
         const float mean = RMS ? 0.f : stats[row];
         const float rstd = stats[rows + row];
         const T* dyr = dy + (size_t)row * d + c0;
@@ -285,10 +285,14 @@ __global__ __launch_bounds__(128) void norm_bwd_pair_kernel(int rows, int d, con
         }
         c1 = wave_sum(c1);
         c2 = wave_sum(c2);
-        if (lane == 0) { red[par][half][0] = c1; red[par][half][1] = c2; }
+        if (lane == 0) { red[par][part][0] = c1; red[par][part][1] = c2; }
         __syncthreads();
-        c1 = RMS ? 0.f : (red[par][0][0] + red[par][1][0]) * inv_d;
-        c2 = (red[par][0][1] + red[par][1][1]) * inv_d;
+        c1 = 0.f;
+        c2 = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) { c1 += red[par][w][0]; c2 += red[par][w][1]; }    // the same order in every wavefront
+        c1 = RMS ? 0.f : c1 * inv_d;
+        c2 *= inv_d;
         T* dxr = dx + (size_t)row * d + c0;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
@@ -398,10 +402,10 @@ template <class T, bool RMS>
 ds_status norm_bwd_dispatch(int rows, int d, const T* dy, const T* x, const T* g, const float* stats, const T* resid,
                             T* dx, float* dg, float* db, float* partial, int accumulate, hipStream_t st) {
     const int ni = (d + 511) / 512;
-    if (ni > 2 && d % 16 == 0) {                 // wide rows: a pair of wavefronts per row (see norm_bwd_pair_kernel)
+    if (ni > 2 && d % 32 == 0) {                 // wide rows: two or four wavefronts per row (see norm_bwd_multi_kernel)
         const int np = rows < kPartialRows ? rows : kPartialRows;
-        if (ni > 4) hipLaunchKernelGGL((norm_bwd_pair_kernel<T, RMS, 4>), dim3(np), dim3(128), 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
-        else hipLaunchKernelGGL((norm_bwd_pair_kernel<T, RMS, 2>), dim3(np), dim3(128), 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
+        if (ni > 4) hipLaunchKernelGGL((norm_bwd_multi_kernel<T, RMS, 2, 4>), dim3(np), dim3(256), 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
+        else hipLaunchKernelGGL((norm_bwd_multi_kernel<T, RMS, 2, 2>), dim3(np), dim3(128), 0, st, rows, d, dy, x, g, stats, resid, dx, partial);
         DS_LAUNCH_CHECK();
         // dgamma and, for LayerNorm, dbeta in one launch
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((d + 31) / 32, RMS ? 1 : 2), dim3(256), 0, st, np, d, (size_t)2 * d, partial, dg,
