@@ -146,6 +146,9 @@ ds_status launch_mask_rows(int32_t dtype, int32_t rows, int32_t d, const void* i
                            const int32_t* row_valid, hipStream_t st);
 ds_status launch_gather_rows(int32_t dtype, int32_t out_rows, int32_t d, const void* in, void* out,
                              const int32_t* src_row, hipStream_t st);
+// out[c] = (accumulate ? out[c] : 0) + sum over p < n_partial of partial[p * n + c]   (float32, fixed summation order)
+ds_status launch_reduce_partials(int32_t n_partial, int32_t n, const float* partial, float* out, int32_t accumulate,
+                                 hipStream_t st);
 // out[c][r] = in[r][c] (bf16); out leading dimension rows_pad, columns rows..rows_pad-1 zero-filled
 ds_status launch_transpose_bf16(int32_t rows, int32_t cols, int32_t rows_pad, const void* in, void* out, hipStream_t st);
 ds_status launch_scatter_rows(int32_t dtype, int32_t in_rows, int32_t d, const void* in, void* out,

@@ -517,6 +517,15 @@ extern "C" ds_status ds_norm_bwd(int32_t dtype, int32_t rms, int32_t rows, int32
     return norm_bwd_dispatch<float, false>(rows, d, (const float*)dy, (const float*)x, (const float*)g, stats, (const float*)resid, (float*)dx, dg, db, partial, accumulate, st);
 }
 
+ds_status launch_reduce_partials(int32_t n_partial, int32_t n, const float* partial, float* out, int32_t accumulate,
+                                 hipStream_t st) {
+    if (n_partial <= 0 || n <= 0 || !partial || !out) return DS_EINVAL;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((n + 31) / 32), dim3(256), 0, st, n_partial, n, (size_t)n, partial, out, accumulate,
+                       (const float*)nullptr, (float*)nullptr);
+    DS_LAUNCH_CHECK();
+    return DS_OK;
+}
+
 extern "C" ds_status ds_colsum(int32_t dtype, int32_t rows, int32_t n, const void* x, float* out, float* partial,
                                int32_t accumulate, void* hip_stream) {
     if (rows <= 0 || n <= 0 || n % 8 || !x || !out || !partial) return DS_EINVAL;

@@ -874,6 +874,11 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
             return;
         }
     }
+    // column sums of what this lane writes (DGELU: the bias gradient of the layer below comes out of this kernel
+    // instead of a pass over the stored tensor); every lane finishes TM * NPSS rows of the same 8 columns
+    float csum[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) csum[j] = 0.f;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         if (epilogue_reads<EPI>() && direct && !PRE_ALL) prefetch_pass(i);
@@ -904,10 +909,26 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                     Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
                 } else if (epilogue_reads<EPI>()) {
                     epilogue8<bf16_t, EPI>(m, n, N, v, C, p, &pre[i][pss]);
+                    if constexpr (EPI == DS_EPI_DGELU) {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) csum[j] += v[j];
+                    }
                 } else {
                     epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
                 }
             }
+        }
+    }
+    if constexpr (EPI == DS_EPI_DGELU) {
+        if (direct && p.colsum) {
+            // lanes l, l + LPR, l + 2 LPR, ... hold the same columns: fold them, then one row of partial sums per
+            // (tile row, wavefront row), written whether or not the wavefront had a valid row
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) csum[j] += __shfl_xor(csum[j], o, 64);
+            if (lane < LPR)
+                Vec8<float>::store(p.colsum + (size_t)(tile_m * WM + wm) * N + n0 + wn * (TN * 32) + rd_col, csum);
         }
     }
 }
@@ -916,14 +937,19 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
 template <int EPI>
 __global__ __launch_bounds__(256) void tail_finish_kernel(int M, int N, int tiles_m, int tiles_n, int n_main, int tail_splits,
                                                           const float* __restrict__ ws, bf16_t* __restrict__ C, GemmEpi p) {
+    // block x of gridDim.x owns 256 / gridDim.x consecutive rows of the tile; a thread 8 columns of every 8th of them
     const int tile = blockIdx.y;
     int tile_m, tile_n;
     nt_tile_coords(n_main + tile, tiles_m, tiles_n, tile_m, tile_n);
     const float* base = ws + (size_t)tile * tail_splits * (BM * BN);
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < BM * (BN / 8); i += gridDim.x * blockDim.x) {
-        const int r = i / (BN / 8), c8 = (i % (BN / 8)) * 8;
-        const int m = tile_m * BM + r, n = tile_n * BN + c8;
-        if (m >= M) continue;
+    const int rpb = BM / gridDim.x;
+    const int c8 = (threadIdx.x & 31) * 8, n = tile_n * BN + c8;
+    float csum[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) csum[j] = 0.f;
+    for (int r = blockIdx.x * rpb + (threadIdx.x >> 5); r < (blockIdx.x + 1) * rpb; r += 8) {
+        const int m = tile_m * BM + r;
+        if (m >= M) break;
         float v[8];
         Vec8<float>::load(base + (size_t)r * BN + c8, v);
         for (int sp = 1; sp < tail_splits; ++sp) {
@@ -933,6 +959,24 @@ __global__ __launch_bounds__(256) void tail_finish_kernel(int M, int N, int tile
             for (int j = 0; j < 8; ++j) v[j] += w[j];
         }
         epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
+        if constexpr (EPI == DS_EPI_DGELU) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) csum[j] += v[j];
+        }
+    }
+    if constexpr (EPI == DS_EPI_DGELU) {
+        // column sums of the tile's two 128-row halves, in the rows of p.colsum the main kernel's work-groups would
+        // have written had they finished this tile themselves (launched with two blocks per tile in that case)
+        __shared__ float red[8][BN];
+        if (p.colsum) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) red[threadIdx.x >> 5][c8 + j] = csum[j];
+            __syncthreads();
+            float t = 0.f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) t += red[k][threadIdx.x];
+            p.colsum[(size_t)(tile_m * 2 + blockIdx.x) * N + tile_n * BN + threadIdx.x] = t;
+        }
     }
 }
 
@@ -1081,8 +1125,9 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
         hipLaunchKernelGGL(splitk_finish_kernel<EPI>, dim3((int)g), dim3(256), 0, st, M, N, splits, split_ws, (bf16_t*)C, p);
         DS_LAUNCH_CHECK();
     } else if (tail_splits > 1) {
-        hipLaunchKernelGGL(tail_finish_kernel<EPI>, dim3(8, tiles - n_main), dim3(256), 0, st, M, N, tiles_m, tiles_n, n_main,
-                           tail_splits, split_ws, (bf16_t*)C, p);
+        const bool with_sums = EPI == DS_EPI_DGELU && p.colsum;      // then one block per 128-row half of a tile
+        hipLaunchKernelGGL(tail_finish_kernel<EPI>, dim3(with_sums ? 2 : 8, tiles - n_main), dim3(256), 0, st, M, N, tiles_m,
+                           tiles_n, n_main, tail_splits, split_ws, (bf16_t*)C, p);
         DS_LAUNCH_CHECK();
     }
     return DS_OK;
@@ -1109,6 +1154,15 @@ ds_status dispatch_epi(int dtype, int ta, int tb, int M, int N, int K, const voi
 }
 
 }  // namespace
+
+bool gemm_colsum_fused(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int32_t N, int32_t K, const void* A, const void* B,
+                       const void* C, int32_t epilogue) {
+    // the conditions under which dispatch_epi takes launch_nt<DS_EPI_DGELU, false>
+    static_assert(NT_WM == 2, "two rows of partial column sums per tile row");
+    if (epilogue != DS_EPI_DGELU || dtype != DS_DTYPE_BF16 || ta || !tb) return false;
+    if (N % BN || K % BK || M < 1 || K < 1) return false;
+    return ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && ((uintptr_t)C % 16 == 0);
+}
 
 // Shared with the stage driver.
 ds_status launch_gemm(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int32_t N, int32_t K, const void* A, const void* B,

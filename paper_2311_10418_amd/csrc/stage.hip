@@ -92,6 +92,7 @@ struct ds_stage {
          *dx1 = nullptr, *dx2 = nullptr, *d_o = nullptr, *dqkv = nullptr, *dqc = nullptr, *dkvc = nullptr, *de = nullptr,
          *deB = nullptr;
     float *delta = nullptr, *partial = nullptr, *split_ws = nullptr;
+    float* colsum_rows = nullptr;      // partial column sums written by the GELU-backward GEMM epilogue (decoder-only stage)
     // scratch of the matrix-core attention kernels (work lists, backward statistics): one per kind of attention the
     // model runs (decoder-only: causal self-attention; encoder-decoder: encoder self-, decoder self-, cross-attention)
     void* attn_scratch[3] = {nullptr, nullptr, nullptr};
@@ -196,6 +197,7 @@ void carve(ds_stage* s) {
     }
     const size_t partial_floats = std::max<size_t>((size_t)ds_norm_bwd_scratch_floats(1, (int)d), (size_t)2048 * 1024);
     s->partial = f32(partial_floats);
+    s->colsum_rows = (c.model == DS_MODEL_GPT && s->nt_mode) ? f32(gemm_colsum_rows((int32_t)R) * F) : nullptr;
     s->split_ws_floats = 4 * std::max(d * 3 * d, d * F);
     s->split_ws = f32(s->split_ws_floats);
     s->main.row_valid = (int32_t*)ar.take(R * 4);
@@ -281,9 +283,10 @@ struct Ops {
     int cur_kind = -1, cur_slot = 0;    // of the attention arguments built last
 
     ds_status gemm_raw(int cat, int ta, int tb, int M, int N, int K, const void* A, const void* B, void* C, int epi,
-                       const void* bias, const void* R, const void* R2, void* C2, const int32_t* row_valid, int acc) {
+                       const void* bias, const void* R, const void* R2, void* C2, const int32_t* row_valid, int acc,
+                       float* colsum_rows = nullptr) {
         return timed(s, cat, st, [&] {
-            GemmEpi p{bias, R, R2, C2, row_valid, acc};
+            GemmEpi p{bias, R, R2, C2, row_valid, acc, colsum_rows};
             s->launches++;
             return launch_gemm(dt, ta, tb, M, N, K, A, B, C, epi, p, false, s->split_ws, s->split_ws_floats, st);
         });
@@ -299,6 +302,21 @@ struct Ops {
     ds_status dgrad(const Stream& sm, int K, int N, const void* dY, const void* W, void* C, int epi, const void* R,
                     const void* R2, void* C2) {
         return gemm_raw(DS_PROF_GEMM_DGRAD, 0, 1, sm.R, K, N, dY, W, C, epi, nullptr, R, R2, C2, nullptr, 0);
+    }
+    // dZ[rows,K] = (dY W^T) * GELU'(Z) and bias_grad[K] (+)= column sums of dZ.  Where the GEMM kernel can, the sums come
+    // out of its epilogue (one partial row per 128 rows, then a small reduction); otherwise from a pass over dZ.
+    ds_status dgrad_gelu_bias(const Stream& sm, int K, int N, const void* dY, const void* W, void* dZ, const void* Z,
+                              void* bias_grad) {
+        if (s->colsum_rows && gemm_colsum_fused(dt, 0, 1, sm.R, K, N, dY, W, dZ, DS_EPI_DGELU)) {
+            DS_TRY(gemm_raw(DS_PROF_GEMM_DGRAD, 0, 1, sm.R, K, N, dY, W, dZ, DS_EPI_DGELU, nullptr, Z, nullptr, nullptr, nullptr, 0,
+                            s->colsum_rows));
+            s->launches++;
+            return timed(s, DS_PROF_COLSUM, st, [&] {
+                return launch_reduce_partials((int32_t)gemm_colsum_rows(sm.R), K, s->colsum_rows, (float*)bias_grad, accumulate, st);
+            });
+        }
+        DS_TRY(dgrad(sm, K, N, dY, W, dZ, DS_EPI_DGELU, Z, nullptr, nullptr));
+        return colsum(sm, K, dZ, bias_grad);
     }
     // dW[K,N] (+)= X[rows,K]^T dY[rows,N]
     ds_status wgrad(const Stream& sm, int K, int N, const void* X, const void* dY, void* dW) {
@@ -462,9 +480,8 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         // MLP
         DS_TRY(op.wgrad(sm, F, d, b.a, dy, g[l].w_2));
         DS_TRY(op.colsum(sm, d, dy, g[l].b_2));
-        DS_TRY(op.dgrad(sm, F, d, dy, w[l].w_2, s->dz, DS_EPI_DGELU, b.z, nullptr, nullptr));
+        DS_TRY(op.dgrad_gelu_bias(sm, F, d, dy, w[l].w_2, s->dz, b.z, g[l].b_1));
         DS_TRY(op.wgrad(sm, d, F, b.u2, s->dz, g[l].w_1));
-        DS_TRY(op.colsum(sm, F, s->dz, g[l].b_1));
         DS_TRY(op.dgrad(sm, d, F, s->dz, w[l].w_1, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr));
         DS_TRY(op.norm_bwd(sm, 0, s->du, b.x1, w[l].ln2_g, b.stats2, dy, s->dx1, g[l].ln2_g, g[l].ln2_b));
         // attention
