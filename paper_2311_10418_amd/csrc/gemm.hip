@@ -937,19 +937,14 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
 template <int EPI>
 __global__ __launch_bounds__(256) void tail_finish_kernel(int M, int N, int tiles_m, int tiles_n, int n_main, int tail_splits,
                                                           const float* __restrict__ ws, bf16_t* __restrict__ C, GemmEpi p) {
-    // block x of gridDim.x owns 256 / gridDim.x consecutive rows of the tile; a thread 8 columns of every 8th of them
     const int tile = blockIdx.y;
     int tile_m, tile_n;
     nt_tile_coords(n_main + tile, tiles_m, tiles_n, tile_m, tile_n);
     const float* base = ws + (size_t)tile * tail_splits * (BM * BN);
-    const int rpb = BM / gridDim.x;
-    const int c8 = (threadIdx.x & 31) * 8, n = tile_n * BN + c8;
-    float csum[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) csum[j] = 0.f;
-    for (int r = blockIdx.x * rpb + (threadIdx.x >> 5); r < (blockIdx.x + 1) * rpb; r += 8) {
-        const int m = tile_m * BM + r;
-        if (m >= M) break;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < BM * (BN / 8); i += gridDim.x * blockDim.x) {
+        const int r = i / (BN / 8), c8 = (i % (BN / 8)) * 8;
+        const int m = tile_m * BM + r, n = tile_n * BN + c8;
+        if (m >= M) continue;
         float v[8];
         Vec8<float>::load(base + (size_t)r * BN + c8, v);
         for (int sp = 1; sp < tail_splits; ++sp) {
@@ -959,24 +954,48 @@ __global__ __launch_bounds__(256) void tail_finish_kernel(int M, int N, int tile
             for (int j = 0; j < 8; ++j) v[j] += w[j];
         }
         epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
-        if constexpr (EPI == DS_EPI_DGELU) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) csum[j] += v[j];
-        }
     }
-    if constexpr (EPI == DS_EPI_DGELU) {
-        // column sums of the tile's two 128-row halves, in the rows of p.colsum the main kernel's work-groups would
-        // have written had they finished this tile themselves (launched with two blocks per tile in that case)
-        __shared__ float red[8][BN];
-        if (p.colsum) {
+}
+
+// The same with the column sums of the output (p.colsum): one block of 1024 threads per 128-row half of a tile, which
+// writes the row of p.colsum the main kernel's work-groups would have written had they finished the tile themselves.
+template <int EPI>
+__global__ __launch_bounds__(1024) void tail_finish_sums_kernel(int M, int N, int tiles_m, int tiles_n, int n_main, int tail_splits,
+                                                                const float* __restrict__ ws, bf16_t* __restrict__ C, GemmEpi p) {
+    __shared__ float red[32][BN];
+    const int tile = blockIdx.y;
+    int tile_m, tile_n;
+    nt_tile_coords(n_main + tile, tiles_m, tiles_n, tile_m, tile_n);
+    const float* base = ws + (size_t)tile * tail_splits * (BM * BN);
+    const int c8 = (threadIdx.x & 31) * 8, n = tile_n * BN + c8;
+    float csum[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) red[threadIdx.x >> 5][c8 + j] = csum[j];
-            __syncthreads();
-            float t = 0.f;
+    for (int j = 0; j < 8; ++j) csum[j] = 0.f;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) t += red[k][threadIdx.x];
-            p.colsum[(size_t)(tile_m * 2 + blockIdx.x) * N + tile_n * BN + threadIdx.x] = t;
+    for (int k = 0; k < 4; ++k) {                   // 4 x 32 rows; independent iterations, their loads in flight together
+        const int r = blockIdx.x * 128 + k * 32 + (threadIdx.x >> 5);
+        const int m = tile_m * BM + r;
+        if (m >= M) continue;
+        float v[8];
+        Vec8<float>::load(base + (size_t)r * BN + c8, v);
+        for (int sp = 1; sp < tail_splits; ++sp) {
+            float w[8];
+            Vec8<float>::load(base + ((size_t)sp * BM + r) * BN + c8, w);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] += w[j];
         }
+        epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) csum[j] += v[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[threadIdx.x >> 5][c8 + j] = csum[j];
+    __syncthreads();
+    if (threadIdx.x < BN) {
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) t += red[k][threadIdx.x];
+        p.colsum[(size_t)(tile_m * 2 + blockIdx.x) * N + tile_n * BN + threadIdx.x] = t;
     }
 }
 
@@ -1125,9 +1144,17 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
         hipLaunchKernelGGL(splitk_finish_kernel<EPI>, dim3((int)g), dim3(256), 0, st, M, N, splits, split_ws, (bf16_t*)C, p);
         DS_LAUNCH_CHECK();
     } else if (tail_splits > 1) {
-        const bool with_sums = EPI == DS_EPI_DGELU && p.colsum;      // then one block per 128-row half of a tile
-        hipLaunchKernelGGL(tail_finish_kernel<EPI>, dim3(with_sums ? 2 : 8, tiles - n_main), dim3(256), 0, st, M, N, tiles_m,
-                           tiles_n, n_main, tail_splits, split_ws, (bf16_t*)C, p);
+        bool with_sums = false;
+        if constexpr (EPI == DS_EPI_DGELU) {
+            if (p.colsum) {
+                with_sums = true;
+                hipLaunchKernelGGL(tail_finish_sums_kernel<EPI>, dim3(2, tiles - n_main), dim3(1024), 0, st, M, N, tiles_m, tiles_n,
+                                   n_main, tail_splits, split_ws, (bf16_t*)C, p);
+            }
+        }
+        if (!with_sums)
+            hipLaunchKernelGGL(tail_finish_kernel<EPI>, dim3(8, tiles - n_main), dim3(256), 0, st, M, N, tiles_m, tiles_n,
+                               n_main, tail_splits, split_ws, (bf16_t*)C, p);
         DS_LAUNCH_CHECK();
     }
     return DS_OK;
