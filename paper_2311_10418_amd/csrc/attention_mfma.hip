@@ -45,6 +45,8 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 // sched_barrier mask: vector ALU, scalar ALU and transcendental instructions may cross, LDS accesses and MFMAs may not
 constexpr int kFence = 0x2 | 0x4 | 0x400;
+// how many fragment reads (forward) / pairs of reads (dQ) run in front of the MFMAs that use them
+constexpr int FWD_AHEAD = 4, DQ_AHEAD = 2;
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
@@ -282,13 +284,24 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) sacc[kt][e] = 0.f;
+        {
+            // fragment reads FWD_AHEAD MFMAs in front of their use, the order pinned by fences (see the dK/dV kernel)
+            constexpr int NF = 2 * (HD / 16);
+            bf16x8_t fk[NF];
+            auto read_k = [&](int i) {
+                const int ks = i >> 1, kt = i & 1;
+                fk[i] = *reinterpret_cast<const bf16x8_t*>(sK + kt * (32 * HD * 2) + rbase + (((ks * 2 + g) ^ rsw) << 4));
+            };
 #pragma unroll
-        for (int ks = 0; ks < HD / 16; ++ks)
+            for (int i = 0; i < FWD_AHEAD; ++i) read_k(i);
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sK + kt * (32 * HD * 2) + rbase + (((ks * 2 + g) ^ rsw) << 4));
-                sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kt], 0, 0, 0);
+            for (int i = 0; i < NF; ++i) {
+                if (i + FWD_AHEAD < NF) read_k(i + FWD_AHEAD);
+                __builtin_amdgcn_sched_barrier(kFence);
+                sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[i], qf[i >> 1], sacc[i & 1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(kFence);
             }
+        }
         const bool need_mask = (kv0 + 64 > kl) || (CAUSAL && kv0 + 63 > qw0);
         if (need_mask) {
             // the volatile statement keeps the whole mask computation inside a real branch: hoisted or if-converted,
@@ -431,13 +444,24 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
             f32x16_t sacc, pacc;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
+            {
+                constexpr int NF = HD / 16;
+                bf16x8_t fk[NF], fv[NF];
+                auto read_kv = [&](int ks) {
+                    const int o = kt * (32 * HD * 2) + rbase + (((ks * 2 + g) ^ rsw) << 4);
+                    fk[ks] = *reinterpret_cast<const bf16x8_t*>(sK + o);
+                    fv[ks] = *reinterpret_cast<const bf16x8_t*>(sV + o);
+                };
 #pragma unroll
-            for (int ks = 0; ks < HD / 16; ++ks) {
-                const int o = kt * (32 * HD * 2) + rbase + (((ks * 2 + g) ^ rsw) << 4);
-                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sK + o);
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
-                const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(sV + o);
-                pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], pacc, 0, 0, 0);
+                for (int ks = 0; ks < DQ_AHEAD; ++ks) read_kv(ks);
+#pragma unroll
+                for (int ks = 0; ks < NF; ++ks) {
+                    if (ks + DQ_AHEAD < NF) read_kv(ks + DQ_AHEAD);
+                    __builtin_amdgcn_sched_barrier(kFence);
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[ks], qf[ks], sacc, 0, 0, 0);
+                    pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[ks], dof[ks], pacc, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(kFence);
+                }
             }
 #pragma unroll
             for (int e = 0; e < 16; ++e) sacc[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[e], c, -lse2));   // P^T
