@@ -495,7 +495,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
 // ------------------------------------------------------------------------------------ backward: dK, dV
 // LDS, a ring of four stages of: Q tile, dO tile ([64][HD]) and the two statistics tiles ([64 rows][8] bf16:
 // {hi, lo, 0 x 6} of lse/scale and of delta, as the dQ kernel left them).  Three blocks are in flight while one is
-// consumed: with one wavefront per SIMD (368 registers) nothing else hides the latency of the transfers.
+// consumed: with one wavefront per SIMD (about 370 registers) nothing else hides the latency of the transfers.
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
