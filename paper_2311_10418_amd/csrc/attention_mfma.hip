@@ -592,6 +592,77 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
         issue_block(b + 3);
         if (!wave_has_keys) return;
         if (MASKED && CAUSAL && q0 + 63 < kw0) return;
+        if constexpr (!MASKED) {
+            // Middle blocks: the two 32-query halves software-pipelined.  The exp / product work of half 0 sits between
+            // the MFMAs of half 1's first products, that of half 1 between the MFMAs of half 0's second products, so
+            // that the one wavefront of this SIMD keeps the matrix pipe and the vector ALU busy at the same time.
+            constexpr int NA = HD / 16 + 1, AHEAD = 3, ND = 2 * (HD / 32), AHEAD_D = 2;
+            f32x16_t sa[2], pa[2];
+            bf16x8_t fq[NA], fo[NA], td[ND], tq[ND], pf[2], dsf[2];
+            auto read_a = [&](int qt, int i) {
+                if (i < HD / 16) {
+                    const int o = qt * (32 * HD * 2) + rbase + (((i * 2 + g) ^ rsw) << 4);
+                    fq[i] = *reinterpret_cast<const bf16x8_t*>(sQ + o);
+                    fo[i] = *reinterpret_cast<const bf16x8_t*>(sdO + o);
+                } else {
+                    fq[i] = *reinterpret_cast<const bf16x8_t*>(s_lse + (qt * 32 + col) * 16);
+                    fo[i] = *reinterpret_cast<const bf16x8_t*>(s_delta + (qt * 32 + col) * 16);
+                }
+            };
+            auto softmax2 = [&](int qt, int e0) {         // two elements of half qt: P and dS in place
+#pragma unroll
+                for (int e = e0; e < e0 + 2; ++e) {
+                    const float p = __builtin_amdgcn_exp2f(sa[qt][e] * c);
+                    sa[qt][e] = p;
+                    pa[qt][e] = p * pa[qt][e];
+                }
+            };
+            auto phase_a = [&](int qt, bool with_prev) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) { sa[qt][e] = 0.f; pa[qt][e] = 0.f; }
+#pragma unroll
+                for (int i = 0; i < AHEAD; ++i) read_a(qt, i);
+#pragma unroll
+                for (int i = 0; i < NA; ++i) {
+                    if (i + AHEAD < NA) read_a(qt, i + AHEAD);
+                    __builtin_amdgcn_sched_barrier(kFence);
+                    sa[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[i], i < HD / 16 ? kf[i < HD / 16 ? i : 0] : neg_ones, sa[qt], 0, 0, 0);
+                    pa[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[i], i < HD / 16 ? vf[i < HD / 16 ? i : 0] : neg_ones, pa[qt], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(kFence);
+                    if (with_prev && i < NA - 1) {          // 16 / (NA - 1) elements of the other half per slice
+#pragma unroll
+                        for (int e = i * (16 / (NA - 1)); e < (i + 1) * (16 / (NA - 1)); e += 2) softmax2(qt ^ 1, e);
+                    }
+                }
+            };
+            auto phase_d = [&](int qt, bool with_next) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) { pf[u] = frag_from_acc(sa[qt], u); dsf[u] = frag_from_acc(pa[qt], u); }
+                auto read_d = [&](int j) {
+                    td[j] = read_tr<HD>(sdO, tro, 2 * qt + j / (HD / 32), j % (HD / 32));
+                    tq[j] = read_tr<HD>(sQ, tro, 2 * qt + j / (HD / 32), j % (HD / 32));
+                };
+#pragma unroll
+                for (int j = 0; j < AHEAD_D; ++j) read_d(j);
+#pragma unroll
+                for (int j = 0; j < ND; ++j) {
+                    if (j + AHEAD_D < ND) read_d(j + AHEAD_D);
+                    __builtin_amdgcn_sched_barrier(kFence);
+                    dvacc[j % (HD / 32)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td[j], pf[j / (HD / 32)], dvacc[j % (HD / 32)], 0, 0, 0);
+                    dkacc[j % (HD / 32)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[j], dsf[j / (HD / 32)], dkacc[j % (HD / 32)], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(kFence);
+                    if (with_next) {
+#pragma unroll
+                        for (int e = j * (16 / ND); e < (j + 1) * (16 / ND); e += 2) softmax2(qt ^ 1, e);
+                    }
+                }
+            };
+            phase_a(0, false);
+            phase_a(1, true);          // + exp / products of half 0
+            phase_d(0, true);          // + exp / products of half 1
+            phase_d(1, false);
+            return;
+        }
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
             if (MASKED && (q0 + qt * 32 >= ql || (CAUSAL && q0 + qt * 32 + 31 < kw0))) continue;   // no visible query
