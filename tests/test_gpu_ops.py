@@ -249,7 +249,7 @@ def test_attention_empty_sequences(dt, force):
 
 @pytest.mark.parametrize("dt", [F32, BF])
 @pytest.mark.parametrize("rms", [False, True])
-@pytest.mark.parametrize("d", [256, 1024, 2048, 4096])
+@pytest.mark.parametrize("d", [256, 1024, 1536, 2048, 3072, 4096])
 def test_norm_forward_backward(dt, rms, d):
     _norm_case(dt, rms, d, 1000 + 3)
 
