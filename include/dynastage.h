@@ -406,6 +406,16 @@ enum { DS_PROF_GEMM_FWD = 0, DS_PROF_GEMM_DGRAD = 1, DS_PROF_GEMM_WGRAD = 2, DS_
 ds_status ds_stage_profile_enable(ds_stage* stage, int32_t enable);
 ds_status ds_stage_profile_read(ds_stage* stage, float* ms, int32_t* count);
 
+/* Weights that do not change between calls (section "Pipeline Execution Schedule": a stage runs the
+ * micro-batches of an iteration one after the other on the same weights).  For bf16 stages
+ * stage_fwd_bwd keeps a transposed copy of every weight matrix in its workspace and normally makes
+ * it anew in every call.  unchanged = 1 is the caller's promise that the following calls are given
+ * the same weight arrays with the same contents as the previous call: the copies are then reused
+ * (they are still made when the stage has none yet, or the array of layer structs passed differs
+ * in address from the previous call's).  Set it back to 0 after every optimizer step.  Default 0.
+ * Errors: DS_EINVAL (null stage). */
+ds_status ds_stage_weights_unchanged(ds_stage* stage, int32_t unchanged);
+
 /* Rough count of the kernels one stage_fwd_bwd call launches (diagnostics). */
 int32_t ds_stage_last_launch_count(const ds_stage* stage);
 

@@ -27,7 +27,7 @@ _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOM
 EXPORTS = ["dp_plan", "dp_plan_sampled", "dp_plan_replicas", "ds_plan_recompute", "ds_assign_replicas", "ds_cost_table_build", "ds_schedule_adaptive",
            "ds_schedule_1f1b", "ds_schedule_simulate", "ds_comm_plan", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "ds_stage_workspace_need", "stage_fwd_bwd",
-           "ds_stage_last_launch_count", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_gemm_ws", "ds_attention_fwd",
+           "ds_stage_last_launch_count", "ds_stage_weights_unchanged", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_gemm_ws", "ds_attention_fwd",
            "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
            "ds_version"]
 
@@ -395,6 +395,10 @@ class Stage:
 
     def last_launch_count(self):
         return lib().ds_stage_last_launch_count(self.handle)
+
+    def weights_unchanged(self, unchanged=True):
+        """Promise that the following calls get the weights of the previous call, contents included."""
+        _check(lib().ds_stage_weights_unchanged(self.handle, C.c_int32(int(unchanged))), "ds_stage_weights_unchanged")
 
     def profile_enable(self, on=True):
         _check(lib().ds_stage_profile_enable(self.handle, C.c_int32(int(on))), "ds_stage_profile_enable")

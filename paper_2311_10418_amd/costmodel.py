@@ -43,7 +43,7 @@ def power_of_two_grid(lo, hi):
 class StageRunner:
     """A GPT stage with seeded random weights and row buffers; runs any layout on a row range."""
 
-    def __init__(self, cfg, max_rows, max_seqs, seed=0, device="cuda:0", recompute=0):
+    def __init__(self, cfg, max_rows, max_seqs, seed=0, device="cuda:0", recompute=0, same_weights=False):
         import torch
         self.torch = torch
         d, F, L, H = cfg["d_model"], cfg["d_ff"], cfg["n_layers"], cfg["n_heads"]
@@ -70,6 +70,9 @@ class StageRunner:
         self.dx = torch.empty_like(self.x)
         self.stage = ds.Stage(ds.DS_MODEL_GPT, ds.DS_DTYPE_BF16 if bf16 else ds.DS_DTYPE_F32, L, d, H, F,
                               max_rows=max_rows, max_seqs=max_seqs, recompute=recompute)
+        if same_weights:
+            # every call is a micro-batch of one iteration: the stage keeps its transposed weight copies
+            self.stage.weights_unchanged(True)
 
     def run(self, layout, row0=0, accumulate=False):
         r1 = row0 + layout.total_rows
@@ -184,7 +187,7 @@ def report(config="gpt_2048_bf16", seed=0, reps=3, log=None):
     b_grid = power_of_two_grid(1, tb)
     poly = ds.dp_plan(lens, ds.make_cost_model(), cap, c)
     max_rows = int(max(poly.total_rows, 2 * cap))
-    runner = StageRunner(cfg, max_rows=max_rows, max_seqs=max(len(lens), b_grid[-1]), seed=seed)
+    runner = StageRunner(cfg, max_rows=max_rows, max_seqs=max(len(lens), b_grid[-1]), seed=seed, same_weights=True)
     # profile up to twice the cap: every bracketing corner of an admissible (b, L) has b*L <= 4*cap, and the
     # interpolation marks cells whose corners were skipped as unaffordable only beyond b*L > cap
     t_ms = profile_grid(runner, b_grid, l_grid, max_rows=max_rows, reps=reps, log=log)
@@ -198,7 +201,7 @@ def report(config="gpt_2048_bf16", seed=0, reps=3, log=None):
     need = max([int(prof.total_rows)] + [int(l.total_rows) for l in tb_plans.values()])
     if need > max_rows:                                 # plans that merge micro-batches pad: they need more rows
         runner.close()
-        runner = StageRunner(cfg, max_rows=need, max_seqs=max(len(lens), b_grid[-1]), seed=seed)
+        runner = StageRunner(cfg, max_rows=need, max_seqs=max(len(lens), b_grid[-1]), seed=seed, same_weights=True)
     out = {
         "config": config, "n_seq": int(len(lens)), "non_pad_tokens": int(lens.sum()), "cap": cap, "num_stages": c,
         "b_grid": b_grid, "l_grid": l_grid,

@@ -104,6 +104,9 @@ struct ds_stage {
     int lists_kind[3] = {-1, -1, -1};
     size_t split_ws_floats = 0;
     int32_t launches = 0;
+    // transposed weight copies: whose weights they were made from, and whether the caller promised those stay as they are
+    bool weights_unchanged = false;
+    std::vector<char> wt_key;          // the layer structs (device pointers) the copies were made from; empty = no copies
     // optional per-kernel-group timing
     bool prof_on = false;
     std::vector<hipEvent_t> ev_pool;
@@ -424,7 +427,10 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
     const int d = s->cfg.d_model, F = s->cfg.d_ff, L = s->cfg.n_layers;
     const Stream& sm = s->main;
     Ops op{s, st, accumulate, s->cfg.dtype, d, F, s->nt_mode};
-    if (op.nt) {
+    const size_t key_bytes = sizeof(ds_gpt_layer) * (size_t)L;
+    const bool copies_valid = s->weights_unchanged && s->wt_key.size() == key_bytes && std::memcmp(s->wt_key.data(), w, key_bytes) == 0;
+    if (op.nt && !copies_valid) {
+        s->wt_key.clear();
         DS_TRY(timed(s, DS_PROF_TRANSPOSE, st, [&] {
             for (int l = 0; l < L; ++l) {
                 GptBufs& b = s->gpt[l];
@@ -435,6 +441,7 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
             }
             return DS_OK;
         }));
+        s->wt_key.assign((const char*)w, (const char*)w + key_bytes);
     }
 
     // ---------------- forward (ForwardPass of every micro-batch)
@@ -552,7 +559,11 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
     const Stream& E = s->main;
     const Stream& D = s->tgt;
     Ops op{s, st, accumulate, s->cfg.dtype, d, F, s->nt_mode};
-    if (op.nt) {
+    const size_t key_e = sizeof(ds_t5_enc_layer) * (size_t)Le, key_d = sizeof(ds_t5_dec_layer) * (size_t)Ld;
+    const bool copies_valid = s->weights_unchanged && s->wt_key.size() == key_e + key_d &&
+                              std::memcmp(s->wt_key.data(), we, key_e) == 0 && std::memcmp(s->wt_key.data() + key_e, wd, key_d) == 0;
+    if (op.nt && !copies_valid) {
+        s->wt_key.clear();
         DS_TRY(timed(s, DS_PROF_TRANSPOSE, st, [&] {
             for (int l = 0; l < Le; ++l) {
                 T5Bufs& b = s->enc[l];
@@ -575,6 +586,8 @@ ds_status t5_fwd_bwd(ds_stage* s, const ds_t5_enc_layer* we, const ds_t5_dec_lay
             }
             return DS_OK;
         }));
+        s->wt_key.assign((const char*)we, (const char*)we + key_e);
+        s->wt_key.insert(s->wt_key.end(), (const char*)wd, (const char*)wd + key_d);
     }
 
     // ---------------- forward: encoder layers over the input stream
@@ -776,6 +789,12 @@ extern "C" void ds_stage_destroy(ds_stage* s) {
     if (s->h_tables) (void)hipHostFree(s->h_tables);
     if (s->ws) (void)hipFree(s->ws);
     delete s;
+}
+
+extern "C" ds_status ds_stage_weights_unchanged(ds_stage* s, int32_t unchanged) {
+    if (!s) return DS_EINVAL;
+    s->weights_unchanged = unchanged != 0;
+    return DS_OK;
 }
 
 extern "C" ds_status ds_stage_profile_enable(ds_stage* s, int32_t enable) {

@@ -97,6 +97,45 @@ def test_weight_gradients_accumulate_across_calls():
     stage.close()
 
 
+def test_weight_copies_are_reused_only_under_the_callers_promise():
+    """Micro-batches of one iteration run on the same weights: with the promise the transposed copies are made once."""
+    from helpers import params_to_dev, stream_from_seqs, to_np
+    cfg, lens, params, xs, dys = _small_case(True, n_seq=12)
+    lo = ds.dp_plan(lens, ds.make_cost_model(fixed=2_000_000), cfg["cap"], cfg["num_stages"])
+    d = cfg["d_model"]
+    stage = ds.Stage(ds.DS_MODEL_GPT, ds.DS_DTYPE_BF16, cfg["n_layers"], d, cfg["n_heads"], cfg["d_ff"],
+                     max_rows=lo.total_rows, max_seqs=64)
+    w = params_to_dev(params, torch.bfloat16)
+    x = stream_from_seqs(xs, lo, d, torch.bfloat16, 0.0)
+    dy = stream_from_seqs(dys, lo, d, torch.bfloat16, 0.0)
+
+    def call():
+        out, dx = torch.empty_like(x), torch.empty_like(x)
+        g = [{k: torch.zeros(v.shape, dtype=torch.float32, device=x.device) for k, v in layer.items()} for layer in w]
+        ds.stage_fwd_bwd(stage, lo, w, x, dy, out, dx, g)
+        torch.cuda.synchronize()
+        return to_np(out), to_np(dx), stage.last_launch_count()
+
+    call()                                       # (the first call of a layout also builds the attention work lists)
+    out0, dx0, n0 = call()
+    stage.weights_unchanged(True)
+    out1, dx1, n1 = call()                       # first call under the promise: same weights as before, copies reused
+    assert n1 == n0 - 4 * cfg["n_layers"]
+    assert np.array_equal(out0, out1) and np.array_equal(dx0, dx1)
+    # an optimizer step: the promise is withdrawn, the new weights are seen
+    stage.weights_unchanged(False)
+    for layer in w:
+        layer["w_2"].mul_(0.5)
+    out2, _, n2 = call()
+    assert n2 == n0 and not np.array_equal(out0, out2)
+    # under the promise again, but with other weight tensors: the copies are made anew all the same
+    stage.weights_unchanged(True)
+    w = params_to_dev(params, torch.bfloat16)
+    out3, dx3, n3 = call()
+    assert n3 == n0 and np.array_equal(out0, out3) and np.array_equal(dx0, dx3)
+    stage.close()
+
+
 def test_layout_too_large_for_workspace_is_rejected():
     cfg, lens, params, xs, dys = _small_case(True, n_seq=6)
     lo = ds.ds_layout_from_cuts(lens, list(range(len(lens) + 1)))
