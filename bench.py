@@ -239,7 +239,7 @@ def main():
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "config": {"workload": args.config, "model": "%d layers d_model %d heads %d d_ff %d causal" % (L, d, H, F),
+        "config": {"workload": args.config, "stage_shape": "%d layers d_model %d heads %d d_ff %d" % (L, d, H, F),
                    "layout": layout_desc, "n_seq": int(len(lens)), "non_pad_tokens": tokens, "rows": int(all_rows),
                    "n_micro_batches": int(layout.n_mb), "padding_efficiency": tokens / all_rows,
                    "dp_plan_ms": plan_ms, "recompute": args.recompute, "workspace_gb": round(workspace_gb, 3),
