@@ -235,10 +235,11 @@ def main():
         traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
 
     result = {
-        "metric": "non-pad tokens/s, stage fwd+bwd bf16 on 1 MI355X",
+        "metric": "non-pad tokens/s, stage fwd+bwd bf16 on 1 MI355X; MFMA util % of peak",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "mfma_util_pct_of_peak": 100.0 * useful_util,      # second part of the metric: useful flops of the whole step
         "config": {"workload": args.config, "stage_shape": "%d layers d_model %d heads %d d_ff %d" % (L, d, H, F),
                    "layout": layout_desc, "n_seq": int(len(lens)), "non_pad_tokens": tokens, "rows": int(all_rows),
                    "n_micro_batches": int(layout.n_mb), "padding_efficiency": tokens / all_rows,
