@@ -106,11 +106,12 @@ def _varlen_case(rng, lens, h, hd, dt, cross_lens=None):
 
 
 @pytest.mark.parametrize("dt,force", [(F32, True), (BF, True), (BF, False)])
-@pytest.mark.parametrize("hd,causal", [(64, True), (128, True), (64, False)])
+@pytest.mark.parametrize("hd,causal", [(64, True), (128, True), (64, False), (128, False)])
 def test_attention_self(dt, force, hd, causal):
     rng = np.random.default_rng(4)
     h = 2
-    lens = [1, 7, 64, 65, 130, 200, 333, 700]
+    # lengths on both sides of every tile boundary (64-row steps, 128-row blocks), a few long ones for the middle steps
+    lens = [1, 7, 63, 64, 65, 127, 128, 129, 130, 191, 192, 193, 200, 256, 257, 333, 700]
     d, T, rows, qkv, d_o = _varlen_case(rng, lens, h, hd, dt)
     dq = to_dev(qkv, dt)
     o = torch.zeros((T, d), dtype=dt, device=DEV)
