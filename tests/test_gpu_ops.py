@@ -158,10 +158,10 @@ def test_attention_cross(dt, force):
     rng = np.random.default_rng(5)
     h, hd = 2, 64
     d = h * hd
-    ql, kl = [3, 40, 129], [70, 5, 260]
-    qr = np.array([0, 5, 50], np.int32)
-    kr = np.array([2, 80, 90], np.int32)
-    Tq, Tk = 200, 360
+    ql, kl = [3, 40, 129, 200, 64], [70, 5, 260, 700, 1000]      # the last two: many key steps / many query steps per block
+    qr = np.array([0, 5, 50, 190, 400], np.int32)
+    kr = np.array([2, 80, 90, 360, 1070], np.int32)
+    Tq, Tk = 470, 2080
     q = _rnd(rng, (Tq, d), dt)
     kv = _rnd(rng, (Tk, 2 * d), dt)
     d_o = _rnd(rng, (Tq, d), dt)
@@ -175,7 +175,7 @@ def test_attention_cross(dt, force):
     i32 = lambda a: torch.tensor(np.asarray(a), dtype=torch.int32, device=DEV)
     t_qr, t_ql, t_kr, t_kl = i32(qr), i32(ql), i32(kr), i32(kl)
     kb = tkv.data_ptr()
-    scratch = torch.zeros(ds.ds_attention_scratch_bytes(h, hd, Tq, Tk, 3), dtype=torch.uint8, device=DEV)
+    scratch = torch.zeros(ds.ds_attention_scratch_bytes(h, hd, Tq, Tk, len(ql)), dtype=torch.uint8, device=DEV)
     ds.ds_attention_fwd(tq, kb, kb + d * es, o, lse, t_qr, t_ql, t_kr, t_kl, h, hd, False, max(ql), max(kl),
                         d, 2 * d, 2 * d, d, Tq, k_total_rows=Tk, scratch=scratch, force_generic=force)
     gb = dkv.data_ptr()
@@ -183,7 +183,7 @@ def test_attention_cross(dt, force):
                         max(ql), max(kl), d, 2 * d, 2 * d, d, Tq, k_total_rows=Tk, scratch=scratch, force_generic=force)
     torch.cuda.synchronize()
     tol = TOL[dt]
-    for i in range(3):
+    for i in range(len(ql)):
         qq = q[qr[i]:qr[i] + ql[i]].astype(np.float64)
         kk = kv[kr[i]:kr[i] + kl[i], :d].astype(np.float64)
         vv = kv[kr[i]:kr[i] + kl[i], d:].astype(np.float64)
