@@ -35,6 +35,8 @@ def test_argument_checks_without_a_gpu():
     assert lib.stage_fwd_bwd(None, None, None, None, None, None, None, 0, None) == ds.DS_EINVAL
     assert lib.ds_gemm(1, 0, 0, 0, 8, 8, None, None, None, 0, None, None, None, None, None, 0, 0, None) == ds.DS_EINVAL
     assert lib.ds_norm_fwd(1, 0, 4, 7, None, None, None, None, None, None) == ds.DS_EINVAL
+    assert lib.ds_stage_weights_unchanged(None, 1) == ds.DS_EINVAL
+    assert lib.ds_attention_scratch_bytes(0, 64, 8, 8, 1) == 0
     cfg = ds.ds_stage_config(ds.DS_MODEL_GPT, ds.DS_DTYPE_BF16, 1, 0, 100, 3, 64, 16, 0, 4)   # 100 % 3 != 0
     h = ctypes.c_void_p()
     assert lib.ds_stage_create(ctypes.byref(cfg), ctypes.byref(h)) == ds.DS_EINVAL
