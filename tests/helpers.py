@@ -21,6 +21,47 @@ def rel_err(got, ref):
     return num / den if den > 0 else num
 
 
+def max_err(got, ref):
+    """Largest elementwise deviation in units of the reference tensor's root mean square."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = np.sqrt(np.mean(ref.ravel() ** 2)) if ref.size else 0.0
+    dev = np.max(np.abs(got - ref)) if ref.size else 0.0
+    return dev / rms if rms > 0 else dev
+
+
+MAX_FACTOR = 8.0       # elementwise companion of a normwise bound tol: max|got - ref| <= MAX_FACTOR * tol * rms(ref)
+
+
+def both_err(got, ref):
+    """max(normwise relative error, largest elementwise deviation / (MAX_FACTOR * rms(ref))): `both_err(...) <= tol`
+    asserts the normwise bound and its elementwise companion at once."""
+    return max(rel_err(got, ref), max_err(got, ref) / MAX_FACTOR)
+
+
+def check(got, ref, tol, tag=""):
+    """One tensor against the oracle: normwise relative error <= tol AND every element within
+    MAX_FACTOR * tol * rms(ref) (a wrong column slice, row or tile cannot hide inside the norm of a large tensor).
+    Returns the normwise error."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (tag, got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), (tag, "non-finite values")
+    e, m = rel_err(got, ref), max_err(got, ref)
+    assert e <= tol, (tag, "normwise", e, tol)
+    assert m <= MAX_FACTOR * tol, (tag, "elementwise", m, MAX_FACTOR * tol)
+    return e
+
+
+def check_seqs(got_seqs, ref_seqs, tol, tag=""):
+    """Per-sequence tensors (outputs, input gradients): every sequence on its own meets the bound."""
+    assert len(got_seqs) == len(ref_seqs), tag
+    worst = 0.0
+    for i, (g, r) in enumerate(zip(got_seqs, ref_seqs)):
+        worst = max(worst, check(g, r, tol, "%s seq %d len %d" % (tag, i, np.asarray(r).shape[0])))
+    return worst
+
+
 def to_dev(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV).to(dtype).contiguous()
 

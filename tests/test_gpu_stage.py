@@ -1,7 +1,8 @@
 """GPU parity of stage_fwd_bwd against the per-sequence float64 oracle, through the C ABI.
 
-Bar: normwise relative error per tensor (each output, each input gradient, each weight gradient)
-<= 1e-4 for fp32 and <= 2e-2 for bf16 storage; padding rows of the outputs exactly zero; results
+Bar: normwise relative error <= 1e-4 for fp32 and <= 2e-2 for bf16 storage, for the outputs and input
+gradients of EVERY SEQUENCE on its own and for each weight-gradient tensor, each with the elementwise
+companion bound of helpers.check; padding rows of the outputs exactly zero; results
 independent of the micro-batch layout (DP plan, padded DP plan, fixed padding, packing,
 single-sequence micro-batches), with NaN planted in every padding row of the inputs."""
 import numpy as np
@@ -11,7 +12,7 @@ import torch
 from oracle import stage as ost
 from paper_2311_10418_amd import binding as ds
 from paper_2311_10418_amd import workload as wl
-from helpers import cat, rel_err, run_gpt_stage
+from helpers import check, check_seqs, rel_err, run_gpt_stage
 
 pytestmark = pytest.mark.gpu
 
@@ -41,14 +42,13 @@ def _oracle(key, xs, dys, params, h):
 def _compare(tag, got, ref, tol):
     outs, dxs, grads, pad_o, pad_dx = got
     r_outs, r_dxs, r_grads = ref
-    errs = {"act_out": rel_err(cat(outs), cat(r_outs)), "grad_in": rel_err(cat(dxs), cat(r_dxs))}
+    # outputs and input gradients: every sequence on its own; weight gradients: every tensor; each normwise AND elementwise
+    errs = {"act_out": check_seqs(outs, r_outs, tol, tag + " act_out"), "grad_in": check_seqs(dxs, r_dxs, tol, tag + " grad_in")}
     for li, layer in enumerate(r_grads):
         for k, v in layer.items():
-            errs["L%d.%s" % (li, k)] = rel_err(grads[li][k], v)
+            errs["L%d.%s" % (li, k)] = check(grads[li][k], v, tol, "%s L%d.%s" % (tag, li, k))
     worst = max(errs, key=errs.get)
     print(tag, "worst", worst, "%.3e" % errs[worst])
-    for k, e in errs.items():
-        assert e <= tol, (tag, k, e)
     assert pad_o.size == 0 or np.all(pad_o == 0), tag
     assert pad_dx.size == 0 or np.all(pad_dx == 0), tag
     return errs
@@ -89,7 +89,7 @@ def test_weight_gradients_accumulate_across_calls():
     got = run_gpt_stage(lo, cfg, params, xs, dys, ds.DS_DTYPE_BF16, stage=stage, grads=grads, accumulate=True)
     for li, layer in enumerate(ref[2]):
         for k, v in layer.items():
-            assert rel_err(got[2][li][k], 2 * v) <= 2e-2, (li, k)
+            check(got[2][li][k], 2 * v, 2e-2, "accumulated L%d.%s" % (li, k))
     # same stage object, another layout right after: tables are re-bound
     lo2 = ds.ds_layout_from_cuts(lens, list(range(len(lens) + 1)))
     got2 = run_gpt_stage(lo2, cfg, params, xs, dys, ds.DS_DTYPE_BF16, stage=stage)

@@ -8,7 +8,7 @@ import pytest
 from oracle import stage as ost
 from paper_2311_10418_amd import binding as ds
 from paper_2311_10418_amd import workload as wl
-from helpers import cat, rel_err, run_t5_stage
+from helpers import check, check_seqs, run_t5_stage
 
 pytestmark = pytest.mark.gpu
 
@@ -38,15 +38,15 @@ def test_t5_stage_matches_oracle(dtype_code):
     assert layouts[0][1].total_rows > layouts[0][1].total_tokens          # the plan really pads
     for name, lo in layouts:
         got = run_t5_stage(lo, CFG, ep, dp, ex, dx, ddy, dtype_code)
-        errs = {"dec_out": rel_err(cat(got["outs"]), cat(r_outs)), "d_enc_in": rel_err(cat(got["d_enc"]), cat(r_denc)),
-                "d_dec_in": rel_err(cat(got["d_dec"]), cat(r_ddec))}
+        # every sample on its own, every weight-gradient tensor; normwise and elementwise (helpers.check)
+        errs = {"dec_out": check_seqs(got["outs"], r_outs, tol, name + " dec_out"),
+                "d_enc_in": check_seqs(got["d_enc"], r_denc, tol, name + " d_enc_in"),
+                "d_dec_in": check_seqs(got["d_dec"], r_ddec, tol, name + " d_dec_in")}
         for tag, gg, rr in (("enc", got["eg"], r_eg), ("dec", got["dg"], r_dg)):
             for li, layer in enumerate(rr):
                 for k, v in layer.items():
-                    errs["%s%d.%s" % (tag, li, k)] = rel_err(gg[li][k], v)
+                    errs["%s%d.%s" % (tag, li, k)] = check(gg[li][k], v, tol, "%s %s%d.%s" % (name, tag, li, k))
         worst = max(errs, key=errs.get)
         print(name, "worst", worst, "%.3e" % errs[worst])
-        for k, e in errs.items():
-            assert e <= tol, (name, k, e)
         for p in got["pads"]:
             assert p.size == 0 or np.all(p == 0), name

@@ -165,3 +165,26 @@ def test_paper_example_of_safety_stocks():
                 held.append(i)
             idle = False
     assert held == g["held_back"]
+
+
+def test_comm_plan_two_stages_two_micro_batches_worked_by_hand():
+    """1F1B on 2 stages x 2 micro-batches, every forward 1 and every backward 2 time units, derived on paper.
+    Orders: stage 0 = F0 F1 B0 B1, stage 1 = F0 B0 F1 B1.  Timeline: stage 0 F0 [0,1] F1 [1,2]; stage 1 F0 [1,2]
+    B0 [2,4] F1 [4,5] B1 [5,7]; stage 0 B0 [4,6] B1 [7,9].  Transfers in order of the producing op's end: act 0 (t=1),
+    act 1 (t=2), grad 0 (t=4), grad 1 (t=7); each start goes before the first compute op of its stage that starts at or
+    after that time, each wait right before its consumer."""
+    C, M = 2, 2
+    O = osch.one_f_one_b(C, M)
+    assert O == [[(0, F), (1, F), (0, B), (1, B)], [(0, F), (0, B), (1, F), (1, B)]]
+    one, two = [[1] * C for _ in range(M)], [[2] * C for _ in range(M)]
+    sim = osch.simulate(C, M, O, one, two, one)
+    assert sim["start"] == [[0, 1, 4, 7], [1, 2, 4, 5]] and sim["end"] == [[1, 2, 6, 9], [2, 4, 5, 7]]
+    assert sim["makespan"] == 9 and sim["idle"] == [3, 3] and sim["peak"] == [2, 1]
+    queue, stream = osch.comm_plan(C, M, O, sim)
+    S = osch
+    assert queue[0] == [(S.SEND_ACT, 0), (S.SEND_ACT, 1), (S.RECV_GRAD, 0), (S.RECV_GRAD, 1)]
+    assert queue[1] == [(S.RECV_ACT, 0), (S.RECV_ACT, 1), (S.SEND_GRAD, 0), (S.SEND_GRAD, 1)]
+    assert stream[0] == [(S.FWD, 0), (S.SEND_ACT, 0), (S.FWD, 1), (S.SEND_ACT, 1), (S.RECV_GRAD, 0), (S.WAIT_GRAD, 0),
+                         (S.BWD, 0), (S.RECV_GRAD, 1), (S.WAIT_GRAD, 1), (S.BWD, 1)]
+    assert stream[1] == [(S.RECV_ACT, 0), (S.WAIT_ACT, 0), (S.FWD, 0), (S.RECV_ACT, 1), (S.BWD, 0), (S.SEND_GRAD, 0),
+                         (S.WAIT_ACT, 1), (S.FWD, 1), (S.BWD, 1), (S.SEND_GRAD, 1)]
