@@ -183,6 +183,21 @@ ds_status ds_layout_from_cuts(const int32_t* len, const int32_t* len_tgt, int32_
                               const ds_cost_model* cm, int32_t num_stages, ds_layout** out);
 
 /*
+ * ds_layout_token_based — token-based micro-batching, the "TB" baseline (section "Motivation", micro-batching
+ * methods: micro-batches of the same token count, fewer samples where they are longer; section "Evaluation",
+ * ablation of micro-batching, where the token count per micro-batch is found by search).  Samples are ordered as
+ * in dp_plan; the ordered list is cut from the front, a micro-batch taking samples as long as
+ *       (samples in it) * (its longest sample)  <=  token_budget
+ * (its padded token count; encoder-decoder: of the input stream, the quantity dp_plan's memory cap limits) and
+ * closing when one more would exceed it.  Each micro-batch is padded to its own longest sample.
+ * len, len_tgt, cm (may be NULL), num_stages, *out as ds_layout_from_cuts.
+ * Errors: DS_EINVAL (null, n <= 0, a length <= 0, token_budget <= 0, bad cost model), DS_EINFEASIBLE (a sample
+ * longer than token_budget), DS_EOVERFLOW, DS_ENOMEM.
+ */
+ds_status ds_layout_token_based(const int32_t* len, const int32_t* len_tgt, int32_t n, int64_t token_budget,
+                                const ds_cost_model* cm, int32_t num_stages, ds_layout** out);
+
+/*
  * ds_layout_packed — the packing baseline (section "Background", "The current packing
  * solution"): sequences, in their original order, are placed first-fit into rows of row_len
  * tokens; rows_per_mb rows form one micro-batch; attention never crosses a sequence boundary.

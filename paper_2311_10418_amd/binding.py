@@ -25,7 +25,7 @@ _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOM
                  -5: "DS_EHIP", -6: "DS_ELAYOUT"}
 
 EXPORTS = ["dp_plan", "dp_plan_sampled", "dp_plan_replicas", "ds_plan_recompute", "ds_assign_replicas", "ds_cost_table_build", "ds_schedule_adaptive",
-           "ds_schedule_1f1b", "ds_schedule_simulate", "ds_comm_plan", "ds_layout_from_cuts", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
+           "ds_schedule_1f1b", "ds_schedule_simulate", "ds_comm_plan", "ds_layout_from_cuts", "ds_layout_token_based", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "ds_stage_workspace_need", "stage_fwd_bwd",
            "ds_stage_last_launch_count", "ds_stage_weights_unchanged", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_gemm_ws", "ds_attention_fwd",
            "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
@@ -349,6 +349,16 @@ def ds_layout_from_cuts(lengths, cuts, perm=None, lengths_tgt=None, pad_to=0, pa
                                    C.byref(cost_model) if cost_model is not None else None,
                                    C.c_int32(num_stages), C.byref(out))
     _check(rc, "ds_layout_from_cuts")
+    return Layout(out)
+
+
+def ds_layout_token_based(lengths, token_budget, lengths_tgt=None, cost_model=None, num_stages=1):
+    ln, lt = _np_i32(lengths), _np_i32(lengths_tgt)
+    out = C.c_void_p()
+    rc = lib().ds_layout_token_based(_hp(ln), _hp(lt), C.c_int32(len(ln)), C.c_int64(token_budget),
+                                     C.byref(cost_model) if cost_model is not None else None,
+                                     C.c_int32(num_stages), C.byref(out))
+    _check(rc, "ds_layout_token_based")
     return Layout(out)
 
 

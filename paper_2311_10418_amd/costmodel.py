@@ -163,17 +163,6 @@ def measure_plan(runner, layout, lens, table, reps=3):
     }
 
 
-def token_based_cuts(sorted_lens, budget):
-    """Equal-token-count micro-batching (the paper's TB baseline, section "Evaluation", ablation): walk the sorted
-    list and close a micro-batch when one more sample would push count * longest over the budget."""
-    cuts, start = [0], 0
-    for k in range(1, len(sorted_lens) + 1):
-        if k == len(sorted_lens) or (k + 1 - start) * int(sorted_lens[k]) > budget:
-            cuts.append(k)
-            start = k
-    return cuts
-
-
 def report(config="gpt_2048_bf16", seed=0, reps=3, log=None):
     cfg = wl.CONFIGS[config]
     if cfg["kind"] != "gpt":
@@ -193,11 +182,9 @@ def report(config="gpt_2048_bf16", seed=0, reps=3, log=None):
     t_ms = profile_grid(runner, b_grid, l_grid, max_rows=max_rows, reps=reps, log=log)
     table = build_table(b_grid, l_grid, t_ms, tb, tl)
     prof = ds.dp_plan(lens, ds.make_cost_model(kind=ds.DS_COST_TABLE, table=table), cap, c)
-    order = np.argsort(lens, kind="stable").astype(np.int32)
     tb_plans = {}
-    for budget in (cap // 4, cap // 2, cap):
-        cuts = token_based_cuts(lens[order], budget)
-        tb_plans["plan_token_based_%d" % budget] = ds.ds_layout_from_cuts(lens, cuts, perm=order)
+    for budget in (cap // 4, cap // 2, cap):        # the paper's TB baseline needs a search over its token budget
+        tb_plans["plan_token_based_%d" % budget] = ds.ds_layout_token_based(lens, budget)
     need = max([int(prof.total_rows)] + [int(l.total_rows) for l in tb_plans.values()])
     if need > max_rows:                                 # plans that merge micro-batches pad: they need more rows
         runner.close()

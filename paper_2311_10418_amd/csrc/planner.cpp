@@ -516,6 +516,40 @@ extern "C" ds_status ds_layout_from_cuts(const int32_t* len, const int32_t* len_
     }
 }
 
+extern "C" ds_status ds_layout_token_based(const int32_t* len, const int32_t* len_tgt, int32_t n, int64_t token_budget,
+                                            const ds_cost_model* cm, int32_t num_stages, ds_layout** out) {
+    if (!out) return DS_EINVAL;
+    *out = nullptr;
+    ds_status st = check_lengths(len, len_tgt, n);
+    if (st != DS_OK) return st;
+    if (token_budget <= 0) return DS_EINVAL;
+    try {
+        // the dynamic programme's order: ascending (input length, target length), equal keys by original index
+        std::vector<int32_t> perm(n);
+        std::iota(perm.begin(), perm.end(), 0);
+        std::stable_sort(perm.begin(), perm.end(), [&](int32_t a, int32_t b) {
+            if (len[a] != len[b]) return len[a] < len[b];
+            return len_tgt && len_tgt[a] < len_tgt[b];
+        });
+        // ascending lengths: the longest sample of a micro-batch is its last one, so "one more sample fits" is a
+        // test on the candidate alone
+        std::vector<int32_t> cuts{0};
+        int32_t start = 0;
+        for (int32_t k = 0; k < n; ++k) {
+            const int64_t l = len[perm[k]];
+            if (l > token_budget) return DS_EINFEASIBLE;
+            if ((int64_t)(k + 1 - start) * l > token_budget) {
+                cuts.push_back(k);
+                start = k;
+            }
+        }
+        cuts.push_back(n);
+        return ds_layout_from_cuts(len, len_tgt, n, perm.data(), cuts.data(), (int32_t)cuts.size() - 1, 0, 0, cm, num_stages, out);
+    } catch (const std::bad_alloc&) {
+        return DS_ENOMEM;
+    }
+}
+
 extern "C" ds_status ds_layout_packed(const int32_t* len, int32_t n, int32_t row_len, int32_t rows_per_mb,
                                       ds_layout** out) {
     if (!out) return DS_EINVAL;
