@@ -66,3 +66,33 @@ def test_errors():
     with pytest.raises(ds.DsError) as e:
         ds.ds_schedule_simulate(omb, okind, [[2 ** 62, 2 ** 62]], [[2 ** 62, 2 ** 62]])
     assert e.value.code == ds.DS_EOVERFLOW
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_arbitrary_deadlock_free_orders_with_ties_and_zero_times(seed):
+    """Orders neither schedule produces (micro-batches out of index order, any interleaving), projected from a random
+    topological order of the op graph so that they cannot deadlock; op times from {0, 0, 1, 2} make equal end times,
+    zero-length ops and equal start times common, which is where the placement and tie rules bite."""
+    rng = np.random.default_rng(500 + seed)
+    C, M = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+    done, O = set(), [[] for _ in range(C)]
+    ops = [(i, j, k) for i in range(M) for j in range(C) for k in (osch.F, osch.B)]
+
+    def ready(i, j, k):
+        if k == osch.F:
+            return j == 0 or (i, j - 1, osch.F) in done
+        return (i, j, osch.F) in done and (j == C - 1 or (i, j + 1, osch.B) in done)
+
+    while len(done) < len(ops):
+        cand = [o for o in ops if o not in done and ready(*o)]
+        i, j, k = cand[int(rng.integers(len(cand)))]
+        done.add((i, j, k))
+        O[j].append((i, k))
+    omb, okind = _orders(O, C, M)
+    tf, tb = rng.choice([0, 0, 1, 2], (M, C)), rng.choice([0, 0, 1, 2], (M, C))
+    a = rng.integers(0, 5, (M, C))
+    got = ds.ds_schedule_simulate(omb, okind, tf, tb, a)
+    ref = osch.simulate(C, M, O, tf.tolist(), tb.tolist(), a.tolist())
+    assert got["makespan"] == ref["makespan"] and got["idle"].tolist() == ref["idle"] and got["peak"].tolist() == ref["peak"]
+    assert got["start"].tolist() == ref["start"] and got["end"].tolist() == ref["end"]
+    assert ds.ds_comm_plan(omb, okind, tf, tb) == osch.comm_plan(C, M, O, ref)[1]
