@@ -1,17 +1,28 @@
 #!/usr/bin/env python3
 """Benchmark: non-pad tokens/s of one stage's forward+backward over a DP-planned global batch.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME] [--layout dp|fixed|packed]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME] [--layout dp|fixed|packed|token_based|packed_dense]
+                    [--no-side] [--no-cpu-baseline]
 
 One step = one stage_fwd_bwd call over the whole seeded synthetic global batch (every micro-batch
 of the layout, forward and backward of every layer, weight gradients overwritten), inputs and
-weights already resident in HBM.  Prints ONE JSON line on stdout; everything else goes to stderr.
-The roofline figure is for the dominant kernel family (the bf16 MFMA GEMM), timed with HIP events
-the library records on the launch stream inside the timed region.
+weights already resident in HBM ("grouped" execution: all micro-batches of the plan in every kernel
+launch).  Prints ONE JSON line on stdout; everything else goes to stderr.
+
+The headline (value, ms_per_step, roofline) is the LARGEST single-GPU workload, gpt_4096_longtail_bf16,
+timed over exactly K steps with the library's per-group events switched off; the per-group breakdown
+and the GEMM family's launch durations (HIP events the library records on the launch stream around
+every kernel group) come from a second, shorter loop.  The same record carries, under "configs", the
+other workloads (gpt_2048_bf16, t5_1024_bf16) and the layout comparison on gpt_2048_bf16's batch
+(fixed padding, first-fit packing, token-based micro-batching, DP plan; plus the dense-attention cost
+of packed rows as context), each with ms/step, tokens/s, useful and executed MFMA utilisation and
+padding efficiency, and "sequential_ms": the headline plan run one stage call per micro-batch, the way
+a pipeline stage executes it between its sends and receives.
 """
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -21,6 +32,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA peak
+HEADLINE = "gpt_4096_longtail_bf16"
 
 
 def log(*a):
@@ -43,7 +55,60 @@ def algorithmic_flops(cfg, lens, tgts=None):
     return linear, attn
 
 
-def build_layout(ds, kind, lens, cfg):
+def attention_tiles(ql, kl, causal):
+    """What the matrix-core attention kernels execute for one (query sequence, key sequence) pair and one head, in units
+    of 32 x 32 (query x key) score blocks: (forward, dQ kernel, dK/dV kernel).  A wavefront owns 32 queries (forward, dQ)
+    or 32 keys (dK/dV) and walks the other side in 64-row tiles; it skips tiles (forward) or 32-row halves (backward)
+    that lie wholly beyond its causal diagonal or past the end of the sequence."""
+    if ql <= 0 or kl <= 0:
+        return 0, 0, 0
+    fwd = dq = dkv = 0
+    for qw0 in range(0, ql, 32):                                # forward / dQ: one wavefront per 32 queries
+        last = min(kl - 1, qw0 + 31) if causal else kl - 1
+        q0 = (qw0 // 128) * 128
+        kv_end = min(kl, q0 + 128) if causal else kl
+        for kv0 in range(0, kv_end, 64):
+            if kv0 > last:
+                break
+            fwd += 2                                            # both 32-key halves of a visited tile
+            dq += sum(1 for kt in (0, 1) if kv0 + kt * 32 <= last)
+    for kw0 in range(0, kl, 32):                                # dK/dV: one wavefront per 32 keys
+        k0 = (kw0 // 128) * 128
+        for q0 in range(k0 if causal else 0, ql, 64):
+            if causal and q0 + 63 < kw0:
+                continue
+            dkv += sum(1 for qt in (0, 1) if q0 + qt * 32 < ql and not (causal and q0 + qt * 32 + 31 < kw0))
+    return fwd, dq, dkv
+
+
+def executed_flops(cfg, layout, lens_sorted, tgts_sorted, dense_rows=None):
+    """Flops the kernels issue to the matrix cores for one step: projections over every stream row (padding rows
+    included; the round-up of the last 256-row tile is not counted) and attention over every score block a wavefront
+    visits (recomputation of the scores in the backward pass included: 2 products forward, 3 in the dQ kernel, 4 in
+    the dK/dV kernel, each 2 x 32 x 32 x head_dim flops per block and head)."""
+    d, F, L = cfg["d_model"], cfg["d_ff"], cfg["n_layers"]
+    rows, rows_t = int(layout.total_rows), int(layout.total_rows_tgt)
+    blk = 2 * 32 * 32 * d                                       # one product over one 32 x 32 block, all heads
+
+    def attn(pairs, causal):
+        f = q = kv = 0
+        for ql, kl in pairs:
+            a, b, c = attention_tiles(int(ql), int(kl), causal)
+            f, q, kv = f + a, q + b, kv + c
+        return blk * (2 * f + 3 * q + 4 * kv)
+
+    if cfg["kind"] == "gpt":
+        linear = 3 * 2 * (4 * d * d + 2 * d * F) * rows * L
+        seqs = dense_rows if dense_rows is not None else lens_sorted
+        return linear, attn([(l, l) for l in seqs], True) * L
+    Ld = cfg["n_dec_layers"]
+    linear = 3 * (2 * (4 * d * d + 3 * d * F) * rows * L + (2 * (6 * d * d + 3 * d * F) * rows_t + 2 * 2 * d * d * rows) * Ld)
+    a = attn([(l, l) for l in lens_sorted], False) * L
+    a += (attn([(t, t) for t in tgts_sorted], True) + attn(list(zip(tgts_sorted, lens_sorted)), False)) * Ld
+    return linear, a
+
+
+def build_layout(ds, kind, lens, cfg, token_budget=None):
     if kind == "dp":
         return ds.dp_plan(lens, ds.make_cost_model(), cfg["cap"], cfg["num_stages"]), \
             "dp_plan c=%d cap=%d t=b*L*(1+L/2048)" % (cfg["num_stages"], cfg["cap"])
@@ -53,6 +118,9 @@ def build_layout(ds, kind, lens, cfg):
         return ds.ds_layout_from_cuts(lens, list(range(0, n, 8)) + [n], pad_to=hi), "fixed padding to %d, 8 per micro-batch" % hi
     if kind == "packed":
         return ds.ds_layout_packed(lens, hi, 8), "first-fit packing into %d-token rows, 8 rows per micro-batch" % hi
+    if kind == "token_based":
+        budget = token_budget or cfg["cap"] // 2
+        return ds.ds_layout_token_based(lens, budget), "token-based micro-batching, %d padded tokens per micro-batch" % budget
     if kind == "packed_dense":
         # CONTEXT ONLY (timing, not the model's result): every packed row treated as ONE causal sequence, which is
         # the work a dense kernel with a block-diagonal mask does on packed input (section "Background", packing)
@@ -67,7 +135,7 @@ def build_layout(ds, kind, lens, cfg):
     raise SystemExit("unknown layout " + kind)
 
 
-def cpu_baseline(cfg, lens, seed, budget_s=6.0):
+def cpu_baseline(cfg, lens, seed, budget_s=12.0):
     """The oracle, as it stands, on a bounded seeded sample of the same workload."""
     from oracle import stage as ost
     from paper_2311_10418_amd import workload as wl
@@ -102,58 +170,49 @@ def cpu_baseline(cfg, lens, seed, budget_s=6.0):
     ost.gpt_stage_fwd_bwd(xs, dys, params, cfg["n_heads"])
     dt = time.perf_counter() - t0
     return {"value": tok / dt, "unit": "non-pad tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": "%d seeded sequences of the batch, %d tokens, float64 numpy, %.1f s" % (len(pick), tok, dt)}
+            "sample": "%d seeded sequences of the %s batch, %d tokens, float64 numpy, %.1f s" % (len(pick), cfg["name"], tok, dt)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="gpt_2048_bf16")
-    ap.add_argument("--layout", default="dp", choices=["dp", "fixed", "packed", "packed_dense"])
-    ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--recompute", default="none", choices=["none", "full"],
-                    help="full: keep only layer inputs and re-run each layer's forward before its backward (context; "
-                         "the headline keeps every activation)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus)
-        sys.exit(2)
+def git_head():
+    try:
+        return subprocess.run(["git", "-C", ROOT, "rev-parse", "--short=12", "HEAD"], capture_output=True, text=True, timeout=10).stdout.strip() or None
+    except Exception:
+        return None
 
+
+def run_case(name, layout_kind, steps, warmup, seed=0, recompute="none", breakdown_steps=3, sequential_reps=0, token_budget=None):
+    """Time one workload / layout.  Returns the record of that case."""
     import torch
     from paper_2311_10418_amd import binding as ds
     from paper_2311_10418_amd import workload as wl
 
-    if not torch.cuda.is_available():
-        log("bench.py: no GPU visible")
-        sys.exit(3)
-    cfg = wl.CONFIGS[args.config]
+    cfg = dict(wl.CONFIGS[name], name=name)
     t5 = cfg["kind"] == "t5"
-    recompute = ds.DS_RECOMPUTE_FULL if args.recompute == "full" else ds.DS_RECOMPUTE_NONE
+    rc = ds.DS_RECOMPUTE_FULL if recompute == "full" else ds.DS_RECOMPUTE_NONE
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    lens, tgts = wl.draw_lengths(cfg["lengths"], seed=args.seed)
+    lens, tgts = wl.draw_lengths(cfg["lengths"], seed=seed)
     t0 = time.perf_counter()
+    dense_rows = None
     if t5:
-        if args.layout != "dp":
+        if layout_kind != "dp":
             raise SystemExit("only the DP-planned layout is timed for the encoder-decoder stage")
         layout = ds.dp_plan(lens, ds.make_cost_model(kind=ds.DS_COST_POLY_T5), cfg["cap"], cfg["num_stages"], lengths_tgt=tgts)
         layout_desc = "dp_plan c=%d cap=%d encoder-decoder cost" % (cfg["num_stages"], cfg["cap"])
     else:
-        layout, layout_desc = build_layout(ds, args.layout, lens, cfg)
+        layout, layout_desc = build_layout(ds, layout_kind, lens, cfg, token_budget)
+        if layout_kind == "packed_dense":
+            dense_rows = [int(x) for x in layout.seq_len]
     plan_ms = (time.perf_counter() - t0) * 1e3
     d, F, L, H = cfg["d_model"], cfg["d_ff"], cfg["n_layers"], cfg["n_heads"]
     bf16 = cfg["dtype"] == "bf16"
     tdt = torch.bfloat16 if bf16 else torch.float32
     code = ds.DS_DTYPE_BF16 if bf16 else ds.DS_DTYPE_F32
     R = layout.total_rows
-    log("workload %s: %d sequences, %d non-pad tokens, %d rows in %d micro-batches (%s), plan %.2f ms"
-        % (args.config, len(lens), layout.total_tokens, R, layout.n_mb, layout_desc, plan_ms))
+    log("workload %s / %s: %d sequences, %d rows in %d micro-batches (%s), plan %.2f ms"
+        % (name, layout_kind, len(lens), R, layout.n_mb, layout_desc, plan_ms))
 
     gen = torch.Generator(device=dev)
-    gen.manual_seed(args.seed)
+    gen.manual_seed(seed)
     shapes = {"ln1_g": (d,), "ln1_b": (d,), "w_qkv": (d, 3 * d), "b_qkv": (3 * d,), "w_o": (d, d), "b_o": (d,),
               "ln2_g": (d,), "ln2_b": (d,), "w_1": (d, F), "b_1": (F,), "w_2": (F, d), "b_2": (d,),
               "lnc_g": (d,), "w_g": (d, F), "w_u": (d, F), "w_cq": (d, d), "w_ckv": (d, 2 * d), "w_co": (d, d)}
@@ -182,7 +241,7 @@ def main():
         x, y, dy = rnd(R), rnd(Rt), rnd(Rt)
         out, dx, dyin = torch.empty_like(y), torch.empty_like(x), torch.empty_like(y)
         stage = ds.Stage(ds.DS_MODEL_T5, code, L, d, H, F, max_rows=R, max_seqs=len(lens),
-                         n_dec_layers=cfg["n_dec_layers"], max_rows_tgt=Rt, recompute=recompute)
+                         n_dec_layers=cfg["n_dec_layers"], max_rows_tgt=Rt, recompute=rc)
 
         def step():
             ds.stage_fwd_bwd(stage, layout, weights, x, dy, out, dx, grads, accumulate=False, weights_dec=weights_d,
@@ -191,77 +250,205 @@ def main():
         weights, grads = make_layers(ds.GPT_KEYS, L)
         x, dy = rnd(R), rnd(R)
         out, dx = torch.empty_like(x), torch.empty_like(x)
-        stage = ds.Stage(ds.DS_MODEL_GPT, code, L, d, H, F, max_rows=R, max_seqs=max(len(lens), layout.n_seq),
-                         recompute=recompute)
+        stage = ds.Stage(ds.DS_MODEL_GPT, code, L, d, H, F, max_rows=R, max_seqs=max(len(lens), layout.n_seq), recompute=rc)
 
         def step():
             ds.stage_fwd_bwd(stage, layout, weights, x, dy, out, dx, grads, accumulate=False)
     workspace_gb = stage.workspace_bytes() / 2 ** 30
-    log("workspace %.2f GB" % workspace_gb)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    stage.profile_enable(True)
+    # ---- timed region: exactly `steps` steps, the library's per-group events off; one event pair per step (on the
+    # stream the stage launches on, which is torch's current stream) gives the per-step median as well
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for k in range(steps):
         step()
+        marks[k + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    prof = stage.profile_read()
-    stage.profile_enable(False)
-    ms_per_step = elapsed * 1e3 / args.steps
+    per_step = [marks[k].elapsed_time(marks[k + 1]) for k in range(steps)]
+    ms_per_step = elapsed * 1e3 / steps
+    launches = stage.last_launch_count()
+
+    # ---- second loop: per-group breakdown, GEMM family launch durations
+    breakdown, gemm_ms, gemm_launches = {}, 0.0, 0
+    if breakdown_steps > 0:
+        stage.profile_enable(True)
+        torch.cuda.synchronize()
+        for _ in range(breakdown_steps):
+            step()
+        torch.cuda.synchronize()
+        prof = stage.profile_read()
+        stage.profile_enable(False)
+        breakdown = {k: round(v[0] / breakdown_steps, 4) for k, v in prof.items()}
+        gemm_ms = sum(prof[k][0] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) / breakdown_steps
+        gemm_launches = sum(prof[k][1] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) // breakdown_steps
+
+    # ---- the same plan, one stage call per micro-batch in plan order (weights unchanged between the calls)
+    sequential_ms = None
+    if sequential_reps > 0 and not t5:
+        from paper_2311_10418_amd.costmodel import micro_batch_layouts
+        subs = micro_batch_layouts(layout, lens)
+        stage.weights_unchanged(True)
+
+        def sequential():
+            for k, (sub, r0) in enumerate(subs):
+                r1 = r0 + sub.total_rows
+                ds.stage_fwd_bwd(stage, sub, weights, x[r0:r1], dy[r0:r1], out[r0:r1], dx[r0:r1], grads, accumulate=k > 0)
+        sequential()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(sequential_reps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            sequential()
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - t0) * 1e3)
+        sequential_ms = float(np.median(ts))
+        stage.weights_unchanged(False)
+
     tokens = int(layout.total_tokens) + int(layout.total_tokens_tgt)
-    value = tokens / (elapsed / args.steps)
-
-    lin_flops, attn_flops = algorithmic_flops(cfg, lens, tgts)
-    gemm_ms = sum(prof[k][0] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) / args.steps
-    gemm_launches = sum(prof[k][1] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) // args.steps
-    achieved = lin_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
-    breakdown = {k: round(v[0] / args.steps, 4) for k, v in prof.items()}
-    log("per-step ms by kernel group:", json.dumps(breakdown))
-    log("launches per step: %d" % stage.last_launch_count())
-    useful_util = (lin_flops + attn_flops) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
     all_rows = R + int(layout.total_rows_tgt)
-    log("useful MFMA utilisation (all algorithmic flops / step time / %.0f TFLOP/s): %.4f" % (PEAK_BF16_TFLOPS, useful_util))
-    log("padding efficiency %.4f" % (tokens / all_rows))
+    lin_flops, attn_flops = algorithmic_flops(cfg, lens, tgts)
+    order = [int(i) for i in layout.perm]
+    ex_lin, ex_attn = executed_flops(cfg, layout, [int(lens[i]) for i in order] if layout_kind != "packed_dense" else None,
+                                     [int(tgts[i]) for i in order] if t5 else None, dense_rows)
+    sec = ms_per_step * 1e-3
+    rec = {
+        "workload": name, "layout": layout_kind, "layout_desc": layout_desc, "execution": "grouped",
+        "stage_shape": "%d%s layers d_model %d heads %d d_ff %d" % (L, "+%d" % cfg["n_dec_layers"] if t5 else "", d, H, F),
+        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "ms_per_step_median": float(np.median(per_step)),
+        "tokens_per_s": tokens / sec, "n_seq": int(len(lens)), "non_pad_tokens": tokens, "rows": int(all_rows),
+        "n_micro_batches": int(layout.n_mb), "padding_efficiency": tokens / all_rows,
+        "useful_mfma_utilisation": (lin_flops + attn_flops) / sec / 1e12 / PEAK_BF16_TFLOPS,
+        "executed_mfma_utilisation": (ex_lin + ex_attn) / sec / 1e12 / PEAK_BF16_TFLOPS,
+        "algorithmic_tflop_per_step": (lin_flops + attn_flops) / 1e12, "executed_tflop_per_step": (ex_lin + ex_attn) / 1e12,
+        "dp_plan_ms": plan_ms, "recompute": recompute, "workspace_gb": round(workspace_gb, 3), "launches_per_step": int(launches),
+        "ms_per_step_by_group": breakdown,
+        "gemm": {"ms_per_step": gemm_ms, "launches_per_step": int(gemm_launches), "algorithmic_flops_per_step": lin_flops,
+                 "achieved_tflops": lin_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None},
+    }
+    if sequential_ms is not None:
+        rec["sequential_ms"] = sequential_ms
+    if layout_kind == "packed_dense":
+        rec["note"] = "context only: timing of dense attention over packed rows, not the model's result"
+    log("  %.2f ms/step (median %.2f), %.0f tokens/s, useful %.4f executed %.4f, padding efficiency %.4f%s"
+        % (ms_per_step, rec["ms_per_step_median"], rec["tokens_per_s"], rec["useful_mfma_utilisation"],
+           rec["executed_mfma_utilisation"], rec["padding_efficiency"],
+           "" if sequential_ms is None else ", sequential %.1f ms" % sequential_ms))
+    if breakdown:
+        log("  per-step ms by kernel group:", json.dumps(breakdown))
+    stage.close()
+    del stage, x, dy, out, dx, weights, grads
+    torch.cuda.empty_cache()
+    return rec, cfg, lens
 
-    # HBM-side bytes per GEMM launch from the committed rocprofv3 --pmc summary of this same command, if it
-    # covers this workload (FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size); else null.
-    traffic = None
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default=HEADLINE)
+    ap.add_argument("--layout", default="dp", choices=["dp", "fixed", "packed", "token_based", "packed_dense"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--recompute", default="none", choices=["none", "full"],
+                    help="full: keep only layer inputs and re-run each layer's forward before its backward (context; "
+                         "the headline keeps every activation)")
+    ap.add_argument("--side-steps", type=int, default=4, help="timed steps of each side record")
+    ap.add_argument("--no-side", action="store_true", help="headline only: no other workloads, no layout comparison")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus)
+        sys.exit(2)
+
+    import torch
+    from paper_2311_10418_amd import workload as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    is_default = args.config == HEADLINE and args.layout == "dp" and args.recompute == "none"
+    head, cfg, lens = run_case(args.config, args.layout, args.steps, args.warmup, args.seed, args.recompute,
+                               breakdown_steps=3, sequential_reps=1 if (is_default and not args.no_side) else 0)
+    bf16 = cfg["dtype"] == "bf16"
+
+    # HBM-side bytes per GEMM launch from the committed rocprofv3 --pmc summary of this same command, if it covers
+    # this workload (FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size) and was taken at this commit's
+    # GEMM kernel; else null.
+    traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", "gemm_traffic_%s.json" % args.config)
     if args.layout == "dp" and os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+        tj = json.load(open(tpath))
+        traffic = tj.get("traffic_bytes_per_launch")
+        traffic_src = {"file": "profiles/gemm_traffic_%s.json" % args.config, "measured_at_commit": tj.get("commit"),
+                       "gemm_source_sha16": tj.get("gemm_source_sha16")}
+        import hashlib
+        cur = hashlib.sha256(open(os.path.join(ROOT, "paper_2311_10418_amd", "csrc", "gemm.hip"), "rb").read()).hexdigest()[:16]
+        if tj.get("gemm_source_sha16") != cur:
+            traffic = None                                      # the profile is of another version of the kernel
+            traffic_src["stale"] = True
 
+    g = head["gemm"]
     result = {
         "metric": "non-pad tokens/s, stage fwd+bwd bf16 on 1 MI355X; MFMA util % of peak",
-        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "mfma_util_pct_of_peak": 100.0 * useful_util,      # second part of the metric: useful flops of the whole step
-        "config": {"workload": args.config, "stage_shape": "%d layers d_model %d heads %d d_ff %d" % (L, d, H, F),
-                   "layout": layout_desc, "n_seq": int(len(lens)), "non_pad_tokens": tokens, "rows": int(all_rows),
-                   "n_micro_batches": int(layout.n_mb), "padding_efficiency": tokens / all_rows,
-                   "dp_plan_ms": plan_ms, "recompute": args.recompute, "workspace_gb": round(workspace_gb, 3),
-                   "useful_mfma_utilisation": useful_util,
-                   "ms_per_step_by_group": breakdown},
+        "mfma_util_pct_of_peak": 100.0 * head["useful_mfma_utilisation"],      # second part of the metric: useful flops of the whole step
+        "executed_mfma_util_pct_of_peak": 100.0 * head["executed_mfma_utilisation"],
+        "config": {k: head[k] for k in ("workload", "stage_shape", "layout_desc", "execution", "n_seq", "non_pad_tokens", "rows",
+                                        "n_micro_batches", "padding_efficiency", "dp_plan_ms", "recompute", "workspace_gb",
+                                        "useful_mfma_utilisation", "executed_mfma_utilisation", "ms_per_step_median",
+                                        "launches_per_step", "ms_per_step_by_group")},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt_kernel (all projections: forward, dgrad, wgrad)",
-                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
-                     "launches_per_step": int(gemm_launches), "ms_per_step": gemm_ms,
-                     "algorithmic_flops_per_step": lin_flops},
+                     "achieved": g["achieved_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": g["achieved_tflops"] / PEAK_BF16_TFLOPS if g["achieved_tflops"] else None,
+                     "traffic": traffic, "traffic_source": traffic_src,
+                     "launches_per_step": g["launches_per_step"], "ms_per_step": g["ms_per_step"],
+                     "algorithmic_flops_per_step": g["algorithmic_flops_per_step"]},
+        "commit": git_head(),
     }
+    if "sequential_ms" in head:
+        result["config"]["sequential_ms"] = head["sequential_ms"]
+
+    if is_default and not args.no_side:
+        side = {}
+        ks, kw = max(1, args.side_steps), 2
+        keep = ("workload", "layout", "layout_desc", "execution", "stage_shape", "steps", "ms_per_step", "ms_per_step_median",
+                "tokens_per_s", "non_pad_tokens", "rows", "n_micro_batches", "padding_efficiency", "useful_mfma_utilisation",
+                "executed_mfma_utilisation", "ms_per_step_by_group", "gemm", "note", "sequential_ms")
+        for key, (name, kind, seq) in {"gpt_2048_bf16": ("gpt_2048_bf16", "dp", 1),
+                                       "t5_1024_bf16": ("t5_1024_bf16", "dp", 0),
+                                       "layout_fixed": ("gpt_2048_bf16", "fixed", 0),
+                                       "layout_packed": ("gpt_2048_bf16", "packed", 0),
+                                       "layout_token_based": ("gpt_2048_bf16", "token_based", 0),
+                                       "layout_packed_dense_context": ("gpt_2048_bf16", "packed_dense", 0)}.items():
+            rec, _, _ = run_case(name, kind, ks, kw, args.seed, breakdown_steps=2, sequential_reps=seq)
+            side[key] = {k: rec[k] for k in keep if k in rec}
+        side["layout_dp"] = side["gpt_2048_bf16"]               # (c) of the layout comparison is the DP plan of that batch
+        result["configs"] = side
+        dp = side["gpt_2048_bf16"]["tokens_per_s"]
+        result["dynamic_over_packing"] = dp / side["layout_packed"]["tokens_per_s"]
+        result["dynamic_over_fixed"] = dp / side["layout_fixed"]["tokens_per_s"]
+        result["dynamic_over_token_based"] = dp / side["layout_token_based"]["tokens_per_s"]
+        result["dynamic_over_packing_dense_attention"] = dp / side["layout_packed_dense_context"]["tokens_per_s"]
+
     # One plain device copy of known size (256 MiB read + 256 MiB written), outside the timed region: the
     # reference dispatch against which FETCH_SIZE / WRITE_SIZE counters of a profiler run are scaled.
-    cal_src = torch.ones(64 * 2 ** 20, dtype=torch.float32, device=dev)
+    cal_src = torch.ones(64 * 2 ** 20, dtype=torch.float32, device="cuda:0")
     cal_dst = torch.empty_like(cal_src)
     cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
     del cal_src, cal_dst
-    stage.close()
     torch.cuda.empty_cache()
-    if not args.no_cpu_baseline and not t5:
+    if not args.no_cpu_baseline and cfg["kind"] == "gpt":
         result["cpu_baseline"] = cpu_baseline(cfg, lens, args.seed)
     print(json.dumps(result), flush=True)
 

@@ -2,17 +2,13 @@
 // the contraction running over every token of every micro-batch, which is the gradient
 // accumulation across micro-batches).
 //
-// Three kernels:
+// Two kernels:
 //   * gemm_bf16_nt_kernel — the one the stage runs on: bf16 in, fp32 accumulate on the CDNA4 matrix cores
 //     (v_mfma_f32_16x16x32_bf16), operands straight from global memory into LDS, NT form (forward with [N][K]
 //     weight copies, input gradients) and TN form (weight gradients); described where it is defined.
-//   * gemm_bf16_mfma_kernel — the earlier register-staged kernel (v_mfma_f32_32x32x16_bf16, 256x256x64 macro
-//     tile, 4 wavefronts of 128x128): operands go global -> registers -> LDS (double buffered) in a [row][k] layout
-//     with a 16-byte XOR swizzle; operands whose contraction index is not contiguous in memory are transposed in
-//     registers (8x8 bf16 blocks, v_perm_b32) on their way to LDS, so one body serves NN, NT and TN.  Kept for the
-//     operand forms the first kernel does not take (NN; TN with an epilogue other than fp32 accumulation).
-//   * gemm_generic_kernel — any dtype / shape / stride, plain FMA; the fp32 path and the fallback for shapes the
-//     matrix-core kernels do not take.
+//   * gemm_generic_kernel — any dtype / shape / stride, plain FMA; the fp32 path and the fallback for the operand
+//     forms and shapes the matrix-core kernel does not take (NN; TN with an epilogue other than fp32 accumulation;
+//     N not a multiple of 256).
 // Epilogues go back through LDS so that global stores (and the residual / activation reads) are 16 bytes per lane
 // and row-contiguous.  Work-group ids are remapped so that each XCD (own L2) gets a contiguous run of tiles.
 #include "gemm.hpp"
@@ -202,282 +198,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(int M, int N, int K, 
     }
 }
 
-// ---------------------------------------------------------------------------- MFMA kernel
+// macro tile of the matrix-core kernel
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int kTileBytes = BM * BK * 2;          // 32 KB per operand per buffer
-constexpr int kStageLd = 132;                    // fp32 row stride of the epilogue staging area
-
-// Byte offset of the 16-byte chunk `chunk` (8 bf16 along k) of tile row `row`.  gfx950's LDS serves
-// a 16-byte read for 16 lanes per cycle (64 banks x 4 B), so the 16 consecutive rows that 16
-// consecutive lanes read must land in 16 different 16-byte units of a 256-byte window: rows 2q and
-// 2q+1 already differ by 128 bytes, and the XOR with (row/2)%8 separates the 8 row pairs.
-// (Measured with SQ_LDS_BANK_CONFLICT: a swizzle by row%8 costs one extra cycle pass per read.)
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
-
-// Register staging for one 256x64 operand tile: 8 chunks of 16 bytes per thread, kept in ONE
-// 32-dword vector value (chunk i = dwords 4i..4i+3) so that it stays in VGPRs across the K loop.
-typedef uint32_t u32x32_t __attribute__((ext_vector_type(32)));
-
-__device__ __forceinline__ void put4(u32x32_t& r, int i, const uint4& v) {
-    r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
-}
-__device__ __forceinline__ uint4 get4(const u32x32_t& r, int i) {
-    return make_uint4(r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]);
-}
-
-typedef uint32_t u32x8_t __attribute__((ext_vector_type(8)));
-
-// Operand tile loader (256 rows x 64 k per step, 8 chunks of 16 bytes per thread).  Addresses are a
-// work-group-uniform 64-bit panel base plus a per-thread unsigned 32-bit byte offset computed once,
-// outside the K loop.
-//  TR = 0: memory is [row][k] (k contiguous): chunk c = t + 256*i -> row c/8, k-chunk c%8; the
-//          K step advances the uniform base by 64 elements.  Rows past the edge are clamped
-//          (they are never stored).
-//  TR = 1: memory is [k][row] (row contiguous): the thread owns k-chunk t%8 and rows
-//          (t/8)*8..+7; chunk i holds 8 consecutive rows at k = kc*8 + i; the K step advances
-//          the base by 64*ld elements.  k indices past the contraction length are clamped for the
-//          load and zeroed when the tile is written to LDS.
-template <int TR>
-__device__ __forceinline__ u32x8_t tile_offsets(long long ld, int row0, int n_rows, int t) {
-    u32x8_t off;
-    if (TR == 0) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int c = t + 256 * i;
-            int row = row0 + (c >> 3);
-            row = row < n_rows ? row : n_rows - 1;
-            off[i] = (uint32_t)(((long long)(row - row0) * ld + ((c & 7) << 3)) * 2);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) off[i] = (uint32_t)((t >> 3) * 16);   // row-group offset; the k part is added per step
-    }
-    return off;
-}
-
-template <int TR>
-__device__ __forceinline__ void load_chunk(u32x32_t& r, int i, const char* __restrict__ panel, const u32x8_t& off,
-                                           uint32_t ld_bytes, int k_left, int t) {
-    if (TR == 0) {
-        put4(r, i, *reinterpret_cast<const uint4*>(panel + off[i]));
-    } else {
-        int k = (t & 7) * 8 + i;
-        k = k < k_left ? k : k_left - 1;
-        put4(r, i, *reinterpret_cast<const uint4*>(panel + (off[i] + (uint32_t)k * ld_bytes)));
-    }
-}
-
-// Write part i (of 8) of a staged tile to LDS.  TR = 0: chunk i as loaded.  TR = 1: tile row
-// (t/8)*8 + i, gathered from element i of all 8 loaded chunks (8x8 transpose of 16-bit elements:
-// k pair (2j, 2j+1) <- element i of chunks 2j, 2j+1); in the work-group-uniform tail tile the chunks
-// whose k index lies past the contraction length are zeroed first.
-template <int TR>
-__device__ __forceinline__ void store_chunk(const u32x32_t& r, int i, char* __restrict__ lds, int k_left, int t) {
-    if (TR == 0) {
-        const int c = t + 256 * i;
-        *reinterpret_cast<uint4*>(lds + lds_off(c >> 3, c & 7)) = get4(r, i);
-    } else {
-        const int kc = t & 7, rg = t >> 3;
-        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-        const int w = i >> 1;
-        uint4 o;
-        if (k_left >= BK) {
-            o.x = __builtin_amdgcn_perm(r[4 * 1 + w], r[4 * 0 + w], sel);
-            o.y = __builtin_amdgcn_perm(r[4 * 3 + w], r[4 * 2 + w], sel);
-            o.z = __builtin_amdgcn_perm(r[4 * 5 + w], r[4 * 4 + w], sel);
-            o.w = __builtin_amdgcn_perm(r[4 * 7 + w], r[4 * 6 + w], sel);
-        } else {
-            uint32_t keep[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) keep[j] = (kc * 8 + j) < k_left ? 0xffffffffu : 0u;
-            o.x = __builtin_amdgcn_perm(r[4 * 1 + w] & keep[1], r[4 * 0 + w] & keep[0], sel);
-            o.y = __builtin_amdgcn_perm(r[4 * 3 + w] & keep[3], r[4 * 2 + w] & keep[2], sel);
-            o.z = __builtin_amdgcn_perm(r[4 * 5 + w] & keep[5], r[4 * 4 + w] & keep[4], sel);
-            o.w = __builtin_amdgcn_perm(r[4 * 7 + w] & keep[7], r[4 * 6 + w] & keep[6], sel);
-        }
-        *reinterpret_cast<uint4*>(lds + lds_off(rg * 8 + i, kc)) = o;
-    }
-}
-
-struct Frags {
-    bf16x8_t a[4], b[4];
-};
-
-__device__ __forceinline__ void load_frags(Frags& f, const char* __restrict__ a_base, const char* __restrict__ b_base, int wm,
-                                           int wn, int ks, int frag_row, int frag_half) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        f.a[i] = *reinterpret_cast<const bf16x8_t*>(a_base + lds_off(wm * 128 + i * 32 + frag_row, ks * 2 + frag_half));
-        f.b[i] = *reinterpret_cast<const bf16x8_t*>(b_base + lds_off(wn * 128 + i * 32 + frag_row, ks * 2 + frag_half));
-    }
-}
-
-// A: TA = 0 -> [M][K] (lda = K stride); TA = 1 -> [K][M].  B: TB = 1 -> [N][K]; TB = 0 -> [K][N].
-// Requirements checked by the launcher: N % 256 == 0; (TA == 0: K % 64 == 0) ; (TA == 1: M % 256 == 0);
-// TB == 0 needs N % 8 == 0 (implied).  k range of this work-group: [k_begin, k_end) in units of BK tiles.
-template <int TA, int TB, int EPI>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_mfma_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
-                                                                const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
-                                                                long long lda, long long ldb, int tiles_m, int tiles_n,
-                                                                int splits, float* __restrict__ split_ws, GemmEpi p) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int t = threadIdx.x;
-    const int lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-
-    // ---- work-group id -> (tile_m, tile_n, split): contiguous runs per XCD, groups of 8 tile rows
-    const int total = tiles_m * tiles_n * splits;
-    int logical;
-    {
-        const int pid = blockIdx.x;
-        const int xcd = pid & 7, local = pid >> 3;
-        const int per = total >> 3, rem = total & 7;
-        const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
-        logical = start + local;
-    }
-    const int split = logical / (tiles_m * tiles_n);
-    logical -= split * (tiles_m * tiles_n);
-    int tile_m, tile_n;
-    {
-        const int group_sz = 8 * tiles_n;
-        const int group = logical / group_sz;
-        const int first_m = group * 8;
-        const int gs = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
-        const int in_group = logical - group * group_sz;
-        tile_m = first_m + in_group % gs;
-        tile_n = in_group / gs;
-    }
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    const int nk_total = (K + BK - 1) / BK;
-    const int per_split = (nk_total + splits - 1) / splits;
-    const int kt_begin = split * per_split;
-    const int kt_end = (kt_begin + per_split) < nk_total ? (kt_begin + per_split) : nk_total;
-
-    f32x16_t acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    // LDS map: buffer b holds A at b*2*kTileBytes and B right after it
-
-    if (kt_begin < kt_end) {
-        // Software pipeline over K tiles: one register staging set, two LDS buffers.  While the MFMAs
-        // of tile kt run out of LDS buffer kt%2, the first quarter of them is interleaved with the LDS
-        // writes of tile kt+1 (fetched 3/4 of a step earlier) into the other buffer, and the second
-        // quarter with the global loads of tile kt+2 into the registers just freed.  One barrier per
-        // step, and no LDS write sits between the barrier and the first MFMA.  Tile indices past the
-        // end are clamped (redundant, harmless work) so that no load or store is conditional:
-        // conditional staging makes the compiler keep it in scratch.
-        constexpr int TBt = (TB == 0);
-        const u32x8_t offA = tile_offsets<TA>(lda, m0, M, t);
-        const u32x8_t offB = tile_offsets<TBt>(ldb, n0, N, t);
-        const uint32_t lda_b = (uint32_t)(lda * 2), ldb_b = (uint32_t)(ldb * 2);
-        const char* pa = reinterpret_cast<const char*>(A) + (TA ? (long long)m0 * 2 : (long long)m0 * lda * 2);
-        const char* pb = reinterpret_cast<const char*>(B) + (TB ? (long long)n0 * ldb * 2 : (long long)n0 * 2);
-        const long long stepA = TA ? (long long)BK * lda * 2 : (long long)BK * 2;
-        const long long stepB = TB ? (long long)BK * 2 : (long long)BK * ldb * 2;
-        const int frag_row = lane & 31, frag_half = lane >> 5;
-        const int kt_last = kt_end - 1;
-
-        u32x32_t sa, sb;
-        {   // prologue: tile kt_begin -> LDS buffer 0; tile kt_begin+1 -> registers
-            const int k0 = kt_begin;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                load_chunk<TA>(sa, i, pa + k0 * stepA, offA, lda_b, K - k0 * BK, t);
-                load_chunk<TBt>(sb, i, pb + k0 * stepB, offB, ldb_b, K - k0 * BK, t);
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                store_chunk<TA>(sa, i, smem, K - k0 * BK, t);
-                store_chunk<TBt>(sb, i, smem + kTileBytes, K - k0 * BK, t);
-            }
-            const int k1 = k0 + 1 < kt_last ? k0 + 1 : kt_last;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                load_chunk<TA>(sa, i, pa + k1 * stepA, offA, lda_b, K - k1 * BK, t);
-                load_chunk<TBt>(sb, i, pb + k1 * stepB, offB, ldb_b, K - k1 * BK, t);
-            }
-            __syncthreads();
-        }
-
-        for (int kt = kt_begin; kt < kt_end; ++kt) {
-            const int buf = (kt - kt_begin) & 1;
-            const char* a_base = smem + buf * (2 * kTileBytes);
-            const char* b_base = a_base + kTileBytes;
-            char* na = smem + (buf ^ 1) * (2 * kTileBytes);
-            char* nb = na + kTileBytes;
-            const int k_store = K - (kt + 1 < kt_last ? kt + 1 : kt_last) * BK;   // tile now in registers
-            const int kn = kt + 2 < kt_last ? kt + 2 : kt_last;                  // tile to fetch
-            const int k_load = K - kn * BK;
-            const char* pan = pa + kn * stepA;
-            const char* pbn = pb + kn * stepB;
-            Frags f[2];
-            load_frags(f[0], a_base, b_base, wm, wn, 0, frag_row, frag_half);
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                if (ks < 3) load_frags(f[(ks + 1) & 1], a_base, b_base, wm, wn, ks + 1, frag_row, frag_half);
-                const Frags& c = f[ks & 1];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.a[i], c.b[j], acc[i][j], 0, 0, 0);
-                    if (ks == 0) {          // slots 0..3: write staged tile kt+1 (parts 2i, 2i+1 of each operand)
-                        store_chunk<TA>(sa, 2 * i, na, k_store, t);
-                        store_chunk<TA>(sa, 2 * i + 1, na, k_store, t);
-                        store_chunk<TBt>(sb, 2 * i, nb, k_store, t);
-                        store_chunk<TBt>(sb, 2 * i + 1, nb, k_store, t);
-                    } else if (ks == 1) {   // slots 4..7: fetch tile kt+2
-                        load_chunk<TA>(sa, 2 * i, pan, offA, lda_b, k_load, t);
-                        load_chunk<TA>(sa, 2 * i + 1, pan, offA, lda_b, k_load, t);
-                        load_chunk<TBt>(sb, 2 * i, pbn, offB, ldb_b, k_load, t);
-                        load_chunk<TBt>(sb, 2 * i + 1, pbn, offB, ldb_b, k_load, t);
-                    }
-                }
-            }
-            __syncthreads();
-        }
-    }
-
-    // ---- epilogue through LDS: per wave a [32][kStageLd] fp32 staging block
-    float* stage = reinterpret_cast<float*>(smem) + wave * (32 * kStageLd);
-    const int col_l = lane & 31, half = lane >> 5;
-    const int rd_row = lane >> 4, rd_col = (lane & 15) * 8;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = 8 * (e >> 2) + 4 * half + (e & 3);
-                stage[row * kStageLd + j * 32 + col_l] = acc[i][j][e];
-            }
-        __syncthreads();
-#pragma unroll
-        for (int pss = 0; pss < 8; ++pss) {
-            const int row = pss * 4 + rd_row;
-            const int m = m0 + wm * 128 + i * 32 + row;
-            const int n = n0 + wn * 128 + rd_col;
-            if (m < M) {
-                float v[8];
-                const float4 x0 = *reinterpret_cast<const float4*>(stage + row * kStageLd + rd_col);
-                const float4 x1 = *reinterpret_cast<const float4*>(stage + row * kStageLd + rd_col + 4);
-                v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
-                if (splits > 1) {
-                    Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
-                } else {
-                    epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
-                }
-            }
-        }
-    }
-}
 
 // ---------------------------------------------------------------------------- NT / TN kernel, direct to LDS
 // NT form: C[M,N] = A[M,K] * B[N,K]^T, both operands k-contiguous (K % 64 == 0, N % 256 == 0).
@@ -497,24 +219,12 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_mfma_kernel(int M, int N, in
 // scales with the number of wavefronts on the CU; and a single wavefront per SIMD cannot keep the matrix pipe
 // busy with the 16x16x32 shape (it needs two issuing).
 constexpr int NT_DK = 32, NT_NS = 4, NT_HALF = 256 * NT_DK * 2, NT_STAGE = 2 * NT_HALF;
-#ifndef NT_WM
-#define NT_WM 2
-#define NT_WN 4
-#endif
+constexpr int NT_WM = 2, NT_WN = 4;             // wavefront grid of a work-group: 2 x 4, each wavefront 128 x 64
 // how a K tile's direct-load instructions are spread over the MFMA groups of the main loops (see the loops)
-#ifndef NT_G0
-#define NT_G0 4
-#define NT_G1 4
-#define NT_G2 0
-#endif
-#ifndef TN_PRE
-#define TN_PRE 4
-#endif
-
+constexpr int NT_G0 = 4, NT_G1 = 4, NT_G2 = 0;
+constexpr int TN_PRE = 4;
 // tile number -> tile coordinates: groups of NT_GROUP tile rows, column-major inside a group
-#ifndef NT_GROUP
-#define NT_GROUP 4
-#endif
+constexpr int NT_GROUP = 4;
 __host__ __device__ __forceinline__ void nt_tile_coords(int logical, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
     const int group_sz = NT_GROUP * tiles_n;
     const int group = logical / group_sz;
@@ -1031,47 +741,6 @@ ds_status launch_generic(int ta, int tb, int M, int N, int K, const void* A, con
     return DS_OK;
 }
 
-template <int TA, int TB, int EPI>
-ds_status launch_mfma(int M, int N, int K, const void* A, const void* B, void* C, const GemmEpi& p, float* split_ws,
-                      size_t split_ws_floats, hipStream_t st) {
-    static bool attr_set = false;
-    auto kern = gemm_bf16_mfma_kernel<TA, TB, EPI>;
-    const int smem = 4 * kTileBytes;
-    if (!attr_set) {
-        DS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-        attr_set = true;
-    }
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
-    const int nk = (K + BK - 1) / BK;
-    int splits = 1;
-    if (EPI == DS_EPI_ACC32 && split_ws) {
-        const int tiles = tiles_m * tiles_n;
-        if (tiles < 384) {
-            splits = (512 + tiles - 1) / tiles;
-            if (splits > 16) splits = 16;
-            if (splits > nk / 8) splits = nk / 8 > 0 ? nk / 8 : 1;
-            while (splits > 1 && (size_t)splits * M * N > split_ws_floats) --splits;
-            // every split must own at least one K tile
-            const int per = (nk + splits - 1) / splits;
-            splits = (nk + per - 1) / per;
-        }
-    }
-    const long long lda = TA ? M : K;
-    const long long ldb = TB ? K : N;
-    const int total = tiles_m * tiles_n * splits;
-    hipLaunchKernelGGL(kern, dim3(total), dim3(256), smem, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C, lda,
-                       ldb, tiles_m, tiles_n, splits, split_ws, p);
-    DS_LAUNCH_CHECK();
-    if (splits > 1) {
-        long long items = (long long)M * (N / 8);
-        long long g = (items + 255) / 256;
-        if (g > 8192) g = 8192;
-        hipLaunchKernelGGL(splitk_finish_kernel<EPI>, dim3((int)g), dim3(256), 0, st, M, N, splits, split_ws, (bf16_t*)C, p);
-        DS_LAUNCH_CHECK();
-    }
-    return DS_OK;
-}
-
 // number of K splits of a weight-gradient GEMM: the fewest that bring the work-group count closest to a whole
 // number of rounds over the compute units (time ~ rounds x split length)
 static int cu_count() {
@@ -1169,11 +838,9 @@ ds_status dispatch_epi(int dtype, int ta, int tb, int M, int N, int K, const voi
         const bool ok_b = tb ? (K % BK == 0) : true;
         const bool aligned = ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && ((uintptr_t)C % 16 == 0);
         if (ok_n && ok_a && ok_b && aligned && M >= 1 && K >= 1) {
-            if (!ta && !tb) return launch_mfma<0, 0, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
             if (!ta && tb) return launch_nt<EPI, false>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
             if constexpr (EPI == DS_EPI_ACC32)
                 if (ta && !tb) return launch_nt<EPI, true>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
-            if (ta && !tb) return launch_mfma<1, 0, EPI>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
         }
     }
     if (dtype == DS_DTYPE_BF16) return launch_generic<bf16_t, EPI>(ta, tb, M, N, K, A, B, C, p, st);

@@ -11,10 +11,10 @@
 // and zero rows stay zero through the backward pass, so padding contributes nothing to any weight
 // gradient.
 //
-// bf16 fast path ("nt mode"): every GEMM runs as C = A B^T with both operands contiguous along the
-// contraction (the direct-to-LDS kernel).  Forward uses [out][in] copies of the weights made at the
-// top of the call; a weight gradient dW[in][out] = X^T dY uses feature-major copies of X and dY whose
-// token dimension is zero-padded to a multiple of 64.
+// bf16 fast path ("nt mode"): forward and input-gradient GEMMs run as C = A B^T with both operands contiguous
+// along the contraction (forward uses [out][in] copies of the weights, made at the top of the call unless the
+// caller has promised unchanged weights); a weight gradient dW[in][out] = X^T dY reads X and dY token-major as
+// they are (the kernel's TN form turns the tiles in LDS), so no transposed copy of an activation exists.
 #include "attention.hpp"
 #include "gemm.hpp"
 #include "layout.hpp"

@@ -42,6 +42,26 @@ def _run(stage, layout, w, x, dy):
     return out, dx, g
 
 
+def _oracle_by_sequence(xs, dys, params, n_heads, tag):
+    """The oracle one sequence at a time (it treats sequences independently and sums their weight gradients, so this
+    is its own definition spelt out), with a progress line after each: a long run stays visibly alive."""
+    import time
+    outs, dxs, grads = [], [], None
+    for j, (x, dy) in enumerate(zip(xs, dys)):
+        t0 = time.time()
+        o, g, w = ost.gpt_stage_fwd_bwd([x], [dy], params, n_heads)
+        outs.append(o[0])
+        dxs.append(g[0])
+        if grads is None:
+            grads = w
+        else:
+            for li, layer in enumerate(w):
+                for k, v in layer.items():
+                    grads[li][k] = grads[li][k] + v
+        print("  oracle %s: sequence %d of %d, %d tokens, %.1f s" % (tag, j + 1, len(xs), x.shape[0], time.time() - t0), flush=True)
+    return outs, dxs, grads
+
+
 def _sample(lens, sample_tokens, long_len):
     """Shortest, median, one near long_len, the longest, then mid-length ones up to the token budget."""
     order = np.argsort(lens, kind="stable")
@@ -103,8 +123,7 @@ def test_full_size_configuration(name, sample_tokens, long_len):
     print(name, "sampled sequences", pick, "lengths", [int(lens[i]) for i in pick], flush=True)
     xs = [_rows_for(lens, i, d, 0, 3) for i in pick]
     dys = [_rows_for(lens, i, d, 0, 5) for i in pick]
-    r_outs, r_dxs, r_grads = ost.gpt_stage_fwd_bwd(xs, dys, params, H)
-    print("  oracle done", flush=True)
+    r_outs, r_dxs, r_grads = _oracle_by_sequence(xs, dys, params, H, name)
 
     for lname, layout in _layouts_for(name, lens, cfg):
         R = layout.total_rows
@@ -192,8 +211,7 @@ def test_full_width_weight_gradients_over_16k_tokens_against_the_oracle():
     from helpers import check_seqs, run_gpt_stage
     layout = ds.dp_plan(lens, ds.make_cost_model(), cfg["cap"], cfg["num_stages"])
     outs, dxs, grads, _, _ = run_gpt_stage(layout, dict(cfg, n_layers=1), params, xs, dys, ds.DS_DTYPE_BF16)
-    r_outs, r_dxs, r_grads = ost.gpt_stage_fwd_bwd(xs, dys, params, H)
-    print("  oracle done", flush=True)
+    r_outs, r_dxs, r_grads = _oracle_by_sequence(xs, dys, params, H, "16k")
     check_seqs(outs, r_outs, TOL, "16k act_out")
     check_seqs(dxs, r_dxs, TOL, "16k grad_in")
     for k, v in r_grads[0].items():
