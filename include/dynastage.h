@@ -24,7 +24,8 @@ typedef enum {
     DS_ENOMEM = -3,       /* host or device allocation failed */
     DS_EOVERFLOW = -4,    /* a cost or an objective does not fit in int64 */
     DS_EHIP = -5,         /* a HIP runtime call failed (no device, launch error) */
-    DS_ELAYOUT = -6       /* layout does not fit the stage's workspace or does not match its model kind */
+    DS_ELAYOUT = -6,      /* layout does not fit the stage's workspace or does not match its model kind */
+    DS_ELIMIT = -7        /* a size beyond the fixed capacity of an entry point that allocates nothing */
 } ds_status;
 
 /* ------------------------------------------------------------------------------------------
@@ -529,6 +530,17 @@ int64_t ds_norm_bwd_scratch_floats(int32_t rows, int32_t d);
 /* out[n] (float32) = sum_m x[m,n] (+ out[n] if accumulate).  partial as above (same size rule). */
 ds_status ds_colsum(int32_t dtype, int32_t rows, int32_t n, const void* x, float* out, float* partial,
                     int32_t accumulate, void* hip_stream);
+
+/* ds_colsum for callers that cannot allocate or hand over scratch memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same two kernels as ds_colsum, with the partial sums in a
+ * 4 MiB array that is part of the library's device image (one copy per GPU, held until the process ends).  The call
+ * allocates nothing and frees nothing; it only enqueues the two kernels on hip_stream.  out[n] as ds_colsum.
+ * Limits: n <= 65536 (DS_ELIMIT beyond), device ordinal < 64.  All calls on one GPU share that GPU's array: calls
+ * that overlap in time on one GPU (different streams, different threads) race; calls on one stream do not.
+ * Nothing in the array needs to start at zero (every partial row that is read was written by the same call).
+ * Errors: DS_EINVAL (null, rows <= 0, n <= 0, n % 8, dtype), DS_ELIMIT, DS_EHIP. */
+ds_status ds_colsum_static(int32_t dtype, int32_t rows, int32_t n, const void* x, float* out, int32_t accumulate,
+                           void* hip_stream);
 
 /* Library identification: returns a static HOST string "dynastage <version> gfx950". */
 const char* ds_version(void);

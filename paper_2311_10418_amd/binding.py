@@ -13,7 +13,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdynastage.so")
 
-DS_OK, DS_EINVAL, DS_EINFEASIBLE, DS_ENOMEM, DS_EOVERFLOW, DS_EHIP, DS_ELAYOUT = 0, -1, -2, -3, -4, -5, -6
+DS_OK, DS_EINVAL, DS_EINFEASIBLE, DS_ENOMEM, DS_EOVERFLOW, DS_EHIP, DS_ELAYOUT, DS_ELIMIT = 0, -1, -2, -3, -4, -5, -6, -7
 DS_COST_POLY_GPT, DS_COST_POLY_T5, DS_COST_TABLE = 0, 1, 2
 DS_MODEL_GPT, DS_MODEL_T5 = 0, 1
 DS_DTYPE_F32, DS_DTYPE_BF16 = 0, 1
@@ -22,13 +22,13 @@ DS_EPI_NONE, DS_EPI_GELU, DS_EPI_RESID, DS_EPI_DGELU, DS_EPI_ACC32, DS_EPI_GATE,
 PROF_KINDS = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "norm", "colsum", "other", "transpose")
 
 _STATUS_NAMES = {0: "DS_OK", -1: "DS_EINVAL", -2: "DS_EINFEASIBLE", -3: "DS_ENOMEM", -4: "DS_EOVERFLOW",
-                 -5: "DS_EHIP", -6: "DS_ELAYOUT"}
+                 -5: "DS_EHIP", -6: "DS_ELAYOUT", -7: "DS_ELIMIT"}
 
 EXPORTS = ["dp_plan", "dp_plan_sampled", "dp_plan_replicas", "ds_plan_recompute", "ds_assign_replicas", "ds_cost_table_build", "ds_schedule_adaptive",
            "ds_schedule_1f1b", "ds_schedule_simulate", "ds_comm_plan", "ds_layout_from_cuts", "ds_layout_token_based", "ds_layout_packed", "ds_layout_get", "ds_layout_free",
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "ds_stage_workspace_need", "stage_fwd_bwd",
            "ds_stage_last_launch_count", "ds_stage_weights_unchanged", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_gemm_ws", "ds_attention_fwd",
-           "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum",
+           "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum", "ds_colsum_static",
            "ds_version"]
 
 
@@ -547,6 +547,15 @@ def ds_colsum(x, out, partial, accumulate=False, stream=None):
     rc = lib().ds_colsum(C.c_int32(_dtype_code(x)), C.c_int32(rows), C.c_int32(n), _dp(x), _dp(out), _dp(partial),
                          C.c_int32(int(accumulate)), _stream(stream))
     _check(rc, "ds_colsum")
+
+
+def ds_colsum_static(x, out, accumulate=False, stream=None, rows=None, n=None):
+    """ds_colsum without a scratch argument and without any allocation (the partial sums live in the library's image)."""
+    if rows is None:
+        rows, n = x.shape
+    rc = lib().ds_colsum_static(C.c_int32(_dtype_code(x)), C.c_int32(rows), C.c_int32(n), _dp(x), _dp(out),
+                                C.c_int32(int(accumulate)), _stream(stream))
+    _check(rc, "ds_colsum_static")
 
 
 def ds_version():

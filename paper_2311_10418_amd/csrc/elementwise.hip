@@ -4,9 +4,20 @@
 // per lane, consecutive lanes touching consecutive addresses.
 #include "common.hpp"
 
+#include <mutex>
+
 namespace {
 
 constexpr int kPartialRows = 2048;   // upper bound on partial-sum rows written by column reductions
+
+// Partial column sums of ds_colsum_static: 4 MiB of device memory per GPU for the life of the process.  In host code
+// this name is only a handle for hipGetSymbolAddress; kernels get the per-device address it returns.
+constexpr int kStaticFloats = 1 << 20;
+constexpr int kStaticMaxCols = 65536;
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) float g_colsum_scratch[kStaticFloats];
+float* g_colsum_scratch_ptr[kMaxDevices];        // device address of the array on each GPU; null until first used there
+std::mutex g_colsum_scratch_mutex;
 
 // ------------------------------------------------------------------ row copy kernels
 template <class T>
@@ -526,14 +537,13 @@ ds_status launch_reduce_partials(int32_t n_partial, int32_t n, const float* part
     return DS_OK;
 }
 
-extern "C" ds_status ds_colsum(int32_t dtype, int32_t rows, int32_t n, const void* x, float* out, float* partial,
-                               int32_t accumulate, void* hip_stream) {
-    if (rows <= 0 || n <= 0 || n % 8 || !x || !out || !partial) return DS_EINVAL;
-    if (dtype != DS_DTYPE_F32 && dtype != DS_DTYPE_BF16) return DS_EINVAL;
-    hipStream_t st = (hipStream_t)hip_stream;
+// Column sums in two kernels: gy partial rows of n floats each (gy <= max_partial_rows), then their sum in a fixed order.
+static ds_status colsum_launch(int32_t dtype, int32_t rows, int32_t n, const void* x, float* out, float* partial,
+                               int max_partial_rows, int32_t accumulate, hipStream_t st) {
     const int gx = (n / 8 + 63) / 64;
     int gy = (rows + 3) / 4;
-    const int cap = kPartialRows / gx > 0 ? kPartialRows / gx : 1;
+    int cap = kPartialRows / gx > 0 ? kPartialRows / gx : 1;
+    if (cap > max_partial_rows) cap = max_partial_rows;
     if (gy > cap) gy = cap;
     if (dtype == DS_DTYPE_BF16)
         hipLaunchKernelGGL(colsum_kernel<bf16_t>, dim3(gx, gy), dim3(256), 0, st, rows, n, (const bf16_t*)x, partial);
@@ -544,4 +554,35 @@ extern "C" ds_status ds_colsum(int32_t dtype, int32_t rows, int32_t n, const voi
                        (const float*)nullptr, (float*)nullptr);
     DS_LAUNCH_CHECK();
     return DS_OK;
+}
+
+extern "C" ds_status ds_colsum(int32_t dtype, int32_t rows, int32_t n, const void* x, float* out, float* partial,
+                               int32_t accumulate, void* hip_stream) {
+    if (rows <= 0 || n <= 0 || n % 8 || !x || !out || !partial) return DS_EINVAL;
+    if (dtype != DS_DTYPE_F32 && dtype != DS_DTYPE_BF16) return DS_EINVAL;
+    return colsum_launch(dtype, rows, n, x, out, partial, kPartialRows, accumulate, (hipStream_t)hip_stream);
+}
+
+extern "C" ds_status ds_colsum_static(int32_t dtype, int32_t rows, int32_t n, const void* x, float* out, int32_t accumulate,
+                                      void* hip_stream) {
+    if (rows <= 0 || n <= 0 || n % 8 || !x || !out) return DS_EINVAL;
+    if (dtype != DS_DTYPE_F32 && dtype != DS_DTYPE_BF16) return DS_EINVAL;
+    if (n > kStaticMaxCols) return DS_ELIMIT;
+    int dev = -1;
+    DS_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return DS_ELIMIT;
+    float* scratch = nullptr;
+    {
+        // once per device, with that device current: every GPU holds its own copy of the array at its own address
+        std::lock_guard<std::mutex> lock(g_colsum_scratch_mutex);
+        if (!g_colsum_scratch_ptr[dev]) {
+            void* p = nullptr;
+            DS_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(g_colsum_scratch)));
+            if (!p) return DS_EHIP;
+            g_colsum_scratch_ptr[dev] = (float*)p;
+        }
+        scratch = g_colsum_scratch_ptr[dev];
+    }
+    // every partial row the second kernel reads is written in full by the first: nothing needs clearing between calls
+    return colsum_launch(dtype, rows, n, x, out, scratch, kStaticFloats / n, accumulate, (hipStream_t)hip_stream);
 }

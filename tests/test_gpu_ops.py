@@ -1,7 +1,7 @@
 """GPU parity of the building-block kernels, each called through the C ABI and compared with its plain
 definition (numpy float64 on the same rounded inputs, or the oracle's per-sequence attention / norm
 functions).  Every comparison bounds the normwise relative error by the stated tolerance AND every
-single element's deviation by 8 x tolerance x rms(reference) (helpers.both_err).  Sizes span several
+single element's deviation by tolerance x (8 x rms(reference) + |reference element|) (helpers.both_err).  Sizes span several
 tiles and a ragged tail."""
 import numpy as np
 import pytest
