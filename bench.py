@@ -135,7 +135,7 @@ def build_layout(ds, kind, lens, cfg, token_budget=None):
     raise SystemExit("unknown layout " + kind)
 
 
-def cpu_baseline(cfg, lens, seed, budget_s=12.0):
+def cpu_baseline(cfg, lens, seed, budget_s=6.0):
     """The oracle, as it stands, on a bounded seeded sample of the same workload."""
     from oracle import stage as ost
     from paper_2311_10418_amd import workload as wl
@@ -182,6 +182,7 @@ def git_head():
 
 def run_case(name, layout_kind, steps, warmup, seed=0, recompute="none", breakdown_steps=3, sequential_reps=0, token_budget=None):
     """Time one workload / layout.  Returns the record of that case."""
+    t_case = time.perf_counter()
     import torch
     from paper_2311_10418_amd import binding as ds
     from paper_2311_10418_amd import workload as wl
@@ -345,6 +346,7 @@ def run_case(name, layout_kind, steps, warmup, seed=0, recompute="none", breakdo
     stage.close()
     del stage, x, dy, out, dx, weights, grads
     torch.cuda.empty_cache()
+    log("  (case took %.1f s of wall clock, set-up included)" % (time.perf_counter() - t_case))
     return rec, cfg, lens
 
 

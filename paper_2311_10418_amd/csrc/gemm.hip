@@ -480,8 +480,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                 tn_iter(tl + 1, fby, fbx);
             }
             if (tl < t_end) tn_iter(tl, fbx, fby);
-        }
-        else {
+        } else {
             // two 64 KB stages, two 32-deep k steps = four half steps per tile, one barrier per tile.  Transfers of
             // tile tl+1 ride on the four half steps between two barriers: NT_G0 on the one right after the barrier
             // (the last half step of tile tl-1), then NT_G1, NT_G2, the rest
