@@ -46,7 +46,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 // sched_barrier mask: vector ALU, scalar ALU and transcendental instructions may cross, LDS accesses and MFMAs may not
 constexpr int kFence = 0x2 | 0x4 | 0x400;
 // how many fragment reads (forward) / pairs of reads (dQ) run in front of the MFMAs that use them
-constexpr int FWD_AHEAD = 4, DQ_AHEAD = 2;
+constexpr int FWD_AHEAD = 4, PV_AHEAD = 4, DQ_AHEAD = 2;
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
@@ -120,6 +120,7 @@ template <int HD> struct TileLoader {
     long long ld2;                                      // row stride in bytes (64 rows of it fit in 31 bits)
     int n_valid, wave, lane;
     uint32_t off_full[PW];
+    uint32_t off_group[PW];                             // the same offsets as lds_dma16_group wants them
     __device__ __forceinline__ static int row_of(int u) { return HD == 128 ? (u >> 4) : (u >> 3); }
     __device__ __forceinline__ static int chunk_of(int u) {
         return (HD == 128 ? (u & 15) : (u & 7)) ^ swz<HD>(row_of(u));
@@ -130,22 +131,25 @@ template <int HD> struct TileLoader {
         for (int i = 0; i < PW; ++i) {
             const int u = (wave * PW + i) * 64 + lane;
             off_full[i] = (uint32_t)(row_of(u) * (int)ld2 + chunk_of(u) * 16);
+            off_group[i] = dma_lane_offset<PW>(off_full[i], i);
         }
     }
-    // rows r0 .. r0+63 -> the tile at `lds`; 0 <= r0 < n_valid
-    __device__ __forceinline__ void issue(char* lds, int r0) const {
+    // rows r0 .. r0+63 -> the tile at LDS address lds_tile; 0 <= r0 < n_valid.  A tile whose 64 rows all exist goes as
+    // one group of PW transfers under a single M0 with the fixed offsets; the ragged last tile clamps its rows.
+    __device__ __forceinline__ void issue(uint32_t lds_tile, int r0) const {
         const char* b = base + (long long)r0 * ld2;
         if (r0 + 64 <= n_valid) {
-#pragma unroll
-            for (int i = 0; i < PW; ++i) lds_dma16_s(b, off_full[i], lds + (wave * PW + i) * 1024);
+            lds_dma16_group<PW>(dma_group_base<PW>(b), off_group, lds_tile + wave * (PW * 1024));
         } else {
             const int last = n_valid - 1 - r0;
+            uint32_t off[PW];
 #pragma unroll
             for (int i = 0; i < PW; ++i) {
                 const int u = (wave * PW + i) * 64 + lane;
                 const int rr = min(row_of(u), last);
-                lds_dma16_s(b, (uint32_t)(rr * (int)ld2 + chunk_of(u) * 16), lds + (wave * PW + i) * 1024);
+                off[i] = dma_lane_offset<PW>((uint32_t)(rr * (int)ld2 + chunk_of(u) * 16), i);
             }
+            lds_dma16_group<PW>(dma_group_base<PW>(b), off, lds_tile + wave * (PW * 1024));
         }
     }
 };
@@ -223,6 +227,7 @@ template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TILE = 64 * HD * 2;                  // bytes of one K tile == one V tile
+    const uint32_t lds0 = lds_address(smem);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, g = lane >> 5;
@@ -264,28 +269,38 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
     const int wave_last = CAUSAL ? min(kl - 1, qw0 + 31) : kl - 1;     // last key this wavefront can see
     const int nb = (kv_end + 63) / 64;
     if (nb > 0) {                                       // (a sequence without keys: zero output, nothing to fetch)
-        ldK.issue(smem, 0);
-        ldV.issue(smem + TILE, 0);
+        ldK.issue(lds0, 0);
+        ldV.issue(lds0 + TILE, 0);
     }
     for (int b = 0; b < nb; ++b) {
         const int kv0 = b * 64;
         char* sK = smem + (b & 1) * (2 * TILE);
         char* sV = sK + TILE;
         wait_tiles_and_sync();                          // block b has landed; the other stage is free
-        if (b + 1 < nb) {
-            char* nK = smem + ((b + 1) & 1) * (2 * TILE);
-            ldK.issue(nK, kv0 + 64);
-            ldV.issue(nK + TILE, kv0 + 64);
+        // The transfers of block b+1.  A wavefront cannot issue anything else while a transfer of its own passes the
+        // address stage of the texture path (measured with timestamps: one burst of 8 transfers with an M0 each held
+        // a wavefront for about 600 cycles of a 4400-cycle step; grouped under one M0 per tile, 250), so a wavefront
+        // that computes in this step hands out the two groups between the MFMAs of its first product; only a ragged
+        // last block (its per-lane offsets are recomputed) and wavefronts without work issue them at once.
+        const bool have_next = b + 1 < nb;
+        const bool active = !(kv0 > wave_last || qw0 >= ql);
+        const bool spread = have_next && active && kv0 + 128 <= kl;
+        const uint32_t nK_lds = lds0 + ((b + 1) & 1) * (2 * TILE);
+        if (have_next && !spread) {
+            ldK.issue(nK_lds, kv0 + 64);
+            ldV.issue(nK_lds + TILE, kv0 + 64);
         }
-        if (kv0 > wave_last || qw0 >= ql) continue;
+        if (!active) continue;
 
         f32x16_t sacc[2];
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) sacc[kt][e] = 0.f;
-        {
-            // fragment reads FWD_AHEAD MFMAs in front of their use, the order pinned by fences (see the dK/dV kernel)
+        // first product, S^T = K Q^T: fragment reads FWD_AHEAD MFMAs in front of their use, the order pinned by fences
+        // (see the dK/dV kernel); two copies, with and without the transfers, so that neither holds a branch
+        auto first_product = [&](auto with_dma) {
+            constexpr bool DMA = decltype(with_dma)::value;
             constexpr int NF = 2 * (HD / 16);
             bf16x8_t fk[NF];
             auto read_k = [&](int i) {
@@ -300,8 +315,25 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
                 __builtin_amdgcn_sched_barrier(kFence);
                 sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[i], qf[i >> 1], sacc[i & 1], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(kFence);
+                if (DMA && i == NF / 4 - 1) {           // the next K tile after a quarter of the product ...
+                    ldK.issue(nK_lds, kv0 + 64);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (DMA && i == 3 * NF / 4 - 1) {       // ... the next V tile after three quarters
+                    ldV.issue(nK_lds + TILE, kv0 + 64);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-        }
+        };
+        if (spread) first_product(std::true_type{});
+        else first_product(std::false_type{});
+        // the first V^T fragments of the second product are fetched now and land during the softmax
+        constexpr int NV = 4 * (HD / 32);
+        bf16x8_t fv[NV];
+        auto read_v = [&](int i) { fv[i] = read_tr<HD>(sV, tro, i / (HD / 32), i % (HD / 32)); };
+#pragma unroll
+        for (int i = 0; i < PV_AHEAD; ++i) read_v(i);
+        __builtin_amdgcn_sched_barrier(kFence);
         const bool need_mask = (kv0 + 64 > kl) || (CAUSAL && kv0 + 63 > qw0);
         if (need_mask) {
             // the volatile statement keeps the whole mask computation inside a real branch: hoisted or if-converted,
@@ -340,14 +372,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
                 for (int e = 0; e < 16; ++e) oacc[dt][e] *= alpha;
         }
         m = m_new;
+        // second product, O^T += V^T P^T: transpose reads PV_AHEAD MFMAs in front of their use
+        bf16x8_t pf;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const bf16x8_t pf = frag_from_acc(sacc[t >> 1], t & 1);
-#pragma unroll
-            for (int dt = 0; dt < HD / 32; ++dt) {
-                const bf16x8_t vf = read_tr<HD>(sV, tro, t, dt);
-                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[dt], 0, 0, 0);
-            }
+        for (int i = 0; i < NV; ++i) {
+            if (i + PV_AHEAD < NV) read_v(i + PV_AHEAD);
+            if (i % (HD / 32) == 0) pf = frag_from_acc(sacc[(i / (HD / 32)) >> 1], (i / (HD / 32)) & 1);
+            __builtin_amdgcn_sched_barrier(kFence);
+            oacc[i % (HD / 32)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[i], pf, oacc[i % (HD / 32)], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(kFence);
         }
     }
     lsum += __shfl_xor(lsum, 32, 64);
@@ -381,12 +414,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
     const int qi = qw0 + col;
     const int qi_c = qi < ql ? qi : ql - 1;
 
+    const uint32_t lds0 = lds_address(smem);
     TileLoader<HD> ldK, ldV;
     ldK.setup(K, a.ldk, kl, wave, lane);
     ldV.setup(V, a.ldv, kl, wave, lane);
     if (kl > 0) {
-        ldK.issue(smem, 0);
-        ldV.issue(smem + TILE, 0);
+        ldK.issue(lds0, 0);
+        ldV.issue(lds0 + TILE, 0);
     }
 
     bf16x8_t qf[HD / 16], dof[HD / 16];
@@ -432,7 +466,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a) {
         char* sV = sK + TILE;
         wait_tiles_and_sync();
         if (b + 1 < nb) {
-            char* n = smem + ((b + 1) & 1) * (2 * TILE);
+            const uint32_t n = lds0 + ((b + 1) & 1) * (2 * TILE);
             ldK.issue(n, kv0 + 64);
             ldV.issue(n + TILE, kv0 + 64);
         }
@@ -529,8 +563,9 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
     // block blk -> stage blk % 4: Q tile, dO tile, and (wavefronts 0 and 1) the two statistics tiles, all by direct
     // transfers; indices past the last block are clamped (redundant transfers into a free stage keep the count of
     // outstanding transfers the same at every step)
+    const uint32_t lds0 = lds_address(smem);
     auto issue_block = [&](int blk) {
-        char* n = smem + (blk & (NS - 1)) * STAGE;
+        const uint32_t n = lds0 + (blk & (NS - 1)) * STAGE;
         const int bc = blk < nb ? blk : nb - 1;
         const int q0 = q_begin + bc * 64;
         ldQ.issue(n, q0);
@@ -538,7 +573,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
         if (wave < 2) {
             int r = q0 + lane;
             r = r < ql ? r : ql - 1;
-            lds_dma16(aug_src + (size_t)r * 16, n + 2 * TILE + wave * 1024);
+            lds_dma16_at(aug_src + (size_t)r * 16, n + 2 * TILE + wave * 1024);
         }
     };
     if (nb > 0) {

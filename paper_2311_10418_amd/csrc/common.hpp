@@ -140,6 +140,83 @@ __device__ __forceinline__ void lds_dma16_s(const void* base, uint32_t lane_off,
                  : : "v"(lane_off), "s"(sb), "s"(lds_addr) : "memory", "m0");
 }
 
+// LDS byte address of a pointer into shared memory, as the integer that M0 and the LDS instructions use.  Taken once
+// per kernel: stage and tile addresses are then scalar integer arithmetic (a generic pointer converted per transfer
+// costs a null check, a 64-bit vector add and two lane reads each time).
+__device__ __forceinline__ uint32_t lds_address(const void* lds_ptr) {
+    return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds_ptr);
+}
+
+// lds_dma16 with the destination given as an LDS address (see lds_address) instead of a generic pointer.
+__device__ __forceinline__ void lds_dma16_at(const void* gptr, uint32_t lds_addr) {
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(m0v) : "memory", "m0");
+}
+
+// N (1..4) direct transfers of 64 x 16 bytes each that share ONE value of M0: transfer i lands at lds_addr + 1024 i
+// and reads base + lane_off[i] (base wavefront-uniform).  The LDS destination of a transfer is M0 + the instruction's
+// immediate offset + 16 * lane, and the immediate is added to the global address as well, so the caller passes lane
+// offsets that are already reduced by 1024 i (see dma_lane_offset).  Why one M0: a transfer reads M0 when it is
+// executed, so every write of M0 waits until the transfer before it has passed the address stage; with one write per
+// transfer a wavefront spent about 75 cycles per transfer unable to issue anything else.
+template <int N>
+__device__ __forceinline__ void lds_dma16_group(const void* base, const uint32_t (&lane_off)[N], uint32_t lds_addr) {
+    static_assert(N >= 1 && N <= 4, "the immediate offset reaches 3 x 1024");
+    const uint64_t b = (uint64_t)(uintptr_t)base;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    const uint64_t sb = ((uint64_t)hi << 32) | (uint64_t)lo;
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_addr);
+    if constexpr (N == 1)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     : : "v"(lane_off[0]), "s"(sb), "s"(m0v) : "memory", "m0");
+    else if constexpr (N == 2)
+        asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2\n\t"
+                     "global_load_lds_dwordx4 %1, %2 offset:1024"
+                     : : "v"(lane_off[0]), "v"(lane_off[1]), "s"(sb), "s"(m0v) : "memory", "m0");
+    else if constexpr (N == 3)
+        asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %3\n\t"
+                     "global_load_lds_dwordx4 %1, %3 offset:1024\n\tglobal_load_lds_dwordx4 %2, %3 offset:2048"
+                     : : "v"(lane_off[0]), "v"(lane_off[1]), "v"(lane_off[2]), "s"(sb), "s"(m0v) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %5\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %4\n\t"
+                     "global_load_lds_dwordx4 %1, %4 offset:1024\n\tglobal_load_lds_dwordx4 %2, %4 offset:2048\n\t"
+                     "global_load_lds_dwordx4 %3, %4 offset:3072"
+                     : : "v"(lane_off[0]), "v"(lane_off[1]), "v"(lane_off[2]), "v"(lane_off[3]), "s"(sb), "s"(m0v)
+                     : "memory", "m0");
+}
+// Lane offset to hand to lds_dma16_group for transfer i of N when the bytes wanted are base + want: the group is
+// given base - 1024 (N - 1), and the instruction adds 1024 i back.
+template <int N> __device__ __forceinline__ uint32_t dma_lane_offset(uint32_t want, int i) { return want + 1024u * (uint32_t)(N - 1 - i); }
+template <int N> __device__ __forceinline__ const char* dma_group_base(const char* base) { return base - 1024 * (N - 1); }
+
+// Raw buffer descriptor over [base, base + bytes) (stride 0, no swizzle): a buffer load whose byte offset is at or
+// beyond `bytes` returns zeros instead of touching memory.  base and bytes wavefront-uniform.
+typedef int32_t i32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4_t make_raw_buffer(const void* base, uint32_t bytes) {
+    const uint64_t b = (uint64_t)(uintptr_t)base;
+    i32x4_t d;
+    d[0] = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    d[1] = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32) & 0xFFFFu);
+    d[2] = __builtin_amdgcn_readfirstlane(bytes);
+    d[3] = 0x00020000;
+    return d;
+}
+// Four direct transfers of 64 x 16 bytes under one M0, two through each of two buffers: they land at lds_addr,
+// + 1024, + 2048, + 3072.  As with lds_dma16_group the immediate offsets (0, 1024, 2048, 3072) are added to the
+// memory offsets too, range check included: the caller builds the buffers 3072 bytes early and 3072 bytes longer
+// and passes lane offsets a0 + 3072, a1 + 2048, b0 + 1024, b1.
+__device__ __forceinline__ void lds_dma16_buffers_2x2(i32x4_t buf_a, uint32_t a0, uint32_t a1, i32x4_t buf_b, uint32_t b0,
+                                                      uint32_t b1, uint32_t lds_addr) {
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %6\n\ts_nop 0\n\t"
+                 "buffer_load_dwordx4 %0, %4, 0 offen lds\n\t"
+                 "buffer_load_dwordx4 %1, %4, 0 offen offset:1024 lds\n\t"
+                 "buffer_load_dwordx4 %2, %5, 0 offen offset:2048 lds\n\t"
+                 "buffer_load_dwordx4 %3, %5, 0 offen offset:3072 lds"
+                 : : "v"(a0), "v"(a1), "v"(b0), "v"(b1), "s"(buf_a), "s"(buf_b), "s"(m0v) : "memory", "m0");
+}
+
 static inline size_t dtype_size(int32_t dtype) { return dtype == DS_DTYPE_BF16 ? 2 : 4; }
 
 // ---- launchers shared between translation units (all enqueue on `st`, return ds_status)

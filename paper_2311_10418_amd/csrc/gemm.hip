@@ -221,8 +221,7 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NT_DK = 32, NT_NS = 4, NT_HALF = 256 * NT_DK * 2, NT_STAGE = 2 * NT_HALF;
 constexpr int NT_WM = 2, NT_WN = 4;             // wavefront grid of a work-group: 2 x 4, each wavefront 128 x 64
 // how a K tile's direct-load instructions are spread over the MFMA groups of the main loops (see the loops)
-constexpr int NT_G0 = 4, NT_G1 = 4, NT_G2 = 0;
-constexpr int TN_PRE = 4;
+constexpr int NT_G0 = 1, NT_G1 = 1, NT_G2 = 0;       // (in transfer groups: the A part, the B part)
 // tile number -> tile coordinates: groups of NT_GROUP tile rows, column-major inside a group
 constexpr int NT_GROUP = 4;
 __host__ __device__ __forceinline__ void nt_tile_coords(int logical, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
@@ -234,9 +233,6 @@ __host__ __device__ __forceinline__ void nt_tile_coords(int logical, int tiles_m
     tile_m = first_m + in_group % gs;
     tile_n = in_group / gs;
 }
-
-// 16 zero bytes: the source of every chunk past the end of a ragged contraction (TN form)
-__device__ uint4 g_zero16;
 
 // WM x WN wavefronts per work-group; each owns a (256/WM) x (256/WN) accumulator block.
 //
@@ -319,7 +315,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
 
     if (t_begin < t_end) {
         uint32_t offA[LPW], offB[LPW];
-        int krow[LPW];                                              // TN: k-row of this lane's chunk within a tile
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int u = (wave * LPW + i) * 64 + lane;
@@ -330,58 +325,61 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                 ra_ = ra_ < M ? ra_ : M - 1;                        // rows past the edge: clamped, never stored
                 offA[i] = (uint32_t)(((long long)(ra_ - m0) * K + chunk * 8) * 2);
                 offB[i] = (uint32_t)(((long long)row * K + chunk * 8) * 2);
-                krow[i] = 0;
             } else {                                                // 16-byte unit of the 32 k-row tile (512-byte rows)
                 const int row = u >> 5, pos = u & 31;
                 const int chunk = (((pos >> 1) ^ (row & 7)) << 1) | (pos & 1);
                 offA[i] = (uint32_t)(((long long)row * M + chunk * 8) * 2);
                 offB[i] = (uint32_t)(((long long)row * N + chunk * 8) * 2);
-                krow[i] = row;
             }
         }
+        uint32_t offAg[LPW], offBg[LPW];                            // the same offsets as a transfer group wants them
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            if constexpr (TNF) {                                    // group of four: A, A, B, B
+                offAg[i] = dma_lane_offset<2 * LPW>(offA[i], i);
+                offBg[i] = dma_lane_offset<2 * LPW>(offB[i], LPW + i);
+            } else {
+                offAg[i] = dma_lane_offset<LPW>(offA[i], i);
+                offBg[i] = dma_lane_offset<LPW>(offB[i], i);
+            }
+        }
+        const uint32_t lds0 = lds_address(smem);
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
         const char* pa = reinterpret_cast<const char*>(A) + (TNF ? (long long)m0 * 2 : (long long)m0 * K * 2);
         const char* pb = reinterpret_cast<const char*>(B) + (TNF ? (long long)n0 * 2 : (long long)n0 * K * 2);
         const long long tile_step_a = TNF ? (long long)DK * M * 2 : DK * 2;
         const long long tile_step_b = TNF ? (long long)DK * N * 2 : DK * 2;
         const int frag_row = lane & 15, frag_grp = lane >> 4;       // operand row / k group of this lane
         const int t_last = t_end - 1;
-        auto issue = [&](int tile, int stage) {
-            tile = tile < t_last ? tile : t_last;
-            const char* ga = pa + tile * tile_step_a;
-            const char* gb = pb + tile * tile_step_b;
-            char* la = smem + stage * STAGE + wave * (LPW * 1024);
-            char* lb = la + HALF;
-            const int k_left = TNF ? K - tile * DK : DK;            // valid k-rows of this tile
-#pragma unroll
-            for (int i = 0; i < LPW; ++i) {
-                const char* sa = ga + offA[i];
-                const char* sb = gb + offB[i];
-                if (TNF && k_left < DK && krow[i] >= k_left) {
-                    sa = reinterpret_cast<const char*>(&g_zero16);
-                    sb = sa;
-                }
-                lds_dma16(sa, la + i * 1024);
-                lds_dma16(sb, lb + i * 1024);
-            }
-        };
-        // One transfer of a K tile: s = 2*i + (0: A, 1: B), i < LPW.  The texture path of a compute unit takes 16
-        // cycles per transfer, 64 of them per 64 KB, and a wavefront cannot issue anything else while its own
-        // transfers queue up there, so the main loops hand them out one at a time between the MFMAs instead of in a
-        // burst after the barrier (which left the matrix cores idle for about a quarter of every tile).
+        // The transfers of a K tile, in the groups the main loops hand out between their MFMAs (a wavefront cannot issue
+        // anything else while a transfer of its own passes the address stage of the texture path, so they are neither
+        // issued in one burst after the barrier, which left the matrix cores idle for about a quarter of every tile,
+        // nor one at a time with an M0 of their own: a write of M0 waits for the transfer before it).
+        //   NT form: s = 0 / 1 = this wavefront's part of the A / B tile, LPW transfers under one M0; wavefront-uniform
+        //     base in scalar registers + per-lane offsets that never change (stepping along K costs no vector
+        //     instruction); LDS destinations are scalar integers, not generic pointers.
+        //   TN form: s = 0 = both parts (A, A, B, B in one 4 KB block of LDS per wavefront), through two buffer
+        //     descriptors whose lengths end at the last row of a ragged K: rows past the end read zeros, with no
+        //     per-lane test.
         auto issue_one = [&](int tile, int stage, int s) {
             tile = tile < t_last ? tile : t_last;
-            const int i = s >> 1;
-            const bool is_b = s & 1;
-            char* dst = smem + stage * STAGE + (is_b ? HALF : 0) + wave * (LPW * 1024) + i * 1024;
-            if constexpr (TNF) {                                    // rows past the end of a ragged K read zeros
-                const char* g = (is_b ? pb + tile * tile_step_b + offB[i] : pa + tile * tile_step_a + offA[i]);
-                if (K - tile * DK < DK && krow[i] >= K - tile * DK) g = reinterpret_cast<const char*>(&g_zero16);
-                lds_dma16(g, dst);
+            if constexpr (TNF) {
+                static_assert(!TNF || LPW == 2, "one group = two A and two B transfers");
+                const int k_left = K - tile * DK;
+                const uint32_t rows = (uint32_t)(k_left < DK ? k_left : DK);
+                const i32x4_t buf_a = make_raw_buffer(pa + tile * tile_step_a - 3072, rows * (uint32_t)M * 2u + 3072u);
+                const i32x4_t buf_b = make_raw_buffer(pb + tile * tile_step_b - 3072, rows * (uint32_t)N * 2u + 3072u);
+                lds_dma16_buffers_2x2(buf_a, offAg[0], offAg[1], buf_b, offBg[0], offBg[1],
+                                      lds0 + stage * STAGE + wave_u * (2 * LPW * 1024));
             } else {
-                // wavefront-uniform base in scalar registers + a per-lane offset that never changes: stepping along
-                // K costs no vector instruction (measured + 1 %; in the TN form the same change costs 2 %)
-                lds_dma16_s(is_b ? pb + tile * tile_step_b : pa + tile * tile_step_a, is_b ? offB[i] : offA[i], dst);
+                const uint32_t dst_g = lds0 + stage * STAGE + (s ? HALF : 0) + wave_u * (LPW * 1024);
+                if (s) lds_dma16_group<LPW>(dma_group_base<LPW>(pb + tile * tile_step_b), offBg, dst_g);
+                else lds_dma16_group<LPW>(dma_group_base<LPW>(pa + tile * tile_step_a), offAg, dst_g);
             }
+        };
+        auto issue = [&](int tile, int stage) {
+#pragma unroll
+            for (int s = 0; s < (TNF ? 1 : 2); ++s) issue_one(tile, stage, s);
         };
         // NT: 128-byte rows: 16 consecutive rows at one chunk index must hit 16 different 16-byte units of a 256-byte
         // window: rows 2q and 2q+1 differ by 128 bytes, the XOR with (row/2)%8 separates the 8 row pairs
@@ -392,14 +390,15 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
         // touch 8 k-rows, so the 32-byte unit index is XORed with row%8.  Both operands use the same k order, so the
         // contraction is unchanged.
         const int tr_x = 4 * ((lane >> 4) & 1) + ((lane >> 2) & 3);
-        const int tr_base = (4 * (lane >> 4) + ((lane & 15) >> 2)) * 512 + (lane & 3) * 8;
+        // (LDS layout of a TN stage: per wavefront w one 4 KB block = k-rows 4w .. 4w+3 of the A tile, then of the B tile)
+        const int tr_base = (lane >> 4) * 4096 + ((lane & 15) >> 2) * 512 + (lane & 3) * 8;
         auto read_tr = [&](const char* base, int unit) {
             typedef short s16x4_t __attribute__((ext_vector_type(4)));
             typedef short s16x8_t __attribute__((ext_vector_type(8)));
             typedef __attribute__((address_space(3))) s16x4_t* lds4_t;
             const char* q = base + tr_base + ((unit ^ tr_x) << 5);
             const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)q);
-            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(q + 16 * 512));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(q + 4 * 4096));
             const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             return __builtin_bit_cast(bf16x8_t, v);
         };
@@ -413,7 +412,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
             }
         };
         auto load_b = [&](int stage, int ks, bf16x8_t (&fb)[TN16]) {
-            const char* b_base = smem + stage * STAGE + HALF;
+            const char* b_base = smem + stage * STAGE + (TNF ? 2 * 1024 : HALF);
 #pragma unroll
             for (int j = 0; j < TN16; ++j) {
                 if constexpr (TNF) fb[j] = read_tr(b_base, wn * TN16 + j);
@@ -433,7 +432,11 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                     // (measured: about 2 % more sustained MFMA rate at the power limit than row-major order)
                     const int j = (i & 1) ? TN16 - 1 - jj : jj;
                     const int q = i * TN16 + jj;
+#ifdef X_QPOS
+                    if (done < cnt && q == (2 * done + 1) * (HA * TN16) / (2 * cnt)) {
+#else
                     if (done < cnt && q == done * (HA * TN16) / cnt) {
+#endif
                         __builtin_amdgcn_sched_barrier(0);
                         issue_one(tile, stage, s0 + done);
                         __builtin_amdgcn_sched_barrier(0);
@@ -446,14 +449,15 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
         // one run, ACROSS the tile boundary too, so that no wavefront waits on LDS latency right after the barrier
         // (all 8 wavefronts leave it together, so nobody would be left to cover for the others).
         bf16x8_t fax[HA], fay[HA], fbx[TN16], fby[TN16];
-        constexpr int NTR = 2 * LPW;                                // transfers per K tile and wavefront
+        // transfers per K tile and wavefront: NVM instructions, handed out in NTR groups (TN: one, NT: A part, B part)
+        constexpr int NVM = 2 * LPW, NTR = TNF ? 1 : 2;
         if constexpr (TNF) {
-            // one 32-deep k step per tile, two half steps; transfers of tile tl+3: TN_PRE before the barrier of
-            // iteration tl, the rest after it
+            // one 32-deep k step per tile, two half steps; the transfers of tile tl+3 go out in the first one, before the
+            // barrier of iteration tl
             issue(t_begin, 0);
             issue(t_begin + 1, 1);
             issue(t_begin + 2, 2);
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * NTR));         // tile t_begin: at most the two newest tiles outstanding
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * NVM));         // tile t_begin: at most the two newest tiles outstanding
             __builtin_amdgcn_s_barrier();
             load_b(0, 0, fbx);
             load_a(0, 0, 0, fax);
@@ -462,16 +466,16 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                 // stage (tl-1)%4 is free: every wavefront finished reading it before the barrier it has passed last
                 load_a(st_, 0, 1, fay);
                 __builtin_amdgcn_sched_barrier(0);
-                mma_dma(0, fax, fb_cur, tl + 3, (st_ + 3) & (NS - 1), 0, TN_PRE);
+                mma_dma(0, fax, fb_cur, tl + 3, (st_ + 3) & (NS - 1), 0, 1);
                 __builtin_amdgcn_sched_barrier(0);
                 // tile tl+1: this wavefront's part has landed (tile tl+2 and the new transfers outstanding), its LDS
                 // reads are done ...
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(NTR + TN_PRE) & 0xF0FF);   // vmcnt(NTR + TN_PRE) lgkmcnt(0)
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * NVM) & 0xF0FF);        // vmcnt(2 NVM) lgkmcnt(0)
                 __builtin_amdgcn_s_barrier();                       // ... and everyone's
                 load_b((st_ + 1) & (NS - 1), 0, fb_next);           // past the last tile: a stale but valid stage, unused
                 load_a((st_ + 1) & (NS - 1), 0, 0, fax);
                 __builtin_amdgcn_sched_barrier(0);
-                mma_dma(1, fay, fb_cur, tl + 3, (st_ + 3) & (NS - 1), TN_PRE, NTR - TN_PRE);
+                mma_dma(1, fay, fb_cur, tl + 3, (st_ + 3) & (NS - 1), 1, 0);
                 __builtin_amdgcn_sched_barrier(0);
             };
             int tl = t_begin;
@@ -839,8 +843,8 @@ ds_status dispatch_epi(int dtype, int ta, int tb, int M, int N, int K, const voi
         const bool aligned = ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && ((uintptr_t)C % 16 == 0);
         if (ok_n && ok_a && ok_b && aligned && M >= 1 && K >= 1) {
             if (!ta && tb) return launch_nt<EPI, false>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
-            if constexpr (EPI == DS_EPI_ACC32)
-                if (ta && !tb) return launch_nt<EPI, true>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
+            if constexpr (EPI == DS_EPI_ACC32)      // (the TN form addresses a K tile of each operand through a 32-bit buffer length)
+                if (ta && !tb && M <= (1 << 25) && N <= (1 << 25)) return launch_nt<EPI, true>(M, N, K, A, B, C, p, split_ws, split_ws_floats, st);
         }
     }
     if (dtype == DS_DTYPE_BF16) return launch_generic<bf16_t, EPI>(ta, tb, M, N, K, A, B, C, p, st);
