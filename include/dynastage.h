@@ -461,10 +461,14 @@ ds_status ds_unpack(const ds_layout* layout, int32_t which, int32_t dtype, int32
  *   ACC32    C is float32 [M,N]; C = acc + (accumulate ? C : 0)
  *   GATE     C = acc (stored), C2 = GELU_tanh(R[m,n]) * C            (gated MLP forward)
  *   DGATE    C = acc * R2[m,n] * GELU_tanh'(R[m,n]), C2 = acc * GELU_tanh(R[m,n])   (its backward)
+ *   GELU_D   z = acc + bias (not stored); C = GELU_tanh'(z), C2 = GELU_tanh(z).  The stage's MLP forward: it keeps
+ *            the derivative instead of the pre-activation (both come from one logistic term), so that the
+ *            backward epilogue is one multiplication per element:
+ *   MULR     C = acc * R[m,n]                                          (R = the derivative GELU_D stored)
  * N must be a multiple of 8.  force_generic != 0 selects the plain FMA kernel.
  * bias may be NULL.  row_valid may be NULL (all rows valid). */
 enum { DS_EPI_NONE = 0, DS_EPI_GELU = 1, DS_EPI_RESID = 2, DS_EPI_DGELU = 3, DS_EPI_ACC32 = 4,
-       DS_EPI_GATE = 5, DS_EPI_DGATE = 6 };
+       DS_EPI_GATE = 5, DS_EPI_DGATE = 6, DS_EPI_GELU_D = 7, DS_EPI_MULR = 8 };
 ds_status ds_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
                   const void* A, const void* B, void* C, int32_t epilogue, const void* bias,
                   const void* R, const void* R2, void* C2, const int32_t* row_valid, int32_t accumulate,

@@ -17,7 +17,7 @@ DS_OK, DS_EINVAL, DS_EINFEASIBLE, DS_ENOMEM, DS_EOVERFLOW, DS_EHIP, DS_ELAYOUT, 
 DS_COST_POLY_GPT, DS_COST_POLY_T5, DS_COST_TABLE = 0, 1, 2
 DS_MODEL_GPT, DS_MODEL_T5 = 0, 1
 DS_DTYPE_F32, DS_DTYPE_BF16 = 0, 1
-DS_EPI_NONE, DS_EPI_GELU, DS_EPI_RESID, DS_EPI_DGELU, DS_EPI_ACC32, DS_EPI_GATE, DS_EPI_DGATE = range(7)
+DS_EPI_NONE, DS_EPI_GELU, DS_EPI_RESID, DS_EPI_DGELU, DS_EPI_ACC32, DS_EPI_GATE, DS_EPI_DGATE, DS_EPI_GELU_D, DS_EPI_MULR = range(9)
 
 PROF_KINDS = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "norm", "colsum", "other", "transpose")
 

@@ -93,6 +93,13 @@ __device__ __forceinline__ float gelu_sigmoid(float z, float w) {      // w = z 
     return __builtin_amdgcn_rcpf(1.0f + e);
 }
 __device__ __forceinline__ float gelu_f(float z) { return z * gelu_sigmoid(z, z * z); }
+__device__ __forceinline__ void gelu_and_grad_f(float z, float& gelu, float& grad) {   // both from one logistic term
+    constexpr float c2 = 2.0f * 0.7978845608028654f, c6a = 3.0f * 0.044715f * c2;
+    const float w = z * z;
+    const float s = gelu_sigmoid(z, w);
+    gelu = z * s;
+    grad = s * __builtin_fmaf(z * __builtin_fmaf(c6a, w, c2), 1.0f - s, 1.0f);
+}
 __device__ __forceinline__ float gelu_grad_f(float z) {
     constexpr float c2 = 2.0f * 0.7978845608028654f, c6a = 3.0f * 0.044715f * c2;
     const float w = z * z;

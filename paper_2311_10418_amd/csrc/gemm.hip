@@ -42,7 +42,7 @@ __device__ __forceinline__ void epilogue_prefetch(int m, int n, int N, const Gem
     if (EPI == DS_EPI_RESID) {
         if (p.row_valid) q.valid = p.row_valid[m] >= 0;
         load8_raw(reinterpret_cast<const T*>(p.R) + off, q.r);
-    } else if (EPI == DS_EPI_DGELU || EPI == DS_EPI_GATE) {
+    } else if (EPI == DS_EPI_DGELU || EPI == DS_EPI_GATE || EPI == DS_EPI_MULR) {
         load8_raw(reinterpret_cast<const T*>(p.R) + off, q.r);
     } else if (EPI == DS_EPI_DGATE) {
         load8_raw(reinterpret_cast<const T*>(p.R) + off, q.r);
@@ -50,7 +50,7 @@ __device__ __forceinline__ void epilogue_prefetch(int m, int n, int N, const Gem
     }
 }
 template <int EPI> constexpr bool epilogue_reads() {
-    return EPI == DS_EPI_RESID || EPI == DS_EPI_DGELU || EPI == DS_EPI_GATE || EPI == DS_EPI_DGATE;
+    return EPI == DS_EPI_RESID || EPI == DS_EPI_DGELU || EPI == DS_EPI_GATE || EPI == DS_EPI_DGATE || EPI == DS_EPI_MULR;
 }
 
 template <class T, int EPI>
@@ -83,6 +83,25 @@ __device__ __forceinline__ void epilogue8(int m, int n, int N, float (&acc)[8], 
 #pragma unroll
         for (int j = 0; j < 8; ++j) { z[j] = to_f32(from_f32<T>(acc[j])); a[j] = gelu_f(z[j]); }
         Vec8<T>::store_nt(reinterpret_cast<T*>(p.C2) + off, a);
+    } else if (EPI == DS_EPI_GELU_D) {
+        // what the layer's backward needs of the pre-activation is GELU'(z) alone: it is computed here, where the
+        // logistic term is at hand anyway, and stored in place of z; the backward epilogue is then one multiplication
+        float dz[8], a[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) gelu_and_grad_f(acc[j], a[j], dz[j]);
+        Vec8<T>::store_nt(C + off, dz);
+        Vec8<T>::store_nt(reinterpret_cast<T*>(p.C2) + off, a);
+    } else if (EPI == DS_EPI_MULR) {
+        float r[8];
+        if (pre) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) r[j] = to_f32(pre->r[j]);
+        } else {
+            Vec8<T>::load(reinterpret_cast<const T*>(p.R) + off, r);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] *= r[j];
+        Vec8<T>::store_nt(C + off, acc);
     } else if (EPI == DS_EPI_RESID) {
         if (pre) {
 #pragma unroll
@@ -623,7 +642,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
                     Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
                 } else if (epilogue_reads<EPI>()) {
                     epilogue8<bf16_t, EPI>(m, n, N, v, C, p, &pre[i][pss]);
-                    if constexpr (EPI == DS_EPI_DGELU) {
+                    if constexpr (EPI == DS_EPI_DGELU || EPI == DS_EPI_MULR) {
 #pragma unroll
                         for (int j = 0; j < 8; ++j) csum[j] += v[j];
                     }
@@ -633,7 +652,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
             }
         }
     }
-    if constexpr (EPI == DS_EPI_DGELU) {
+    if constexpr (EPI == DS_EPI_DGELU || EPI == DS_EPI_MULR) {
         if (direct && p.colsum) {
             // lanes l, l + LPR, l + 2 LPR, ... hold the same columns: fold them, then one row of partial sums per
             // (tile row, wavefront row), written whether or not the wavefront had a valid row
@@ -818,7 +837,7 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
         DS_LAUNCH_CHECK();
     } else if (tail_splits > 1) {
         bool with_sums = false;
-        if constexpr (EPI == DS_EPI_DGELU) {
+        if constexpr (EPI == DS_EPI_DGELU || EPI == DS_EPI_MULR) {
             if (p.colsum) {
                 with_sums = true;
                 hipLaunchKernelGGL(tail_finish_sums_kernel<EPI>, dim3(2, tiles - n_main), dim3(1024), 0, st, M, N, tiles_m, tiles_n,
@@ -855,9 +874,9 @@ ds_status dispatch_epi(int dtype, int ta, int tb, int M, int N, int K, const voi
 
 bool gemm_colsum_fused(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int32_t N, int32_t K, const void* A, const void* B,
                        const void* C, int32_t epilogue) {
-    // the conditions under which dispatch_epi takes launch_nt<DS_EPI_DGELU, false>
+    // the conditions under which dispatch_epi takes launch_nt<DS_EPI_DGELU or DS_EPI_MULR, false>
     static_assert(NT_WM == 2, "two rows of partial column sums per tile row");
-    if (epilogue != DS_EPI_DGELU || dtype != DS_DTYPE_BF16 || ta || !tb) return false;
+    if ((epilogue != DS_EPI_DGELU && epilogue != DS_EPI_MULR) || dtype != DS_DTYPE_BF16 || ta || !tb) return false;
     if (N % BN || K % BK || M < 1 || K < 1) return false;
     return ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && ((uintptr_t)C % 16 == 0);
 }
@@ -877,6 +896,12 @@ ds_status launch_gemm(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int32_t 
     case DS_EPI_RESID:
         if (!p.R) return DS_EINVAL;
         return dispatch_epi<DS_EPI_RESID>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
+    case DS_EPI_GELU_D:
+        if (!p.C2) return DS_EINVAL;
+        return dispatch_epi<DS_EPI_GELU_D>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
+    case DS_EPI_MULR:
+        if (!p.R) return DS_EINVAL;
+        return dispatch_epi<DS_EPI_MULR>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);
     case DS_EPI_DGELU:
         if (!p.R) return DS_EINVAL;
         return dispatch_epi<DS_EPI_DGELU>(dtype, ta, tb, M, N, K, A, B, C, p, force_generic, split_ws, split_ws_floats, st);

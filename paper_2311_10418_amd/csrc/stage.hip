@@ -306,19 +306,20 @@ struct Ops {
                     const void* R2, void* C2) {
         return gemm_raw(DS_PROF_GEMM_DGRAD, 0, 1, sm.R, K, N, dY, W, C, epi, nullptr, R, R2, C2, nullptr, 0);
     }
-    // dZ[rows,K] = (dY W^T) * GELU'(Z) and bias_grad[K] (+)= column sums of dZ.  Where the GEMM kernel can, the sums come
-    // out of its epilogue (one partial row per 128 rows, then a small reduction); otherwise from a pass over dZ.
-    ds_status dgrad_gelu_bias(const Stream& sm, int K, int N, const void* dY, const void* W, void* dZ, const void* Z,
+    // dZ[rows,K] = (dY W^T) * G with G = GELU'(Z) as the forward pass stored it, and bias_grad[K] (+)= column sums of dZ.
+    // Where the GEMM kernel can, the sums come out of its epilogue (one partial row per 128 rows, then a small
+    // reduction); otherwise from a pass over dZ.
+    ds_status dgrad_gelu_bias(const Stream& sm, int K, int N, const void* dY, const void* W, void* dZ, const void* G,
                               void* bias_grad) {
-        if (s->colsum_rows && gemm_colsum_fused(dt, 0, 1, sm.R, K, N, dY, W, dZ, DS_EPI_DGELU)) {
-            DS_TRY(gemm_raw(DS_PROF_GEMM_DGRAD, 0, 1, sm.R, K, N, dY, W, dZ, DS_EPI_DGELU, nullptr, Z, nullptr, nullptr, nullptr, 0,
+        if (s->colsum_rows && gemm_colsum_fused(dt, 0, 1, sm.R, K, N, dY, W, dZ, DS_EPI_MULR)) {
+            DS_TRY(gemm_raw(DS_PROF_GEMM_DGRAD, 0, 1, sm.R, K, N, dY, W, dZ, DS_EPI_MULR, nullptr, G, nullptr, nullptr, nullptr, 0,
                             s->colsum_rows));
             s->launches++;
             return timed(s, DS_PROF_COLSUM, st, [&] {
                 return launch_reduce_partials((int32_t)gemm_colsum_rows(sm.R), K, s->colsum_rows, (float*)bias_grad, accumulate, st);
             });
         }
-        DS_TRY(dgrad(sm, K, N, dY, W, dZ, DS_EPI_DGELU, Z, nullptr, nullptr));
+        DS_TRY(dgrad(sm, K, N, dY, W, dZ, DS_EPI_MULR, G, nullptr, nullptr));
         return colsum(sm, K, dZ, bias_grad);
     }
     // dW[K,N] (+)= X[rows,K]^T dY[rows,N]
@@ -459,7 +460,7 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         DS_TRY(op.self_fwd(sm, 1, b.qkv, b.o, b.lse));
         DS_TRY(op.fwd(sm, d, d, b.o, w[l].w_o, b.wo_t, b.x1, DS_EPI_RESID, w[l].b_o, xl, nullptr, true));
         DS_TRY(op.norm_fwd(sm, 0, b.x1, w[l].ln2_g, w[l].ln2_b, b.u2, b.stats2));
-        DS_TRY(op.fwd(sm, F, d, b.u2, w[l].w_1, b.w1_t, b.z, DS_EPI_GELU, w[l].b_1, nullptr, b.a, false));
+        DS_TRY(op.fwd(sm, F, d, b.u2, w[l].w_1, b.w1_t, b.z, DS_EPI_GELU_D, w[l].b_1, nullptr, b.a, false));   // b.z := GELU'(z)
         if (!x_out) return DS_OK;
         return op.fwd(sm, d, F, b.a, w[l].w_2, b.w2_t, x_out, DS_EPI_RESID, w[l].b_2, b.x1, nullptr, true);
     };

@@ -72,6 +72,10 @@ def test_gemm_epilogues(dt, force):
     assert both_err(c, ref) <= tol and np.all(c[valid < 0] == 0)
     c, _ = run(ds.DS_EPI_DGELU, R=dR)
     assert both_err(c, acc * ost.gelu_grad(R.astype(np.float64))) <= tol
+    gd, a = run(ds.DS_EPI_GELU_D, bias=db)                # derivative kept instead of the pre-activation
+    assert both_err(gd, ost.gelu_grad(acc + bias)) <= tol and both_err(a, ost.gelu(acc + bias)) <= tol
+    c, _ = run(ds.DS_EPI_MULR, R=dR)
+    assert both_err(c, acc * R) <= tol
     zu, h = run(ds.DS_EPI_GATE, R=dR)
     assert both_err(zu, acc) <= tol and both_err(h, ost.gelu(R.astype(np.float64)) * acc) <= tol
     g1, g2 = run(ds.DS_EPI_DGATE, R=dR, R2=dR2)
@@ -374,6 +378,10 @@ def test_gemm_nt_epilogues(use_ws, M, N, K):
     assert both_err(c, (acc + bias + R) * (valid[:, None] >= 0)) <= tol and np.all(c[valid < 0] == 0)
     c, _ = run(ds.DS_EPI_DGELU, R=dR)
     assert both_err(c, acc * ost.gelu_grad(R.astype(np.float64))) <= tol
+    gd, a = run(ds.DS_EPI_GELU_D, bias=db)                # derivative kept instead of the pre-activation
+    assert both_err(gd, ost.gelu_grad(acc + bias)) <= tol and both_err(a, ost.gelu(acc + bias)) <= tol
+    c, _ = run(ds.DS_EPI_MULR, R=dR)
+    assert both_err(c, acc * R) <= tol
     zu, h = run(ds.DS_EPI_GATE, R=dR)
     assert both_err(zu, acc) <= tol and both_err(h, ost.gelu(R.astype(np.float64)) * acc) <= tol
     g1, g2 = run(ds.DS_EPI_DGATE, R=dR, R2=dR2)
