@@ -13,6 +13,9 @@
 // and row-contiguous.  Work-group ids are remapped so that each XCD (own L2) gets a contiguous run of tiles.
 #include "gemm.hpp"
 
+#include <atomic>
+#include <mutex>
+
 
 namespace {
 
@@ -261,12 +264,24 @@ __host__ __device__ __forceinline__ void nt_tile_coords(int logical, int tiles_m
 // come out of LDS through the transpose read ds_read_b64_tr_b16, 4 k-rows per read; both operands
 // use the same k order, so the contraction is unchanged.  K may be ragged: rows past the end read
 // zeros.  This form needs no transposed copies of the activations.
-template <int EPI, int WM, int WN, bool TNF>
+//
+// PS (persistent form, NT only, no uniform split-K): the first ps_wgs work-groups, one per compute unit, stay resident
+// and take the n_main unsplit tiles one after another; the tail pieces are ordinary work-groups behind them.  The
+// tiles keep their XCD-contiguous numbering: work-group w serves the run of XCD w % 8, starts with tile w / 8 of that
+// run and draws every further one from that XCD's counter (ps_ctr[xcd], one atomic per tile, issued a whole main
+// loop before its result is needed), so a faster compute unit takes more tiles, as under the hardware dispatcher.
+// What persistence buys: the first K tile of the NEXT tile is requested before the epilogue of the current one
+// starts (into stage 0, while the epilogue stages through LDS above it), so neither the latency of that first fetch
+// nor the end of one work-group and the start of the next leaves the matrix cores idle.  The last work-group to
+// finish puts the counters back to zero (ps_ctr[8] counts the finished ones).
+template <int EPI, int WM, int WN, bool TNF, bool PS>
 __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
                                                                        const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
                                                                        int tiles_m, int tiles_n, int splits,
                                                                        int n_main, int tail_splits,
-                                                                       float* __restrict__ split_ws, GemmEpi p) {
+                                                                       float* __restrict__ split_ws, GemmEpi p,
+                                                                       int ps_wgs, int* __restrict__ ps_ctr) {
+    static_assert(!(PS && TNF), "the persistent form exists for the NT kernel only");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int NW = WM * WN;                    // wavefronts
     constexpr int TM = 256 / WM / 32, TN = 256 / WN / 32;   // 32x32 MFMA tiles per wavefront
@@ -286,8 +301,18 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
     const int n_tiles = tiles_m * tiles_n;
     int logical, split, nsplit;
     bool tail = false;
-    {
-        const int pid = blockIdx.x;
+    const bool persistent = PS && (int)blockIdx.x < ps_wgs;
+    int run_start = 0, run_cnt = 0;                 // persistent: this XCD's run of unsplit tiles
+    if (persistent) {
+        const int xcd = blockIdx.x & 7;
+        const int per = n_main >> 3, rem = n_main & 7;
+        run_start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+        run_cnt = per + (xcd < rem ? 1 : 0);
+        logical = run_start + (blockIdx.x >> 3);    // (the host launches this form only with n_main >= 2 ps_wgs)
+        split = 0;
+        nsplit = 1;
+    } else {
+        const int pid = PS ? (int)blockIdx.x - ps_wgs + n_main : (int)blockIdx.x;
         const int total = splits > 1 ? n_tiles * splits : n_main;
         if (pid < total) {
             const int xcd = pid & 7, local = pid >> 3;
@@ -305,9 +330,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
             tail = true;
         }
     }
-    int tile_m, tile_n;
-    nt_tile_coords(logical, tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // K tiles: TN form 32 k-rows of 512 bytes, ring of 4 stages; NT form 64 k (one whole 128-byte line per row and
     // request, which is what the L2 serves at full rate), 2 stages
@@ -325,343 +347,400 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_nt_kernel(int M, in
     // sustains about a sixth more than 32x32x16 on random operands, at the same LDS traffic per flop)
     constexpr int TM16 = 2 * TM, TN16 = 2 * TN, HA = TM16 / 2;
     f32x4_t acc[TM16][TN16];
-#pragma unroll
-    for (int i = 0; i < TM16; ++i)
-#pragma unroll
-        for (int j = 0; j < TN16; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-    if (t_begin < t_end) {
-        uint32_t offA[LPW], offB[LPW];
+    // what the transfers of a tile need: its corner, the operand bases there and the per-lane offsets (set_tile)
+    int tile_m = 0, tile_n = 0, m0 = 0, n0 = 0;
+    const char* pa = nullptr;
+    const char* pb = nullptr;
+    uint32_t offAg[LPW], offBg[LPW];                                // per-lane offsets as a transfer group wants them
+    auto set_tile = [&](int lg) {
+        nt_tile_coords(lg, tiles_m, tiles_n, tile_m, tile_n);
+        m0 = tile_m * BM;
+        n0 = tile_n * BN;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int u = (wave * LPW + i) * 64 + lane;
+            uint32_t oa, ob;
             if constexpr (!TNF) {                                    // 16-byte unit of the 256 x 8 tile (128-byte rows)
                 const int row = u >> 3, slot = u & 7;
                 const int chunk = slot ^ ((row >> 1) & 7);
                 int ra_ = m0 + row;
                 ra_ = ra_ < M ? ra_ : M - 1;                        // rows past the edge: clamped, never stored
-                offA[i] = (uint32_t)(((long long)(ra_ - m0) * K + chunk * 8) * 2);
-                offB[i] = (uint32_t)(((long long)row * K + chunk * 8) * 2);
+                oa = (uint32_t)(((long long)(ra_ - m0) * K + chunk * 8) * 2);
+                ob = (uint32_t)(((long long)row * K + chunk * 8) * 2);
+                offAg[i] = dma_lane_offset<LPW>(oa, i);
+                offBg[i] = dma_lane_offset<LPW>(ob, i);
             } else {                                                // 16-byte unit of the 32 k-row tile (512-byte rows)
                 const int row = u >> 5, pos = u & 31;
                 const int chunk = (((pos >> 1) ^ (row & 7)) << 1) | (pos & 1);
-                offA[i] = (uint32_t)(((long long)row * M + chunk * 8) * 2);
-                offB[i] = (uint32_t)(((long long)row * N + chunk * 8) * 2);
+                oa = (uint32_t)(((long long)row * M + chunk * 8) * 2);
+                ob = (uint32_t)(((long long)row * N + chunk * 8) * 2);
+                offAg[i] = dma_lane_offset<2 * LPW>(oa, i);         // group of four: A, A, B, B
+                offBg[i] = dma_lane_offset<2 * LPW>(ob, LPW + i);
             }
         }
-        uint32_t offAg[LPW], offBg[LPW];                            // the same offsets as a transfer group wants them
-#pragma unroll
-        for (int i = 0; i < LPW; ++i) {
-            if constexpr (TNF) {                                    // group of four: A, A, B, B
-                offAg[i] = dma_lane_offset<2 * LPW>(offA[i], i);
-                offBg[i] = dma_lane_offset<2 * LPW>(offB[i], LPW + i);
-            } else {
-                offAg[i] = dma_lane_offset<LPW>(offA[i], i);
-                offBg[i] = dma_lane_offset<LPW>(offB[i], i);
-            }
-        }
-        const uint32_t lds0 = lds_address(smem);
-        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-        const char* pa = reinterpret_cast<const char*>(A) + (TNF ? (long long)m0 * 2 : (long long)m0 * K * 2);
-        const char* pb = reinterpret_cast<const char*>(B) + (TNF ? (long long)n0 * 2 : (long long)n0 * K * 2);
-        const long long tile_step_a = TNF ? (long long)DK * M * 2 : DK * 2;
-        const long long tile_step_b = TNF ? (long long)DK * N * 2 : DK * 2;
-        const int frag_row = lane & 15, frag_grp = lane >> 4;       // operand row / k group of this lane
-        const int t_last = t_end - 1;
-        // The transfers of a K tile, in the groups the main loops hand out between their MFMAs (a wavefront cannot issue
-        // anything else while a transfer of its own passes the address stage of the texture path, so they are neither
-        // issued in one burst after the barrier, which left the matrix cores idle for about a quarter of every tile,
-        // nor one at a time with an M0 of their own: a write of M0 waits for the transfer before it).
-        //   NT form: s = 0 / 1 = this wavefront's part of the A / B tile, LPW transfers under one M0; wavefront-uniform
-        //     base in scalar registers + per-lane offsets that never change (stepping along K costs no vector
-        //     instruction); LDS destinations are scalar integers, not generic pointers.
-        //   TN form: s = 0 = both parts (A, A, B, B in one 4 KB block of LDS per wavefront), through two buffer
-        //     descriptors whose lengths end at the last row of a ragged K: rows past the end read zeros, with no
-        //     per-lane test.
-        auto issue_one = [&](int tile, int stage, int s) {
-            tile = tile < t_last ? tile : t_last;
-            if constexpr (TNF) {
-                static_assert(!TNF || LPW == 2, "one group = two A and two B transfers");
-                const int k_left = K - tile * DK;
-                const uint32_t rows = (uint32_t)(k_left < DK ? k_left : DK);
-                const i32x4_t buf_a = make_raw_buffer(pa + tile * tile_step_a - 3072, rows * (uint32_t)M * 2u + 3072u);
-                const i32x4_t buf_b = make_raw_buffer(pb + tile * tile_step_b - 3072, rows * (uint32_t)N * 2u + 3072u);
-                lds_dma16_buffers_2x2(buf_a, offAg[0], offAg[1], buf_b, offBg[0], offBg[1],
-                                      lds0 + stage * STAGE + wave_u * (2 * LPW * 1024));
-            } else {
-                const uint32_t dst_g = lds0 + stage * STAGE + (s ? HALF : 0) + wave_u * (LPW * 1024);
-                if (s) lds_dma16_group<LPW>(dma_group_base<LPW>(pb + tile * tile_step_b), offBg, dst_g);
-                else lds_dma16_group<LPW>(dma_group_base<LPW>(pa + tile * tile_step_a), offAg, dst_g);
-            }
-        };
-        auto issue = [&](int tile, int stage) {
-#pragma unroll
-            for (int s = 0; s < (TNF ? 1 : 2); ++s) issue_one(tile, stage, s);
-        };
-        // NT: 128-byte rows: 16 consecutive rows at one chunk index must hit 16 different 16-byte units of a 256-byte
-        // window: rows 2q and 2q+1 differ by 128 bytes, the XOR with (row/2)%8 separates the 8 row pairs
-        auto off64 = [](int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); };
-        // TN: 512-byte rows.  One operand fragment (16 features x 32 k) is two transpose reads, each 16 k-rows x 32
-        // bytes: lane (i = lane%16, g = lane/16) addresses k-row 4g + i/4 (+16 for the second read) at features
-        // (i%4)*4 of the 16-feature unit and receives feature i at k-rows 4g..4g+3.  The 32 lanes served together
-        // touch 8 k-rows, so the 32-byte unit index is XORed with row%8.  Both operands use the same k order, so the
-        // contraction is unchanged.
-        const int tr_x = 4 * ((lane >> 4) & 1) + ((lane >> 2) & 3);
-        // (LDS layout of a TN stage: per wavefront w one 4 KB block = k-rows 4w .. 4w+3 of the A tile, then of the B tile)
-        const int tr_base = (lane >> 4) * 4096 + ((lane & 15) >> 2) * 512 + (lane & 3) * 8;
-        auto read_tr = [&](const char* base, int unit) {
-            typedef short s16x4_t __attribute__((ext_vector_type(4)));
-            typedef short s16x8_t __attribute__((ext_vector_type(8)));
-            typedef __attribute__((address_space(3))) s16x4_t* lds4_t;
-            const char* q = base + tr_base + ((unit ^ tr_x) << 5);
-            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)q);
-            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(q + 4 * 4096));
-            const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            return __builtin_bit_cast(bf16x8_t, v);
-        };
-        // fragments of 32-deep k step `ks` of a stage: HA of this wavefront's TM16 row units (half h), all TN16 column units
-        auto load_a = [&](int stage, int ks, int h, bf16x8_t (&fa)[HA]) {
-            const char* a_base = smem + stage * STAGE;
-#pragma unroll
-            for (int i = 0; i < HA; ++i) {
-                if constexpr (TNF) fa[i] = read_tr(a_base, wm * TM16 + h * HA + i);
-                else fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off64(wm * (TM * 32) + (h * HA + i) * 16 + frag_row, ks * 4 + frag_grp));
-            }
-        };
-        auto load_b = [&](int stage, int ks, bf16x8_t (&fb)[TN16]) {
-            const char* b_base = smem + stage * STAGE + (TNF ? 2 * 1024 : HALF);
-#pragma unroll
-            for (int j = 0; j < TN16; ++j) {
-                if constexpr (TNF) fb[j] = read_tr(b_base, wn * TN16 + j);
-                else fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off64(wn * (TN * 32) + j * 16 + frag_row, ks * 4 + frag_grp));
-            }
-        };
-        // One half step: HA x TN16 MFMAs on row units h*HA.., with transfers [s0, s0 + cnt) of K tile `tile` handed
-        // out evenly between them.  Operands swapped on purpose: the accumulator block is C^T (rows = n, columns =
-        // m), so a lane holds 4 CONSECUTIVE n per block and the epilogue stages with 16-byte writes.
-        auto mma_dma = [&](int h, const bf16x8_t (&fa)[HA], const bf16x8_t (&fb)[TN16], int tile, int stage, int s0, int cnt) {
-            int done = 0;
-#pragma unroll
-            for (int i = 0; i < HA; ++i)
-#pragma unroll
-                for (int jj = 0; jj < TN16; ++jj) {
-                    // boustrophedon order: consecutive MFMAs share one operand and the other changes to its neighbour
-                    // (measured: about 2 % more sustained MFMA rate at the power limit than row-major order)
-                    const int j = (i & 1) ? TN16 - 1 - jj : jj;
-                    const int q = i * TN16 + jj;
-#ifdef X_QPOS
-                    if (done < cnt && q == (2 * done + 1) * (HA * TN16) / (2 * cnt)) {
-#else
-                    if (done < cnt && q == done * (HA * TN16) / cnt) {
-#endif
-                        __builtin_amdgcn_sched_barrier(0);
-                        issue_one(tile, stage, s0 + done);
-                        __builtin_amdgcn_sched_barrier(0);
-                        ++done;
-                    }
-                    acc[h * HA + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[h * HA + i][j], 0, 0, 0);
-                }
-        };
-        // Software pipeline: the fragments of the next half step are read from LDS while the MFMAs of the current
-        // one run, ACROSS the tile boundary too, so that no wavefront waits on LDS latency right after the barrier
-        // (all 8 wavefronts leave it together, so nobody would be left to cover for the others).
-        bf16x8_t fax[HA], fay[HA], fbx[TN16], fby[TN16];
-        // transfers per K tile and wavefront: NVM instructions, handed out in NTR groups (TN: one, NT: A part, B part)
-        constexpr int NVM = 2 * LPW, NTR = TNF ? 1 : 2;
-        if constexpr (TNF) {
-            // one 32-deep k step per tile, two half steps; the transfers of tile tl+3 go out in the first one, before the
-            // barrier of iteration tl
-            issue(t_begin, 0);
-            issue(t_begin + 1, 1);
-            issue(t_begin + 2, 2);
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * NVM));         // tile t_begin: at most the two newest tiles outstanding
-            __builtin_amdgcn_s_barrier();
-            load_b(0, 0, fbx);
-            load_a(0, 0, 0, fax);
-            auto tn_iter = [&](int tl, bf16x8_t (&fb_cur)[TN16], bf16x8_t (&fb_next)[TN16]) {
-                const int st_ = (tl - t_begin) & (NS - 1);
-                // stage (tl-1)%4 is free: every wavefront finished reading it before the barrier it has passed last
-                load_a(st_, 0, 1, fay);
-                __builtin_amdgcn_sched_barrier(0);
-                mma_dma(0, fax, fb_cur, tl + 3, (st_ + 3) & (NS - 1), 0, 1);
-                __builtin_amdgcn_sched_barrier(0);
-                // tile tl+1: this wavefront's part has landed (tile tl+2 and the new transfers outstanding), its LDS
-                // reads are done ...
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * NVM) & 0xF0FF);        // vmcnt(2 NVM) lgkmcnt(0)
-                __builtin_amdgcn_s_barrier();                       // ... and everyone's
-                load_b((st_ + 1) & (NS - 1), 0, fb_next);           // past the last tile: a stale but valid stage, unused
-                load_a((st_ + 1) & (NS - 1), 0, 0, fax);
-                __builtin_amdgcn_sched_barrier(0);
-                mma_dma(1, fay, fb_cur, tl + 3, (st_ + 3) & (NS - 1), 1, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            };
-            int tl = t_begin;
-            for (; tl + 1 < t_end; tl += 2) {
-                tn_iter(tl, fbx, fby);
-                tn_iter(tl + 1, fby, fbx);
-            }
-            if (tl < t_end) tn_iter(tl, fbx, fby);
-        } else {
-            // two 64 KB stages, two 32-deep k steps = four half steps per tile, one barrier per tile.  Transfers of
-            // tile tl+1 ride on the four half steps between two barriers: NT_G0 on the one right after the barrier
-            // (the last half step of tile tl-1), then NT_G1, NT_G2, the rest
-            static_assert(NT_G0 + NT_G1 + NT_G2 <= NTR, "more transfers scheduled than a tile has");
-            issue(t_begin, 0);
-            __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0)
-            __builtin_amdgcn_s_barrier();
-#pragma unroll
-            for (int s_ = 0; s_ < NT_G0; ++s_) issue_one(t_begin + 1, 1, s_);
-            load_b(0, 0, fbx);
-            load_a(0, 0, 0, fax);
-            for (int tl = t_begin; tl < t_end; ++tl) {
-                const int st_ = (tl - t_begin) & 1;
-                load_a(st_, 0, 1, fay);
-                __builtin_amdgcn_sched_barrier(0);
-                mma_dma(0, fax, fbx, tl + 1, st_ ^ 1, NT_G0, NT_G1);
-                __builtin_amdgcn_sched_barrier(0);
-                load_b(st_, 1, fby);
-                load_a(st_, 1, 0, fax);
-                __builtin_amdgcn_sched_barrier(0);
-                mma_dma(1, fay, fbx, tl + 1, st_ ^ 1, NT_G0 + NT_G1, NT_G2);
-                __builtin_amdgcn_sched_barrier(0);
-                load_a(st_, 1, 1, fay);
-                __builtin_amdgcn_sched_barrier(0);
-                mma_dma(0, fax, fby, tl + 1, st_ ^ 1, NT_G0 + NT_G1 + NT_G2, NTR - NT_G0 - NT_G1 - NT_G2);
-                __builtin_amdgcn_sched_barrier(0);
-                __builtin_amdgcn_s_waitcnt(0x0070);                 // vmcnt(0) lgkmcnt(0): tile tl+1 landed, reads of tile tl done
-                __builtin_amdgcn_s_barrier();
-                // this stage is free from here on: tile tl+2 starts to arrive in it
-                load_b(st_ ^ 1, 0, fbx);                            // past the last tile: a reloaded copy of it, unused
-                load_a(st_ ^ 1, 0, 0, fax);
-                __builtin_amdgcn_sched_barrier(0);
-                mma_dma(1, fay, fby, tl + 2, st_, 0, NT_G0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        // drain the redundant tail transfers before LDS is reused by the epilogue (explicit: the compiler does not
-        // see transfers issued by lds_dma16)
-        __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0) lgkmcnt(0)
-        __builtin_amdgcn_s_barrier();
-    }
-
-    // ---- epilogue through LDS: per wavefront a [32][STG_LD] fp32 staging block
-    float* stage = reinterpret_cast<float*>(smem) + wave * (32 * STG_LD);
-    constexpr int LPR = TN * 4;                    // lanes per staged row (8 columns each)
-    const int rd_row = lane / LPR, rd_col = (lane % LPR) * 8;
-    constexpr int NPSS = 32 / (64 / LPR);          // staged rows each lane finishes per pass
-    const bool direct = !tail && splits == 1;      // this work-group applies the epilogue itself
-    // what the epilogue reads from memory, for every row this lane will finish: all in flight before the first pass
-    // (one pass ahead only for the two-operand gated form, which would not fit in registers otherwise)
-    constexpr bool PRE_ALL = EPI != DS_EPI_DGATE;
-    EpiPre<bf16_t> pre[TM][NPSS];
-    auto prefetch_pass = [&](int i) {
-#pragma unroll
-        for (int pss = 0; pss < NPSS; ++pss) {
-            const int m = m0 + wm * (TM * 32) + i * 32 + pss * (64 / LPR) + rd_row;
-            if (m < M) epilogue_prefetch<bf16_t, EPI>(m, n0 + wn * (TN * 32) + rd_col, N, p, pre[i][pss]);
-        }
+        pa = reinterpret_cast<const char*>(A) + (TNF ? (long long)m0 * 2 : (long long)m0 * K * 2);
+        pb = reinterpret_cast<const char*>(B) + (TNF ? (long long)n0 * 2 : (long long)n0 * K * 2);
     };
-    if (epilogue_reads<EPI>() && direct && PRE_ALL) {
+    set_tile(logical);
+    bool primed = false;                            // persistent: the first K tile of this tile is already on its way
+    constexpr int PS_SLOT = 65536 + NW * 32 * (TN * 32 + 4) * 4;    // LDS word through which wavefront 0 hands on the next tile
+    constexpr int STG_OFF = PS ? 65536 : 0;         // epilogue staging: above stage 0, which already receives the next tile
+    for (;;) {
+        // the epilogue below belongs to the tile the main loop has just finished, not to the one set_tile has moved on to
+        const int em0 = m0, en0 = n0, etile_m = tile_m, elogical = logical;
+        int next_local = 0x7fffffff;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) prefetch_pass(i);
-    }
-    if constexpr (EPI == DS_EPI_NONE) {
-        // Plain output (+ bias): nothing is computed after the transposition, so the bias is added and the value
-        // rounded to bf16 BEFORE staging: half the LDS traffic of the fp32 staging below, which bounds the epilogue.
-        if (direct) {
-            bf16_t* stage_h = reinterpret_cast<bf16_t*>(stage);
-            constexpr int LD_H = TN * 32 + 8;                       // bf16 row stride (144 bytes: 8-byte writes of 16 rows spread over the banks)
-            float bias4[TN16][4];
+        for (int i = 0; i < TM16; ++i)
 #pragma unroll
             for (int j = 0; j < TN16; ++j)
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    bias4[j][e] = p.bias ? (float)reinterpret_cast<const bf16_t*>(p.bias)[n0 + wn * (TN * 32) + j * 16 + 4 * (lane >> 4) + e] : 0.f;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                wave_lds_sync();
-#pragma unroll
-                for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-                    for (int j = 0; j < TN16; ++j) {
-                        typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
-                        const f32x4_t a4 = acc[2 * i + i2][j];
-                        const bf16x4_t h4 = {(bf16_t)(a4[0] + bias4[j][0]), (bf16_t)(a4[1] + bias4[j][1]),
-                                             (bf16_t)(a4[2] + bias4[j][2]), (bf16_t)(a4[3] + bias4[j][3])};
-                        *reinterpret_cast<bf16x4_t*>(stage_h + (i2 * 16 + (lane & 15)) * LD_H + j * 16 + 4 * (lane >> 4)) = h4;
-                    }
-                wave_lds_sync();
-#pragma unroll
-                for (int pss = 0; pss < NPSS; ++pss) {
-                    const int row = pss * (64 / LPR) + rd_row;
-                    const int m = m0 + wm * (TM * 32) + i * 32 + row;
-                    const int n = n0 + wn * (TN * 32) + rd_col;
-                    if (m < M) {
-                        const bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(stage_h + row * LD_H + rd_col);
-                        __builtin_nontemporal_store(v, reinterpret_cast<bf16x8_t*>(C + (size_t)m * N + n));
-                    }
-                }
-            }
-            return;
-        }
-    }
-    // column sums of what this lane writes (DGELU: the bias gradient of the layer below comes out of this kernel
-    // instead of a pass over the stored tensor); every lane finishes TM * NPSS rows of the same 8 columns
-    float csum[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) csum[j] = 0.f;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        if (epilogue_reads<EPI>() && direct && !PRE_ALL) prefetch_pass(i);
-        wave_lds_sync();            // the staging block is private to the wavefront: no work-group barrier (which would
-                                    // also wait for the global stores of the previous pass to be acknowledged)
-#pragma unroll
-        for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-            for (int j = 0; j < TN16; ++j) {    // lane = row m (lane%16 of block 2i+i2); its 4 registers = columns 4*(lane/16) + 0..3
-                const f32x4_t a4 = acc[2 * i + i2][j];
-                *reinterpret_cast<float4*>(stage + (i2 * 16 + (lane & 15)) * STG_LD + j * 16 + 4 * (lane >> 4)) =
-                    make_float4(a4[0], a4[1], a4[2], a4[3]);
-            }
-        wave_lds_sync();
-#pragma unroll
-        for (int pss = 0; pss < NPSS; ++pss) {
-            const int row = pss * (64 / LPR) + rd_row;
-            const int m = m0 + wm * (TM * 32) + i * 32 + row;
-            const int n = n0 + wn * (TN * 32) + rd_col;
-            if (m < M) {
-                float v[8];
-                const float4 x0 = *reinterpret_cast<const float4*>(stage + row * STG_LD + rd_col);
-                const float4 x1 = *reinterpret_cast<const float4*>(stage + row * STG_LD + rd_col + 4);
-                v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
-                if (tail) {
-                    Vec8<float>::store(split_ws + ((size_t)((logical - n_main) * tail_splits + split) * BM + (m - m0)) * BN + (n - n0), v);
-                } else if (splits > 1) {
-                    Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
-                } else if (epilogue_reads<EPI>()) {
-                    epilogue8<bf16_t, EPI>(m, n, N, v, C, p, &pre[i][pss]);
-                    if constexpr (EPI == DS_EPI_DGELU || EPI == DS_EPI_MULR) {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) csum[j] += v[j];
-                    }
+                for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+
+        if (t_begin < t_end) {
+            const uint32_t lds0 = lds_address(smem);
+            const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+            const long long tile_step_a = TNF ? (long long)DK * M * 2 : DK * 2;
+            const long long tile_step_b = TNF ? (long long)DK * N * 2 : DK * 2;
+            const int frag_row = lane & 15, frag_grp = lane >> 4;       // operand row / k group of this lane
+            const int t_last = t_end - 1;
+            // The transfers of a K tile, in the groups the main loops hand out between their MFMAs (a wavefront cannot issue
+            // anything else while a transfer of its own passes the address stage of the texture path, so they are neither
+            // issued in one burst after the barrier, which left the matrix cores idle for about a quarter of every tile,
+            // nor one at a time with an M0 of their own: a write of M0 waits for the transfer before it).
+            //   NT form: s = 0 / 1 = this wavefront's part of the A / B tile, LPW transfers under one M0; wavefront-uniform
+            //     base in scalar registers + per-lane offsets that never change (stepping along K costs no vector
+            //     instruction); LDS destinations are scalar integers, not generic pointers.
+            //   TN form: s = 0 = both parts (A, A, B, B in one 4 KB block of LDS per wavefront), through two buffer
+            //     descriptors whose lengths end at the last row of a ragged K: rows past the end read zeros, with no
+            //     per-lane test.
+            auto issue_one = [&](int tile, int stage, int s) {
+                tile = tile < t_last ? tile : t_last;
+                if constexpr (TNF) {
+                    static_assert(!TNF || LPW == 2, "one group = two A and two B transfers");
+                    const int k_left = K - tile * DK;
+                    const uint32_t rows = (uint32_t)(k_left < DK ? k_left : DK);
+                    const i32x4_t buf_a = make_raw_buffer(pa + tile * tile_step_a - 3072, rows * (uint32_t)M * 2u + 3072u);
+                    const i32x4_t buf_b = make_raw_buffer(pb + tile * tile_step_b - 3072, rows * (uint32_t)N * 2u + 3072u);
+                    lds_dma16_buffers_2x2(buf_a, offAg[0], offAg[1], buf_b, offBg[0], offBg[1],
+                                          lds0 + stage * STAGE + wave_u * (2 * LPW * 1024));
                 } else {
-                    epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
+                    const uint32_t dst_g = lds0 + stage * STAGE + (s ? HALF : 0) + wave_u * (LPW * 1024);
+                    if (s) lds_dma16_group<LPW>(dma_group_base<LPW>(pb + tile * tile_step_b), offBg, dst_g);
+                    else lds_dma16_group<LPW>(dma_group_base<LPW>(pa + tile * tile_step_a), offAg, dst_g);
+                }
+            };
+            auto issue = [&](int tile, int stage) {
+#pragma unroll
+                for (int s = 0; s < (TNF ? 1 : 2); ++s) issue_one(tile, stage, s);
+            };
+            // NT: 128-byte rows: 16 consecutive rows at one chunk index must hit 16 different 16-byte units of a 256-byte
+            // window: rows 2q and 2q+1 differ by 128 bytes, the XOR with (row/2)%8 separates the 8 row pairs
+            auto off64 = [](int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); };
+            // TN: 512-byte rows.  One operand fragment (16 features x 32 k) is two transpose reads, each 16 k-rows x 32
+            // bytes: lane (i = lane%16, g = lane/16) addresses k-row 4g + i/4 (+16 for the second read) at features
+            // (i%4)*4 of the 16-feature unit and receives feature i at k-rows 4g..4g+3.  The 32 lanes served together
+            // touch 8 k-rows, so the 32-byte unit index is XORed with row%8.  Both operands use the same k order, so the
+            // contraction is unchanged.
+            const int tr_x = 4 * ((lane >> 4) & 1) + ((lane >> 2) & 3);
+            // (LDS layout of a TN stage: per wavefront w one 4 KB block = k-rows 4w .. 4w+3 of the A tile, then of the B tile)
+            const int tr_base = (lane >> 4) * 4096 + ((lane & 15) >> 2) * 512 + (lane & 3) * 8;
+            auto read_tr = [&](const char* base, int unit) {
+                typedef short s16x4_t __attribute__((ext_vector_type(4)));
+                typedef short s16x8_t __attribute__((ext_vector_type(8)));
+                typedef __attribute__((address_space(3))) s16x4_t* lds4_t;
+                const char* q = base + tr_base + ((unit ^ tr_x) << 5);
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)q);
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(q + 4 * 4096));
+                const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                return __builtin_bit_cast(bf16x8_t, v);
+            };
+            // fragments of 32-deep k step `ks` of a stage: HA of this wavefront's TM16 row units (half h), all TN16 column units
+            auto load_a = [&](int stage, int ks, int h, bf16x8_t (&fa)[HA]) {
+                const char* a_base = smem + stage * STAGE;
+#pragma unroll
+                for (int i = 0; i < HA; ++i) {
+                    if constexpr (TNF) fa[i] = read_tr(a_base, wm * TM16 + h * HA + i);
+                    else fa[i] = *reinterpret_cast<const bf16x8_t*>(a_base + off64(wm * (TM * 32) + (h * HA + i) * 16 + frag_row, ks * 4 + frag_grp));
+                }
+            };
+            auto load_b = [&](int stage, int ks, bf16x8_t (&fb)[TN16]) {
+                const char* b_base = smem + stage * STAGE + (TNF ? 2 * 1024 : HALF);
+#pragma unroll
+                for (int j = 0; j < TN16; ++j) {
+                    if constexpr (TNF) fb[j] = read_tr(b_base, wn * TN16 + j);
+                    else fb[j] = *reinterpret_cast<const bf16x8_t*>(b_base + off64(wn * (TN * 32) + j * 16 + frag_row, ks * 4 + frag_grp));
+                }
+            };
+            // One half step: HA x TN16 MFMAs on row units h*HA.., with transfers [s0, s0 + cnt) of K tile `tile` handed
+            // out evenly between them.  Operands swapped on purpose: the accumulator block is C^T (rows = n, columns =
+            // m), so a lane holds 4 CONSECUTIVE n per block and the epilogue stages with 16-byte writes.
+            auto mma_dma = [&](int h, const bf16x8_t (&fa)[HA], const bf16x8_t (&fb)[TN16], int tile, int stage, int s0, int cnt) {
+                int done = 0;
+#pragma unroll
+                for (int i = 0; i < HA; ++i)
+#pragma unroll
+                    for (int jj = 0; jj < TN16; ++jj) {
+                        // boustrophedon order: consecutive MFMAs share one operand and the other changes to its neighbour
+                        // (measured: about 2 % more sustained MFMA rate at the power limit than row-major order)
+                        const int j = (i & 1) ? TN16 - 1 - jj : jj;
+                        const int q = i * TN16 + jj;
+#ifdef X_QPOS
+                        if (done < cnt && q == (2 * done + 1) * (HA * TN16) / (2 * cnt)) {
+#else
+                        if (done < cnt && q == done * (HA * TN16) / cnt) {
+#endif
+                            __builtin_amdgcn_sched_barrier(0);
+                            issue_one(tile, stage, s0 + done);
+                            __builtin_amdgcn_sched_barrier(0);
+                            ++done;
+                        }
+                        acc[h * HA + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[h * HA + i][j], 0, 0, 0);
+                    }
+            };
+            // Software pipeline: the fragments of the next half step are read from LDS while the MFMAs of the current
+            // one run, ACROSS the tile boundary too, so that no wavefront waits on LDS latency right after the barrier
+            // (all 8 wavefronts leave it together, so nobody would be left to cover for the others).
+            bf16x8_t fax[HA], fay[HA], fbx[TN16], fby[TN16];
+            // transfers per K tile and wavefront: NVM instructions, handed out in NTR groups (TN: one, NT: A part, B part)
+            constexpr int NVM = 2 * LPW, NTR = TNF ? 1 : 2;
+            if constexpr (TNF) {
+                // one 32-deep k step per tile, two half steps; the transfers of tile tl+3 go out in the first one, before the
+                // barrier of iteration tl
+                issue(t_begin, 0);
+                issue(t_begin + 1, 1);
+                issue(t_begin + 2, 2);
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * NVM));         // tile t_begin: at most the two newest tiles outstanding
+                __builtin_amdgcn_s_barrier();
+                load_b(0, 0, fbx);
+                load_a(0, 0, 0, fax);
+                auto tn_iter = [&](int tl, bf16x8_t (&fb_cur)[TN16], bf16x8_t (&fb_next)[TN16]) {
+                    const int st_ = (tl - t_begin) & (NS - 1);
+                    // stage (tl-1)%4 is free: every wavefront finished reading it before the barrier it has passed last
+                    load_a(st_, 0, 1, fay);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma_dma(0, fax, fb_cur, tl + 3, (st_ + 3) & (NS - 1), 0, 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    // tile tl+1: this wavefront's part has landed (tile tl+2 and the new transfers outstanding), its LDS
+                    // reads are done ...
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * NVM) & 0xF0FF);        // vmcnt(2 NVM) lgkmcnt(0)
+                    __builtin_amdgcn_s_barrier();                       // ... and everyone's
+                    load_b((st_ + 1) & (NS - 1), 0, fb_next);           // past the last tile: a stale but valid stage, unused
+                    load_a((st_ + 1) & (NS - 1), 0, 0, fax);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma_dma(1, fay, fb_cur, tl + 3, (st_ + 3) & (NS - 1), 1, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                };
+                int tl = t_begin;
+                for (; tl + 1 < t_end; tl += 2) {
+                    tn_iter(tl, fbx, fby);
+                    tn_iter(tl + 1, fby, fbx);
+                }
+                if (tl < t_end) tn_iter(tl, fbx, fby);
+            } else {
+                // two 64 KB stages, two 32-deep k steps = four half steps per tile, one barrier per tile.  Transfers of
+                // tile tl+1 ride on the four half steps between two barriers: NT_G0 on the one right after the barrier
+                // (the last half step of tile tl-1), then NT_G1, NT_G2, the rest
+                static_assert(NT_G0 + NT_G1 + NT_G2 <= NTR, "more transfers scheduled than a tile has");
+                if (!primed) issue(t_begin, 0);
+                if constexpr (PS) {
+                    // the tile after this one: drawn now, needed after the main loop (first tiles of a run: one per work-group)
+                    if (persistent && t == 0)
+                        next_local = (ps_wgs >> 3) + __hip_atomic_fetch_add(ps_ctr + (blockIdx.x & 7), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0) (persistent: the previous tile's stores too)
+                __builtin_amdgcn_s_barrier();
+#pragma unroll
+                for (int s_ = 0; s_ < NT_G0; ++s_) issue_one(t_begin + 1, 1, s_);
+                load_b(0, 0, fbx);
+                load_a(0, 0, 0, fax);
+                for (int tl = t_begin; tl < t_end; ++tl) {
+                    const int st_ = (tl - t_begin) & 1;
+                    load_a(st_, 0, 1, fay);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma_dma(0, fax, fbx, tl + 1, st_ ^ 1, NT_G0, NT_G1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_b(st_, 1, fby);
+                    load_a(st_, 1, 0, fax);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma_dma(1, fay, fbx, tl + 1, st_ ^ 1, NT_G0 + NT_G1, NT_G2);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_a(st_, 1, 1, fay);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma_dma(0, fax, fby, tl + 1, st_ ^ 1, NT_G0 + NT_G1 + NT_G2, NTR - NT_G0 - NT_G1 - NT_G2);
+                    __builtin_amdgcn_sched_barrier(0);
+                    __builtin_amdgcn_s_waitcnt(0x0070);                 // vmcnt(0) lgkmcnt(0): tile tl+1 landed, reads of tile tl done
+                    __builtin_amdgcn_s_barrier();
+                    // this stage is free from here on: tile tl+2 starts to arrive in it
+                    load_b(st_ ^ 1, 0, fbx);                            // past the last tile: a reloaded copy of it, unused
+                    load_a(st_ ^ 1, 0, 0, fax);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma_dma(1, fay, fby, tl + 2, st_, 0, NT_G0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            // drain the redundant tail transfers before LDS is reused by the epilogue (explicit: the compiler does not
+            // see transfers issued by lds_dma16)
+            __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0) lgkmcnt(0)
+            if constexpr (PS) {
+                if (persistent && t == 0) *reinterpret_cast<volatile int*>(smem + PS_SLOT) = next_local;
+            }
+            __builtin_amdgcn_s_barrier();
+        }
+        int next_logical = -1;
+        if constexpr (PS) {
+            if (persistent) {
+                const int nl = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(smem + PS_SLOT));
+                if (nl < run_cnt) {
+                    // the next tile's first K tile goes out before this tile's epilogue: stage 0 is free, the staging block
+                    // lies above it
+                    next_logical = run_start + nl;
+                    set_tile(next_logical);
+                    const uint32_t lds0 = lds_address(smem);
+                    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#pragma unroll
+                    for (int s_ = 0; s_ < 2; ++s_) {
+                        const uint32_t dst_g = lds0 + (s_ ? HALF : 0) + wave_u * (LPW * 1024);
+                        if (s_) lds_dma16_group<LPW>(dma_group_base<LPW>(pb + t_begin * (long long)(DK * 2)), offBg, dst_g);
+                        else lds_dma16_group<LPW>(dma_group_base<LPW>(pa + t_begin * (long long)(DK * 2)), offAg, dst_g);
+                    }
+                    primed = true;
                 }
             }
         }
-    }
-    if constexpr (EPI == DS_EPI_DGELU || EPI == DS_EPI_MULR) {
-        if (direct && p.colsum) {
-            // lanes l, l + LPR, l + 2 LPR, ... hold the same columns: fold them, then one row of partial sums per
-            // (tile row, wavefront row), written whether or not the wavefront had a valid row
+
+        auto epilogue = [&]() {
+        // ---- epilogue through LDS: per wavefront a [32][STG_LD] fp32 staging block
+        float* stage = reinterpret_cast<float*>(smem + STG_OFF) + wave * (32 * STG_LD);
+        constexpr int LPR = TN * 4;                    // lanes per staged row (8 columns each)
+        const int rd_row = lane / LPR, rd_col = (lane % LPR) * 8;
+        constexpr int NPSS = 32 / (64 / LPR);          // staged rows each lane finishes per pass
+        const bool direct = !tail && splits == 1;      // this work-group applies the epilogue itself
+        // what the epilogue reads from memory, for every row this lane will finish: all in flight before the first pass
+        // (one pass ahead only for the two-operand gated form, which would not fit in registers otherwise)
+        constexpr bool PRE_ALL = EPI != DS_EPI_DGATE;
+        EpiPre<bf16_t> pre[TM][NPSS];
+        auto prefetch_pass = [&](int i) {
 #pragma unroll
-            for (int o = LPR; o < 64; o <<= 1)
+            for (int pss = 0; pss < NPSS; ++pss) {
+                const int m = em0 + wm * (TM * 32) + i * 32 + pss * (64 / LPR) + rd_row;
+                if (m < M) epilogue_prefetch<bf16_t, EPI>(m, en0 + wn * (TN * 32) + rd_col, N, p, pre[i][pss]);
+            }
+        };
+        if (epilogue_reads<EPI>() && direct && PRE_ALL) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) csum[j] += __shfl_xor(csum[j], o, 64);
-            if (lane < LPR)
-                Vec8<float>::store(p.colsum + (size_t)(tile_m * WM + wm) * N + n0 + wn * (TN * 32) + rd_col, csum);
+            for (int i = 0; i < TM; ++i) prefetch_pass(i);
+        }
+        if constexpr (EPI == DS_EPI_NONE) {
+            // Plain output (+ bias): nothing is computed after the transposition, so the bias is added and the value
+            // rounded to bf16 BEFORE staging: half the LDS traffic of the fp32 staging below, which bounds the epilogue.
+            if (direct) {
+                bf16_t* stage_h = reinterpret_cast<bf16_t*>(stage);
+                constexpr int LD_H = TN * 32 + 8;                       // bf16 row stride (144 bytes: 8-byte writes of 16 rows spread over the banks)
+                float bias4[TN16][4];
+#pragma unroll
+                for (int j = 0; j < TN16; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        bias4[j][e] = p.bias ? (float)reinterpret_cast<const bf16_t*>(p.bias)[en0 + wn * (TN * 32) + j * 16 + 4 * (lane >> 4) + e] : 0.f;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    wave_lds_sync();
+#pragma unroll
+                    for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                        for (int j = 0; j < TN16; ++j) {
+                            typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+                            const f32x4_t a4 = acc[2 * i + i2][j];
+                            const bf16x4_t h4 = {(bf16_t)(a4[0] + bias4[j][0]), (bf16_t)(a4[1] + bias4[j][1]),
+                                                 (bf16_t)(a4[2] + bias4[j][2]), (bf16_t)(a4[3] + bias4[j][3])};
+                            *reinterpret_cast<bf16x4_t*>(stage_h + (i2 * 16 + (lane & 15)) * LD_H + j * 16 + 4 * (lane >> 4)) = h4;
+                        }
+                    wave_lds_sync();
+#pragma unroll
+                    for (int pss = 0; pss < NPSS; ++pss) {
+                        const int row = pss * (64 / LPR) + rd_row;
+                        const int m = em0 + wm * (TM * 32) + i * 32 + row;
+                        const int n = en0 + wn * (TN * 32) + rd_col;
+                        if (m < M) {
+                            const bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(stage_h + row * LD_H + rd_col);
+                            __builtin_nontemporal_store(v, reinterpret_cast<bf16x8_t*>(C + (size_t)m * N + n));
+                        }
+                    }
+                }
+                return;
+            }
+        }
+        // column sums of what this lane writes (DGELU: the bias gradient of the layer below comes out of this kernel
+        // instead of a pass over the stored tensor); every lane finishes TM * NPSS rows of the same 8 columns
+        float csum[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) csum[j] = 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (epilogue_reads<EPI>() && direct && !PRE_ALL) prefetch_pass(i);
+            wave_lds_sync();            // the staging block is private to the wavefront: no work-group barrier (which would
+                                        // also wait for the global stores of the previous pass to be acknowledged)
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                for (int j = 0; j < TN16; ++j) {    // lane = row m (lane%16 of block 2i+i2); its 4 registers = columns 4*(lane/16) + 0..3
+                    const f32x4_t a4 = acc[2 * i + i2][j];
+                    *reinterpret_cast<float4*>(stage + (i2 * 16 + (lane & 15)) * STG_LD + j * 16 + 4 * (lane >> 4)) =
+                        make_float4(a4[0], a4[1], a4[2], a4[3]);
+                }
+            wave_lds_sync();
+#pragma unroll
+            for (int pss = 0; pss < NPSS; ++pss) {
+                const int row = pss * (64 / LPR) + rd_row;
+                const int m = em0 + wm * (TM * 32) + i * 32 + row;
+                const int n = en0 + wn * (TN * 32) + rd_col;
+                if (m < M) {
+                    float v[8];
+                    const float4 x0 = *reinterpret_cast<const float4*>(stage + row * STG_LD + rd_col);
+                    const float4 x1 = *reinterpret_cast<const float4*>(stage + row * STG_LD + rd_col + 4);
+                    v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+                    if (tail) {
+                        Vec8<float>::store(split_ws + ((size_t)((elogical - n_main) * tail_splits + split) * BM + (m - em0)) * BN + (n - en0), v);
+                    } else if (splits > 1) {
+                        Vec8<float>::store(split_ws + ((size_t)split * M + m) * N + n, v);
+                    } else if (epilogue_reads<EPI>()) {
+                        epilogue8<bf16_t, EPI>(m, n, N, v, C, p, &pre[i][pss]);
+                        if constexpr (EPI == DS_EPI_DGELU || EPI == DS_EPI_MULR) {
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) csum[j] += v[j];
+                        }
+                    } else {
+                        epilogue8<bf16_t, EPI>(m, n, N, v, C, p);
+                    }
+                }
+            }
+        }
+        if constexpr (EPI == DS_EPI_DGELU || EPI == DS_EPI_MULR) {
+            if (direct && p.colsum) {
+                // lanes l, l + LPR, l + 2 LPR, ... hold the same columns: fold them, then one row of partial sums per
+                // (tile row, wavefront row), written whether or not the wavefront had a valid row
+#pragma unroll
+                for (int o = LPR; o < 64; o <<= 1)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) csum[j] += __shfl_xor(csum[j], o, 64);
+                if (lane < LPR)
+                    Vec8<float>::store(p.colsum + (size_t)(etile_m * WM + wm) * N + en0 + wn * (TN * 32) + rd_col, csum);
+            }
+        }
+        };
+        epilogue();
+        if (next_logical < 0) break;
+        logical = next_logical;
+    }   // for (;;): persistent work-groups go on with their next tile
+    if constexpr (PS) {
+        if (persistent && t == 0) {
+            // every persistent work-group ends with a draw beyond its run; the last one to finish clears the counters
+            const int done = __hip_atomic_fetch_add(ps_ctr + 8, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (done == ps_wgs - 1) {
+#pragma unroll
+                for (int i = 0; i < 9; ++i) ps_ctr[i] = 0;
+            }
         }
     }
 }
@@ -790,12 +869,35 @@ static int choose_splits(int tiles, int nt, int M, int N, size_t split_ws_floats
     return best;
 }
 
+// Tile counters of the persistent form: 64 slots of [8 per-XCD counters, 1 count of finished work-groups], all zero
+// between launches (the last work-group of a launch clears its slot).  Launches take the slots in turn, so two
+// launches can only share one if more than 64 are in flight on a device at the same time.
+constexpr int PS_SLOTS = 64;
+__device__ int g_ps_ctr[PS_SLOTS][16];
+constexpr bool NT_PERSISTENT = true;
+static int* ps_counters() {
+    static std::mutex mu;
+    static int* base[64] = {};
+    static std::atomic<unsigned> next{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!base[dev]) {
+            void* ptr = nullptr;
+            if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_ps_ctr)) != hipSuccess) return nullptr;
+            base[dev] = static_cast<int*>(ptr);
+        }
+    }
+    return base[dev] + 16 * (next.fetch_add(1) % PS_SLOTS);
+}
+
 template <int EPI, bool TNF>
 ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, const GemmEpi& p, float* split_ws,
                     size_t split_ws_floats, hipStream_t st) {
     static bool attr_set = false;
     constexpr int WM = NT_WM, WN = NT_WN;
-    auto kern = gemm_bf16_nt_kernel<EPI, WM, WN, TNF>;
+    auto kern = gemm_bf16_nt_kernel<EPI, WM, WN, TNF, false>;
     constexpr int stg = WM * WN * 32 * ((256 / WN) + 4) * 4;
     const int smem = NT_NS * NT_STAGE > stg ? NT_NS * NT_STAGE : stg;
     if (!attr_set) {
@@ -826,8 +928,31 @@ ds_status launch_nt(int M, int N, int K, const void* A, const void* B, void* C, 
         }
     }
     const int total = splits > 1 ? tiles * splits : n_main + (tiles - n_main) * tail_splits;
-    hipLaunchKernelGGL(kern, dim3(total), dim3(WM * WN * 64), smem, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C,
-                       tiles_m, tiles_n, splits, n_main, tail_splits, split_ws, p);
+    bool launched = false;
+    if constexpr (!TNF && NT_PERSISTENT) {
+        // persistent form: one resident work-group per compute unit for the unsplit tiles, when each has several to do
+        const int n_cu = cu_count();
+        if (splits == 1 && n_cu % 8 == 0 && n_main >= 2 * n_cu) {
+            static bool ps_attr_set = false;
+            auto kern_ps = gemm_bf16_nt_kernel<EPI, WM, WN, false, true>;
+            constexpr int smem_ps = 65536 + stg + 64;              // stage 0 | epilogue staging | hand-over word
+            static_assert(smem_ps >= NT_NS * NT_STAGE && smem_ps <= 160 * 1024, "LDS of the persistent form");
+            if (!ps_attr_set) {
+                DS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern_ps), hipFuncAttributeMaxDynamicSharedMemorySize, smem_ps));
+                ps_attr_set = true;
+            }
+            int* ctr = ps_counters();
+            if (ctr) {
+                hipLaunchKernelGGL(kern_ps, dim3(n_cu + (tiles - n_main) * tail_splits), dim3(WM * WN * 64), smem_ps, st, M, N, K,
+                                   (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C, tiles_m, tiles_n, splits, n_main, tail_splits,
+                                   split_ws, p, n_cu, ctr);
+                launched = true;
+            }
+        }
+    }
+    if (!launched)
+        hipLaunchKernelGGL(kern, dim3(total), dim3(WM * WN * 64), smem, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, (bf16_t*)C,
+                           tiles_m, tiles_n, splits, n_main, tail_splits, split_ws, p, 0, (int*)nullptr);
     DS_LAUNCH_CHECK();
     if (splits > 1) {
         long long items = (long long)M * (N / 8);
