@@ -92,6 +92,13 @@ struct ds_stage {
          *dx1 = nullptr, *dx2 = nullptr, *d_o = nullptr, *dqkv = nullptr, *dqc = nullptr, *dkvc = nullptr, *de = nullptr,
          *deB = nullptr;
     float *delta = nullptr, *partial = nullptr, *split_ws = nullptr;
+    // Bias-gradient column sums (decoder-only stage) run on a stream of their own beside the GEMMs that follow their
+    // producer: nothing on the main stream reads what they write, so they only have to be back before the tensor they
+    // read is overwritten (joined at the end of every layer's backward pass).  Same priority as the caller's stream.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    float* partial_side = nullptr;     // their partial sums (the main stream's `partial` belongs to the norm kernels)
+    bool side_pending = false;
     float* colsum_rows = nullptr;      // partial column sums written by the GELU-backward GEMM epilogue (decoder-only stage)
     // scratch of the matrix-core attention kernels (work lists, backward statistics): one per kind of attention the
     // model runs (decoder-only: causal self-attention; encoder-decoder: encoder self-, decoder self-, cross-attention)
@@ -200,6 +207,7 @@ void carve(ds_stage* s) {
     }
     const size_t partial_floats = std::max<size_t>((size_t)ds_norm_bwd_scratch_floats(1, (int)d), (size_t)2048 * 1024);
     s->partial = f32(partial_floats);
+    s->partial_side = c.model == DS_MODEL_GPT ? f32((size_t)2048 * 1024) : nullptr;
     s->colsum_rows = (c.model == DS_MODEL_GPT && s->nt_mode) ? f32(gemm_colsum_rows((int32_t)R) * F) : nullptr;
     s->split_ws_floats = 4 * std::max(d * 3 * d, d * F);
     s->split_ws = f32(s->split_ws_floats);
@@ -334,6 +342,25 @@ struct Ops {
     ds_status colsum(const Stream& sm, int n, const void* x, void* out) {
         s->launches += 2;
         return timed(s, DS_PROF_COLSUM, st, [&] { return ds_colsum(dt, sm.R, n, x, (float*)out, s->partial, accumulate, st); });
+    }
+    // The same on the side stream: starts once everything enqueued so far on the main stream is done, runs beside
+    // what is enqueued after it.  x must stay as it is, and out untouched, until join_side().
+    ds_status colsum_side(const Stream& sm, int n, const void* x, void* out) {
+        if (!s->side) return colsum(sm, n, x, out);
+        s->launches += 2;
+        DS_HIP_CHECK(hipEventRecord(s->ev_fork, st));
+        DS_HIP_CHECK(hipStreamWaitEvent(s->side, s->ev_fork, 0));
+        s->side_pending = true;
+        return timed(s, DS_PROF_COLSUM, s->side, [&] {
+            return ds_colsum(dt, sm.R, n, x, (float*)out, s->partial_side, accumulate, s->side);
+        });
+    }
+    ds_status join_side() {
+        if (!s->side_pending) return DS_OK;
+        DS_HIP_CHECK(hipEventRecord(s->ev_join, s->side));
+        DS_HIP_CHECK(hipStreamWaitEvent(st, s->ev_join, 0));
+        s->side_pending = false;
+        return DS_OK;
     }
     ds_status norm_fwd(const Stream& sm, int rms, const void* x, const void* g, const void* b, void* y, float* stats) {
         s->launches++;
@@ -486,21 +513,23 @@ ds_status gpt_fwd_bwd(ds_stage* s, const ds_gpt_layer* w, const ds_stage_io* io,
         // the shared buffers still hold the last layer's forward; every other layer's is run again
         if (recompute && l != L - 1) DS_TRY(layer_fwd(l, xl_in, nullptr));
         // MLP
+        DS_TRY(op.colsum_side(sm, d, dy, g[l].b_2));        // (each column sum right behind its producer, beside the next GEMM)
         DS_TRY(op.wgrad(sm, F, d, b.a, dy, g[l].w_2));
-        DS_TRY(op.colsum(sm, d, dy, g[l].b_2));
         DS_TRY(op.dgrad_gelu_bias(sm, F, d, dy, w[l].w_2, s->dz, b.z, g[l].b_1));
         DS_TRY(op.wgrad(sm, d, F, b.u2, s->dz, g[l].w_1));
         DS_TRY(op.dgrad(sm, d, F, s->dz, w[l].w_1, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr));
         DS_TRY(op.norm_bwd(sm, 0, s->du, b.x1, w[l].ln2_g, b.stats2, dy, s->dx1, g[l].ln2_g, g[l].ln2_b));
         // attention
+        DS_TRY(op.colsum_side(sm, d, s->dx1, g[l].b_o));
         DS_TRY(op.wgrad(sm, d, d, b.o, s->dx1, g[l].w_o));
-        DS_TRY(op.colsum(sm, d, s->dx1, g[l].b_o));
         DS_TRY(op.dgrad(sm, d, d, s->dx1, w[l].w_o, s->d_o, DS_EPI_NONE, nullptr, nullptr, nullptr));
         DS_TRY(op.self_bwd(sm, 1, b.qkv, b.o, s->d_o, b.lse, s->dqkv));
+        DS_TRY(op.colsum_side(sm, 3 * d, s->dqkv, g[l].b_qkv));
         DS_TRY(op.wgrad(sm, d, 3 * d, b.u1, s->dqkv, g[l].w_qkv));
-        DS_TRY(op.colsum(sm, 3 * d, s->dqkv, g[l].b_qkv));
         DS_TRY(op.dgrad(sm, d, 3 * d, s->dqkv, w[l].w_qkv, s->du, DS_EPI_NONE, nullptr, nullptr, nullptr));
         DS_TRY(op.norm_bwd(sm, 0, s->du, xl_in, w[l].ln1_g, b.stats1, s->dx1, dx_in, g[l].ln1_g, g[l].ln1_b));
+        // the next layer overwrites dx1 and dqkv, which the column sums on the side stream may still be reading
+        DS_TRY(op.join_side());
         dy = dx_in;
         flip ^= 1;
     }
@@ -773,8 +802,13 @@ extern "C" ds_status ds_stage_create(const ds_stage_config* cfg, ds_stage** out)
     s->arena.base = (char*)s->ws;
     carve(s);
     const size_t ints = (size_t)cfg->max_rows + (size_t)cfg->max_rows_tgt + 4 * (size_t)cfg->max_seqs;
-    if (hipHostMalloc((void**)&s->h_tables, ints * 4, hipHostMallocDefault) != hipSuccess ||
-        hipEventCreateWithFlags(&s->upload_done, hipEventDisableTiming) != hipSuccess) {
+    bool ok = hipHostMalloc((void**)&s->h_tables, ints * 4, hipHostMallocDefault) == hipSuccess &&
+              hipEventCreateWithFlags(&s->upload_done, hipEventDisableTiming) == hipSuccess;
+    if (ok && cfg->model == DS_MODEL_GPT)
+        ok = hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking) == hipSuccess &&
+             hipEventCreateWithFlags(&s->ev_fork, hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&s->ev_join, hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
         (void)hipGetLastError();
         ds_stage_destroy(s);
         return DS_EHIP;
@@ -787,6 +821,9 @@ extern "C" void ds_stage_destroy(ds_stage* s) {
     if (!s) return;
     for (hipEvent_t e : s->ev_pool) (void)hipEventDestroy(e);
     if (s->upload_done) (void)hipEventDestroy(s->upload_done);
+    if (s->ev_fork) (void)hipEventDestroy(s->ev_fork);
+    if (s->ev_join) (void)hipEventDestroy(s->ev_join);
+    if (s->side) (void)hipStreamDestroy(s->side);
     if (s->h_tables) (void)hipHostFree(s->h_tables);
     if (s->ws) (void)hipFree(s->ws);
     delete s;
