@@ -12,7 +12,8 @@ launch).  Prints ONE JSON line on stdout; everything else goes to stderr.
 The headline (value, ms_per_step, roofline) is the LARGEST single-GPU workload, gpt_4096_longtail_bf16,
 timed over exactly K steps with the library's per-group events switched off; the per-group breakdown
 and the GEMM family's launch durations (HIP events the library records on the launch stream around
-every kernel group) come from a second, shorter loop.  The same record carries, under "configs", the
+every kernel group) come from a second, shorter loop; the bias-gradient column sums run on a side stream
+beside the GEMMs, so the groups of that breakdown overlap and add up to more than the step.  The same record carries, under "configs", the
 other workloads (gpt_2048_bf16, t5_1024_bf16) and the layout comparison on gpt_2048_bf16's batch
 (fixed padding, first-fit packing, token-based micro-batching, DP plan; plus the dense-attention cost
 of packed rows as context), each with ms/step, tokens/s, useful and executed MFMA utilisation and
