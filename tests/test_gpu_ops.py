@@ -409,3 +409,45 @@ def test_gemm_weight_gradient_split_over_the_contraction(M, N, K):
     ds.ds_gemm(dX, ddY, plain, M, N, K, trans_a=True, epilogue=ds.DS_EPI_ACC32, accumulate=False)
     torch.cuda.synchronize()
     assert both_err(to_np(plain), ref) <= 1e-5
+
+
+@pytest.mark.parametrize("use_ws", [False, True])
+def test_gemm_nt_persistent_form(use_ws):
+    """A launch with at least two unsplit tiles per compute unit takes the persistent form of the NT kernel (resident
+    work-groups drawing tiles from per-XCD counters; with a workspace the last tiles are split pieces behind them):
+    every tile against the reference, ragged M, several epilogues; again on another stream and a third time, bit for
+    bit the same (the counters a launch leaves behind are those the next one starts from)."""
+    rng = np.random.default_rng(21)
+    M, N, K = 256 * 40 + 57, 3328, 512                     # 41 x 13 = 533 tiles
+    A, B = _rnd(rng, (M, K), BF), _rnd(rng, (N, K), BF, 0.1)
+    bias, R = _rnd(rng, (N,), BF), _rnd(rng, (M, N), BF)
+    valid = np.where(rng.random(M) < 0.9, 1, -1).astype(np.int32)
+    acc = A.astype(np.float64) @ B.astype(np.float64).T
+    dA, dB, db, dR = (to_dev(x, BF) for x in (A, B, bias, R))
+    dvalid = torch.from_numpy(valid).to(DEV)
+    ws = _ws(64 * 256 * 256) if use_ws else None
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    tol = 6e-3
+
+    def run(epi, stream=None, **kw):
+        c = torch.zeros((M, N), dtype=BF, device=DEV)
+        c2 = torch.zeros((M, N), dtype=BF, device=DEV)
+        ds.ds_gemm(dA, dB, c, M, N, K, trans_b=True, epilogue=epi, C2=c2, workspace=ws, stream=stream, **kw)
+        torch.cuda.synchronize()
+        return to_np(c), to_np(c2)
+
+    for epi, kw, want, want2 in [
+            (ds.DS_EPI_NONE, dict(bias=db), acc + bias, None),
+            (ds.DS_EPI_RESID, dict(bias=db, R=dR, row_valid=dvalid), (acc + bias + R) * (valid[:, None] >= 0), None),
+            (ds.DS_EPI_GELU_D, dict(bias=db), ost.gelu_grad(acc + bias), ost.gelu(acc + bias)),
+            (ds.DS_EPI_MULR, dict(R=dR), acc * R, None)]:
+        c, c2 = run(epi, **kw)
+        assert both_err(c, want) <= tol
+        if want2 is not None:
+            assert both_err(c2, want2) <= tol
+        for stream in (side.cuda_stream, None):
+            d, d2 = run(epi, stream=stream, **kw)
+            assert np.array_equal(c, d)
+            if want2 is not None:
+                assert np.array_equal(c2, d2)
