@@ -174,6 +174,33 @@ def cpu_baseline(cfg, lens, seed, budget_s=6.0):
             "sample": "%d seeded sequences of the %s batch, %d tokens, float64 numpy, %.1f s" % (len(pick), cfg["name"], tok, dt)}
 
 
+def mfma_loop_tflops(seed):
+    """What the matrix cores sustain with nothing else going on (the library's register-only MFMA loop at the GEMM
+    kernel's occupancy and register tile), on operands distributed like the workload's and on zeros: the chip runs at its
+    power limit, so the published peak is reachable only on operands that toggle nothing."""
+    import torch
+    from paper_2311_10418_amd import binding as ds
+    n_groups, iters = 1024, 2000
+    sink = torch.empty(n_groups * 512, dtype=torch.float32, device="cuda:0")
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(seed + 77)
+    out = {}
+    for name in ("random_operands", "zero_operands"):
+        ops = torch.randn(24 * 512 * 8, device="cuda:0", generator=gen).to(torch.bfloat16)
+        if name == "zero_operands":
+            ops.zero_()
+        for _ in range(3):
+            ds.ds_mfma_probe(ops, sink, n_groups, iters)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            ds.ds_mfma_probe(ops, sink, n_groups, iters)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = 5.0 * n_groups * 8 * iters * 64 * 2 * 16 * 16 * 32 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return out
+
+
 def git_head():
     try:
         return subprocess.run(["git", "-C", ROOT, "rev-parse", "--short=12", "HEAD"], capture_output=True, text=True, timeout=10).stdout.strip() or None
@@ -420,6 +447,13 @@ def main():
     }
     if "sequential_ms" in head:
         result["config"]["sequential_ms"] = head["sequential_ms"]
+    if bf16:
+        # context beside `peak` (which stays the published figure): the matrix cores' own sustained rate on this machine
+        loop = mfma_loop_tflops(args.seed)
+        result["roofline"]["mfma_loop_tflops"] = loop
+        if g["achieved_tflops"]:
+            result["roofline"]["frac_of_mfma_loop"] = g["achieved_tflops"] / loop["random_operands"]
+        log("register-only MFMA loop: %.0f TFLOP/s on random operands, %.0f on zeros" % (loop["random_operands"], loop["zero_operands"]))
 
     if is_default and not args.no_side:
         side = {}

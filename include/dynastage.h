@@ -546,6 +546,17 @@ ds_status ds_colsum(int32_t dtype, int32_t rows, int32_t n, const void* x, float
 ds_status ds_colsum_static(int32_t dtype, int32_t rows, int32_t n, const void* x, float* out, int32_t accumulate,
                            void* hip_stream);
 
+/* Measurement aid (no part of the method): the rate the matrix cores sustain with nothing else going on, the yardstick
+ * bench.py prints beside the published peak.  Launches ONE kernel of n_groups work-groups (512 threads each, one per
+ * compute unit at a time) on hip_stream; every wavefront issues iters x 64 v_mfma_f32_16x16x32_bf16 on the GEMM
+ * kernel's register tile, operands read once.  The caller times it:
+ *     flops = n_groups x 8 wavefronts x iters x 64 MFMAs x 2 x 16 x 16 x 32.
+ * operands: DEVICE, 24 x 512 x 8 bf16 values (196 608 bytes, 16-byte aligned), read only: fragment f of thread t is
+ * the 8 values at (f x 512 + t) x 8; what they hold decides the power the chip draws and with it the result.
+ * sink: DEVICE, n_groups x 512 floats, written (one sum per thread, so that the loop cannot be optimised away).
+ * Allocates nothing.  Errors: DS_EINVAL (null, alignment, counts <= 0), DS_EHIP. */
+ds_status ds_mfma_probe(const void* operands, float* sink, int32_t n_groups, int32_t iters, void* hip_stream);
+
 /* Library identification: returns a static HOST string "dynastage <version> gfx950". */
 const char* ds_version(void);
 

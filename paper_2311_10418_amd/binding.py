@@ -29,7 +29,7 @@ EXPORTS = ["dp_plan", "dp_plan_sampled", "dp_plan_replicas", "ds_plan_recompute"
            "ds_stage_create", "ds_stage_destroy", "ds_stage_workspace_bytes", "ds_stage_workspace_need", "stage_fwd_bwd",
            "ds_stage_last_launch_count", "ds_stage_weights_unchanged", "ds_stage_profile_enable", "ds_stage_profile_read", "ds_pack", "ds_unpack", "ds_gemm", "ds_gemm_ws", "ds_attention_fwd",
            "ds_attention_bwd", "ds_attention_scratch_bytes", "ds_norm_fwd", "ds_norm_bwd", "ds_norm_bwd_scratch_floats", "ds_colsum", "ds_colsum_static",
-           "ds_version"]
+           "ds_mfma_probe", "ds_version"]
 
 
 class DsError(RuntimeError):
@@ -540,6 +540,11 @@ def ds_norm_bwd(dy, x, g, stats, resid, dx, dg, db, partial, rms=False, accumula
                            _dp(g), _dp(stats), _dp(resid), _dp(dx), _dp(dg), _dp(db), _dp(partial),
                            C.c_int32(int(accumulate)), _stream(stream))
     _check(rc, "ds_norm_bwd")
+
+
+def ds_mfma_probe(operands, sink, n_groups, iters, stream=None):
+    rc = lib().ds_mfma_probe(_dp(operands), _dp(sink), C.c_int32(n_groups), C.c_int32(iters), _stream(stream))
+    _check(rc, "ds_mfma_probe")
 
 
 def ds_colsum(x, out, partial, accumulate=False, stream=None):

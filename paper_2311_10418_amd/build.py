@@ -13,7 +13,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdynastage.so")
 
-HIP_SOURCES = ["elementwise.hip", "gemm.hip", "attention_generic.hip", "attention_mfma.hip", "attention_api.hip", "stage.hip"]
+HIP_SOURCES = ["elementwise.hip", "gemm.hip", "attention_generic.hip", "attention_mfma.hip", "attention_api.hip", "stage.hip", "probe.hip"]
 CPP_SOURCES = ["planner.cpp", "schedule.cpp", "recompute.cpp"]
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",

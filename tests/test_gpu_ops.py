@@ -451,3 +451,25 @@ def test_gemm_nt_persistent_form(use_ws):
             assert np.array_equal(c, d)
             if want2 is not None:
                 assert np.array_equal(c2, d2)
+
+
+def test_mfma_probe_runs_and_is_deterministic():
+    """The measurement aid: the loop really runs (sums differ from zero on random operands, are zero on zeros) and
+    gives the same sums every time."""
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    ops = torch.randn(24 * 512 * 8, device=DEV, generator=gen).to(BF)
+    sink = torch.zeros(2 * 512, dtype=F32, device=DEV)
+    ds.ds_mfma_probe(ops, sink, 2, 3)
+    torch.cuda.synchronize()
+    first = to_np(sink)
+    assert np.all(np.isfinite(first)) and np.count_nonzero(first) > 900
+    assert np.array_equal(first[:512], first[512:])             # every work-group computes the same
+    ds.ds_mfma_probe(ops, sink, 2, 3)
+    torch.cuda.synchronize()
+    assert np.array_equal(first, to_np(sink))
+    ds.ds_mfma_probe(torch.zeros_like(ops), sink, 2, 3)
+    torch.cuda.synchronize()
+    assert np.count_nonzero(to_np(sink)) == 0
+    with pytest.raises(ds.DsError):
+        ds.ds_mfma_probe(ops, sink, 0, 3)
