@@ -191,3 +191,36 @@ def test_stage_call_can_be_captured_in_a_graph_and_replays_identically():
         torch.cuda.synchronize()
     del graph
     stage.close()
+
+
+def test_back_to_back_calls_on_a_caller_stream_without_host_synchronisation():
+    """The bias-gradient column sums run on a stream of the stage's own and are joined before a call returns control of
+    the caller's stream: calls enqueued back to back on a stream of the caller's, with nothing in between, leave the same
+    bits as one call followed by a synchronisation, and buffers the caller overwrites right behind a call are not read
+    late."""
+    cfg, lens, params, xs, dys = _small_case(True, n_seq=12)
+    lo = ds.dp_plan(lens, ds.make_cost_model(fixed=2_000_000), cfg["cap"], cfg["num_stages"])
+    from helpers import params_to_dev, stream_from_seqs, zero_grads_like
+    d = cfg["d_model"]
+    stage = ds.Stage(ds.DS_MODEL_GPT, ds.DS_DTYPE_BF16, cfg["n_layers"], d, cfg["n_heads"], cfg["d_ff"],
+                     max_rows=lo.total_rows, max_seqs=lo.n_seq)
+    w = params_to_dev(params, torch.bfloat16)
+    grads = zero_grads_like(w)
+    x = stream_from_seqs(xs, lo, d, torch.bfloat16, 0.0)
+    dy = stream_from_seqs(dys, lo, d, torch.bfloat16, 0.0)
+    out, dx = torch.empty_like(x), torch.empty_like(x)
+    ds.stage_fwd_bwd(stage, lo, w, x, dy, out, dx, grads, accumulate=False)
+    torch.cuda.synchronize()
+    ref = [out.clone(), dx.clone()] + [g[k].clone() for g in grads for k in g]
+    dy_copy = dy.clone()
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        for _ in range(4):
+            ds.stage_fwd_bwd(stage, lo, w, x, dy, out, dx, grads, accumulate=False, stream=st.cuda_stream)
+            dy.fill_(float("nan"))                  # the caller reuses its gradient buffer right behind the call ...
+            dy.copy_(dy_copy)                       # ... and refills it for the next one, all in stream order
+    torch.cuda.synchronize()
+    for a, b in zip(ref, [out, dx] + [g[k] for g in grads for k in g]):
+        assert torch.equal(a, b)
+    stage.close()
